@@ -1,0 +1,271 @@
+"""ctypes front end of the CPU oracle (test infrastructure, not part of the product).
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg import this package.  It
+never imports the GPU binding.  `build()` compiles oracle/ddef_oracle.cpp with g++ into
+oracle/libddef_oracle.so; the functions below only marshal numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ddef_oracle.cpp")
+_LIB = os.path.join(_HERE, "libddef_oracle.so")
+
+# -ffp-contract=off: every fp32 operation rounds on its own (no fused multiply-add).
+CXXFLAGS = ["-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+            "-pthread"]
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", *CXXFLAGS, _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    L = C.CDLL(_LIB)
+    u32p, f32p, u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
+    vp = C.c_void_p
+    sig = {
+        "oracle_philox4x32_10": (None, [u32p, u32p, u32p]),
+        "oracle_neg2ln_uniform": (C.c_float, [C.c_uint32]),
+        "oracle_unit_circle_point": (None, [C.c_uint32, f32p, f32p]),
+        "oracle_noise_z": (C.c_float, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int]),
+        "oracle_noise_fill": (None, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64,
+                                     C.c_int, f32p]),
+        "oracle_k_from_delta": (C.c_uint64, [C.c_double, C.c_uint64]),
+        "oracle_topk": (None, [f32p, C.c_uint64, C.c_uint64, u32p, u32p, u64p]),
+        "oracle_create": (vp, [C.c_uint64, C.c_uint32, C.c_uint32]),
+        "oracle_destroy": (None, [vp]),
+        "oracle_set_threads": (None, [vp, C.c_int]),
+        "oracle_set_problem": (None, [vp, f32p, f32p, f32p, C.c_uint64, C.c_int, C.c_float]),
+        "oracle_set_tau": (None, [vp, C.c_uint32]),
+        "oracle_step_index": (C.c_uint64, [vp]),
+        "oracle_grad": (None, [vp]),
+        "oracle_load_grad": (None, [vp, C.c_uint32, f32p]),
+        "oracle_ef_compress": (None, [vp, C.c_double, C.c_float]),
+        "oracle_aggregate": (None, [vp]),
+        "oracle_apply_delayed": (None, [vp]),
+        "oracle_step": (None, [vp, C.c_double, C.c_float]),
+        "oracle_get_model": (None, [vp, f32p]),
+        "oracle_set_model": (None, [vp, f32p]),
+        "oracle_get_snapshot": (None, [vp, C.c_uint64, f32p]),
+        "oracle_get_error": (None, [vp, C.c_uint32, f32p]),
+        "oracle_set_error": (None, [vp, C.c_uint32, f32p]),
+        "oracle_get_grad": (None, [vp, C.c_uint32, f32p]),
+        "oracle_message_size": (C.c_uint64, [vp, C.c_uint32]),
+        "oracle_get_message": (None, [vp, C.c_uint32, u32p, f32p]),
+        "oracle_get_update": (None, [vp, f32p]),
+        "oracle_get_threshold": (None, [vp, C.c_uint32, u32p, u64p]),
+        "oracle_queue_run": (None, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_double,
+                                    C.c_float, f32p, f32p, f32p, C.c_uint64, C.c_int, C.c_float,
+                                    f32p, f32p]),
+        "oracle_phi": (C.c_double, [C.c_double, C.c_double]),
+        "oracle_delta_star": (C.c_double, [C.c_double] * 5),
+        "oracle_deco": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
+        "oracle_t_avg_closed_form": (C.c_double, [C.c_double] * 6),
+        "oracle_t_avg_recurrence": (C.c_double, [C.c_uint32] + [C.c_double] * 5 + [C.c_uint64]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _u32(a):
+    a = np.ascontiguousarray(a, dtype=np.uint32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+# ---- stateless helpers -------------------------------------------------------------
+def philox4x32_10(ctr, key):
+    c, cp = _u32(ctr)
+    k, kp = _u32(key)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(cp, kp, out.ctypes.data_as(C.POINTER(C.c_uint32)))
+    return out
+
+
+def neg2ln_uniform(w: int) -> float:
+    return float(lib().oracle_neg2ln_uniform(C.c_uint32(w)))
+
+
+def unit_circle_point(w: int):
+    c, s = C.c_float(), C.c_float()
+    lib().oracle_unit_circle_point(C.c_uint32(w), C.byref(c), C.byref(s))
+    return c.value, s.value
+
+
+def noise_z(seed, t, worker, j, kind) -> float:
+    return float(lib().oracle_noise_z(seed, t, worker, j, kind))
+
+
+def noise_fill(seed, t, worker, j0, count, kind) -> np.ndarray:
+    out = np.empty(count, dtype=np.float32)
+    lib().oracle_noise_fill(seed, t, worker, j0, count, kind, out.ctypes.data_as(C.POINTER(C.c_float)))
+    return out
+
+
+def k_from_delta(delta: float, d: int) -> int:
+    return int(lib().oracle_k_from_delta(float(delta), int(d)))
+
+
+def topk(p, k):
+    """Indices (ascending) of the top-k of p under (|v| desc, index asc); also (T, r)."""
+    p, pp = _f32(p)
+    idx = np.empty(k, dtype=np.uint32)
+    T, r = C.c_uint32(), C.c_uint64()
+    lib().oracle_topk(pp, p.shape[0], k, idx.ctypes.data_as(C.POINTER(C.c_uint32)),
+                      C.byref(T), C.byref(r))
+    return idx, T.value, r.value
+
+
+def queue_run(lam, xstar, x0, n, tau, T, delta, lr, seed, noise_kind, noise_scale, trajectory=False):
+    lam, lp = _f32(lam)
+    xstar, sp = _f32(xstar)
+    x0, xp = _f32(x0)
+    d = lam.shape[0]
+    xf = np.empty(d, dtype=np.float32)
+    traj = np.empty((T + 1, d), dtype=np.float32) if trajectory else None
+    tp = traj.ctypes.data_as(C.POINTER(C.c_float)) if trajectory else None
+    lib().oracle_queue_run(d, n, tau, T, float(delta), float(lr), lp, sp, xp, seed, noise_kind,
+                           float(noise_scale), tp, xf.ctypes.data_as(C.POINTER(C.c_float)))
+    return (xf, traj) if trajectory else xf
+
+
+def phi(delta, tau):
+    return float(lib().oracle_phi(float(delta), float(tau)))
+
+
+def delta_star(tau, v_g, a, b, t_comp):
+    return float(lib().oracle_delta_star(float(tau), float(v_g), float(a), float(b), float(t_comp)))
+
+
+def deco(v_g, a, b, t_comp):
+    tau, delta = C.c_uint32(), C.c_double()
+    rc = lib().oracle_deco(float(v_g), float(a), float(b), float(t_comp), C.byref(tau), C.byref(delta))
+    if rc != 0:
+        return None
+    return int(tau.value), float(delta.value)
+
+
+def t_avg_closed_form(tau, delta, v_g, a, b, t_comp):
+    return float(lib().oracle_t_avg_closed_form(float(tau), float(delta), float(v_g), float(a),
+                                                float(b), float(t_comp)))
+
+
+def t_avg_recurrence(tau, delta, v_g, a, b, t_comp, E):
+    return float(lib().oracle_t_avg_recurrence(int(tau), float(delta), float(v_g), float(a),
+                                               float(b), float(t_comp), int(E)))
+
+
+class Oracle:
+    """Normative (ring-form) DD-EF-SGD state on the CPU."""
+
+    def __init__(self, d: int, n: int, tau_max: int, threads: int = 1):
+        self.d, self.n, self.tau_max = int(d), int(n), int(tau_max)
+        self._h = C.c_void_p(lib().oracle_create(self.d, self.n, self.tau_max))
+        lib().oracle_set_threads(self._h, int(threads))
+
+    def close(self):
+        if self._h:
+            lib().oracle_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_problem(self, lam, xstar, x0, seed, noise_kind, noise_scale):
+        _, lp = _f32(lam)
+        _, sp = _f32(xstar)
+        _, xp = _f32(x0)
+        lib().oracle_set_problem(self._h, lp, sp, xp, int(seed), int(noise_kind), float(noise_scale))
+
+    def set_tau(self, tau):
+        lib().oracle_set_tau(self._h, int(tau))
+
+    @property
+    def t(self):
+        return int(lib().oracle_step_index(self._h))
+
+    def grad(self):
+        lib().oracle_grad(self._h)
+
+    def load_grad(self, worker, g):
+        _, gp = _f32(g)
+        lib().oracle_load_grad(self._h, int(worker), gp)
+
+    def ef_compress(self, delta, lr):
+        lib().oracle_ef_compress(self._h, float(delta), float(lr))
+
+    def aggregate(self):
+        lib().oracle_aggregate(self._h)
+
+    def apply_delayed(self):
+        lib().oracle_apply_delayed(self._h)
+
+    def step(self, delta, lr):
+        lib().oracle_step(self._h, float(delta), float(lr))
+
+    def _get_vec(self, fn, *args):
+        out = np.empty(self.d, dtype=np.float32)
+        fn(self._h, *args, out.ctypes.data_as(C.POINTER(C.c_float)))
+        return out
+
+    def get_model(self):
+        return self._get_vec(lib().oracle_get_model)
+
+    def set_model(self, x):
+        _, xp = _f32(x)
+        lib().oracle_set_model(self._h, xp)
+
+    def get_snapshot(self, step):
+        return self._get_vec(lib().oracle_get_snapshot, int(step))
+
+    def get_error(self, w):
+        return self._get_vec(lib().oracle_get_error, int(w))
+
+    def set_error(self, w, e):
+        _, ep = _f32(e)
+        lib().oracle_set_error(self._h, int(w), ep)
+
+    def get_grad(self, w):
+        return self._get_vec(lib().oracle_get_grad, int(w))
+
+    def get_update(self):
+        return self._get_vec(lib().oracle_get_update)
+
+    def get_message(self, w):
+        k = int(lib().oracle_message_size(self._h, int(w)))
+        idx = np.empty(k, dtype=np.uint32)
+        val = np.empty(k, dtype=np.float32)
+        lib().oracle_get_message(self._h, int(w), idx.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                 val.ctypes.data_as(C.POINTER(C.c_float)))
+        return idx, val
+
+    def get_threshold(self, w):
+        T, r = C.c_uint32(), C.c_uint64()
+        lib().oracle_get_threshold(self._h, int(w), C.byref(T), C.byref(r))
+        return int(T.value), int(r.value)

@@ -1,0 +1,122 @@
+"""Pins for the oracle's counter-based gradient noise (Assumption 2: zero mean, bounded variance).
+
+The generator is this build's choice (the paper only fixes the moments); what pins it is the
+published Philox known answers, libm for the two transcendental pieces, and the textbook
+distributions it must reproduce.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+
+
+def test_philox_known_answers(oracle_mod):
+    rows = [l.split() for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        out = oracle_mod.philox4x32_10(w[0:4], w[4:6])
+        assert out.tolist() == w[6:10]
+
+
+def test_philox_counter_words_are_not_interchangeable(oracle_mod):
+    base = oracle_mod.philox4x32_10([1, 2, 3, 4], [5, 6]).tolist()
+    seen = {tuple(base)}
+    for ctr, key in [([2, 1, 3, 4], [5, 6]), ([1, 2, 4, 3], [5, 6]), ([1, 2, 3, 4], [6, 5]),
+                     ([1, 3, 2, 4], [5, 6])]:
+        seen.add(tuple(oracle_mod.philox4x32_10(ctr, key).tolist()))
+    assert len(seen) == 5
+
+
+def _words(rng, m):
+    w = rng.integers(0, 1 << 32, size=m, dtype=np.uint64)
+    edge = np.array([0, 0xFF, 0x100, 0xFFFFFFFF, 0xFFFFFF00, 0x80000000, 0x7FFFFFFF,
+                     0x3504F300, 0x3504F400, 0xB504F300, 0x20000000, 0x1FFFFF00, 0xDFFFFF00,
+                     0xE0000000, 0x5FFFFF00, 0x60000000, 0x9FFFFF00, 0xA0000000], dtype=np.uint64)
+    return np.concatenate([edge, w])
+
+
+def test_neg2ln_matches_libm(oracle_mod):
+    rng = np.random.default_rng(11)
+    for w in _words(rng, 20000):
+        w = int(w)
+        u = ((w >> 8) + 1) / 2.0 ** 24
+        want = -2.0 * math.log(u)
+        got = oracle_mod.neg2ln_uniform(w)
+        assert got >= 0.0
+        assert abs(got - want) <= 2e-6 * max(1.0, want), (hex(w), got, want)
+    assert oracle_mod.neg2ln_uniform(0xFFFFFFFF) == 0.0          # u = 1 exactly
+
+
+def test_unit_circle_matches_libm(oracle_mod):
+    rng = np.random.default_rng(12)
+    for w in _words(rng, 20000):
+        w = int(w)
+        ang = 2.0 * math.pi * ((w >> 8) + 0.5) / 2.0 ** 24
+        c, s = oracle_mod.unit_circle_point(w)
+        assert abs(c - math.cos(ang)) <= 3e-7, hex(w)
+        assert abs(s - math.sin(ang)) <= 3e-7, hex(w)
+
+
+def test_normal_draw_is_box_muller_of_the_philox_words(oracle_mod):
+    # z = sqrt(-2 ln u1) cos(2 pi u2) with u1, u2 from output words 0 and 1 of the block
+    # whose counter is (j, worker, t_lo, t_hi) and whose key is the seed.
+    seed, t, worker = 0x1234567855AA33CC, (7 << 32) | 9, 3
+    for j in [0, 1, 77, 2 ** 31 + 5]:
+        w = oracle_mod.philox4x32_10([j, worker, t & 0xFFFFFFFF, t >> 32],
+                                     [seed & 0xFFFFFFFF, seed >> 32])
+        u1 = ((int(w[0]) >> 8) + 1) / 2.0 ** 24
+        ang = 2.0 * math.pi * ((int(w[1]) >> 8) + 0.5) / 2.0 ** 24
+        want = math.sqrt(-2.0 * math.log(u1)) * math.cos(ang)
+        got = oracle_mod.noise_z(seed, t, worker, j, 1)
+        assert abs(got - want) <= 5e-6 * max(1.0, abs(want))
+        z1 = math.sqrt(-2.0 * math.log(u1)) * math.sin(ang)
+        u3 = ((int(w[2]) >> 8) + 1) / 2.0 ** 24
+        a3 = 2.0 * math.pi * ((int(w[3]) >> 8) + 0.5) / 2.0 ** 24
+        z2 = math.sqrt(-2.0 * math.log(u3)) * math.cos(a3)
+        z3 = math.sqrt(-2.0 * math.log(u3)) * math.sin(a3)
+        want_t = want / math.sqrt((z1 * z1 + z2 * z2 + z3 * z3) / 3.0)
+        got_t = oracle_mod.noise_z(seed, t, worker, j, 2)
+        assert abs(got_t - want_t) <= 2e-5 * max(1.0, abs(want_t))
+    assert oracle_mod.noise_z(seed, t, worker, 5, 0) == 0.0
+
+
+def test_normal_distribution(oracle_mod):
+    z = oracle_mod.noise_fill(0, 3, 1, 0, 400_000, 1).astype(np.float64)
+    assert abs(z.mean()) < 5e-3
+    assert abs(z.var() - 1.0) < 1e-2
+    assert abs(stats.skew(z)) < 2e-2
+    assert abs(stats.kurtosis(z)) < 5e-2
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    # tails: P(|z| > 3) = 2.6998e-3
+    assert abs((np.abs(z) > 3).mean() - 2.6998e-3) < 4e-4
+
+
+def test_student_t3_distribution(oracle_mod):
+    z = oracle_mod.noise_fill(2, 9, 0, 0, 400_000, 2).astype(np.float64)
+    assert abs(np.median(z)) < 5e-3
+    assert stats.kstest(z, "t", args=(3,)).pvalue > 1e-3
+    # heavy tail: P(|t3| > 5) = 2 * sf(5)
+    want = 2 * stats.t.sf(5.0, 3)
+    assert abs((np.abs(z) > 5).mean() - want) < 1e-3
+    assert np.abs(z).max() > 30.0
+
+
+def test_draws_depend_on_every_coordinate(oracle_mod):
+    a = oracle_mod.noise_fill(5, 10, 2, 0, 1000, 1)
+    assert np.array_equal(a, oracle_mod.noise_fill(5, 10, 2, 0, 1000, 1))
+    for other in (oracle_mod.noise_fill(6, 10, 2, 0, 1000, 1),
+                  oracle_mod.noise_fill(5, 11, 2, 0, 1000, 1),
+                  oracle_mod.noise_fill(5, 10, 3, 0, 1000, 1),
+                  oracle_mod.noise_fill(5, 10, 2, 1, 1000, 1)):
+        assert abs(np.corrcoef(a, other)[0, 1]) < 0.15
+    # the fill is the per-element function evaluated at consecutive j
+    assert a[17] == np.float32(oracle_mod.noise_z(5, 10, 2, 17, 1))
+    # workers are uncorrelated at the same (t, j): the noise is per worker
+    b = oracle_mod.noise_fill(5, 10, 3, 0, 200_000, 1)
+    c = oracle_mod.noise_fill(5, 10, 2, 0, 200_000, 1)
+    assert abs(np.corrcoef(b, c)[0, 1]) < 1e-2

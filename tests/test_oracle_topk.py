@@ -1,0 +1,105 @@
+"""Pins for the oracle's Top-k compressor (Section 5.2: keep the k largest-magnitude entries;
+ties broken towards the lower index; Top-k lemma: ||C(p) - p||^2 <= (1 - k/d) ||p||^2)."""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2507_17346_amd import workloads
+
+
+def key_of(p):
+    return np.asarray(p, dtype=np.float32).view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def brute_force(p, k):
+    """Full sort by (|v| descending, index ascending), written without the oracle."""
+    keys = key_of(p)
+    order = sorted(range(len(p)), key=lambda j: (-int(keys[j]), j))
+    return np.array(sorted(order[:k]), dtype=np.uint32)
+
+
+KINDS = ["normal", "heavy", "few_values", "all_equal", "signed_zero", "denormal", "wide"]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("d", [1, 2, 7, 64, 1000])
+def test_topk_matches_full_sort(oracle_mod, kind, d):
+    p = workloads.random_vector(100 + d, d, kind)
+    for k in sorted({1, max(1, d // 100), max(1, d // 3), max(1, d - 1), d}):
+        idx, T, r = oracle_mod.topk(p, k)
+        want = brute_force(p, k)
+        assert np.array_equal(idx, want), (kind, d, k)
+        keys = key_of(p)
+        assert T == int(keys[idx].min())
+        assert r == int((keys[idx] == T).sum())
+        unsel = np.setdiff1d(np.arange(d), idx)
+        if len(unsel):
+            assert int(keys[idx].min()) >= int(keys[unsel].max())
+            # among entries tied at the threshold the chosen ones are the lowest indices
+            tied_sel = idx[keys[idx] == T]
+            tied_uns = unsel[keys[unsel] == T]
+            if len(tied_uns):
+                assert tied_sel.max() < tied_uns.min()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_is_the_unique_dominating_subset(oracle_mod, seed):
+    # exhaustive over all subsets of size k for d <= 10: exactly one subset has every
+    # member ahead of every non-member in the total order.
+    rng = np.random.default_rng(seed)
+    d = int(rng.integers(2, 11))
+    p = (rng.integers(-2, 3, size=d) * 0.5).astype(np.float32)   # plenty of ties and zeros
+    keys = key_of(p)
+    rank = {j: (-int(keys[j]), j) for j in range(d)}
+    for k in range(1, d + 1):
+        winners = []
+        for S in itertools.combinations(range(d), k):
+            rest = [j for j in range(d) if j not in S]
+            if not rest or max(rank[j] for j in S) < min(rank[j] for j in rest):
+                winners.append(S)
+        assert len(winners) == 1
+        idx, _, _ = oracle_mod.topk(p, k)
+        assert tuple(int(i) for i in idx) == winners[0]
+
+
+def test_crafted_cases(oracle_mod):
+    p = np.array([0.5, -0.5, 0.25, -1.0, 1.0, 0.0, -0.0, 0.5], dtype=np.float32)
+    assert oracle_mod.topk(p, 1)[0].tolist() == [3]                # -1.0 before +1.0 (lower index)
+    assert oracle_mod.topk(p, 2)[0].tolist() == [3, 4]
+    assert oracle_mod.topk(p, 3)[0].tolist() == [0, 3, 4]          # first of the three 0.5
+    assert oracle_mod.topk(p, 4)[0].tolist() == [0, 1, 3, 4]
+    idx, T, r = oracle_mod.topk(p, 4)
+    assert T == int(np.float32(0.5).view(np.uint32)) and r == 2
+    assert oracle_mod.topk(p, 7)[0].tolist() == [0, 1, 2, 3, 4, 5, 7]   # +0 at 5 before -0 at 6
+    tiny = np.array([1, 0x80000003, 0, 2], dtype=np.uint32).view(np.float32)   # denormals order by value
+    assert oracle_mod.topk(tiny, 2)[0].tolist() == [1, 3]
+
+
+def test_contraction_bound(oracle_mod):
+    for kind in ["normal", "heavy", "wide"]:
+        p = workloads.random_vector(7, 5000, kind).astype(np.float32)
+        p64 = p.astype(np.float64)
+        if not np.isfinite((p64 ** 2).sum()):
+            p64 = p64 * 1e-30
+        for k in [1, 50, 2500, 5000]:
+            idx, _, _ = oracle_mod.topk(p, k)
+            res = p64.copy()
+            res[idx] = 0.0
+            assert (res ** 2).sum() <= (1 - k / 5000) * (p64 ** 2).sum() * (1 + 1e-12)
+
+
+def test_k_from_delta(oracle_mod):
+    # k = ceil(delta * d) in double precision, clamped to [1, d]; the workloads' stated k.
+    assert oracle_mod.k_from_delta(0.01, 1_000_000) == 10_000
+    assert oracle_mod.k_from_delta(0.01, 11_700_000) == 117_000
+    assert oracle_mod.k_from_delta(0.001, 124_000_000) == 124_000
+    assert oracle_mod.k_from_delta(0.1, 1_300_000_000) == 130_000_000
+    assert oracle_mod.k_from_delta(0.001, 1_300_000_000) == 1_300_000
+    assert oracle_mod.k_from_delta(1.0, 17) == 17
+    assert oracle_mod.k_from_delta(1e-9, 17) == 1
+    assert oracle_mod.k_from_delta(0.5, 3) == 2
+    for name in ["C1", "C2", "C3", "C4"]:
+        w = workloads.get(name)
+        for dl in w.deltas:
+            assert oracle_mod.k_from_delta(dl, w.d) == w.k(dl)
