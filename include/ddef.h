@@ -1,0 +1,154 @@
+/*
+ * ddef — the data-parallel hot path of DD-EF-SGD / DeCo-SGD on one AMD MI355X (gfx950).
+ *
+ * One context simulates the n workers and the server of Algorithm 1 of the paper
+ * ("DD-EF-SGD") with every worker's share resident in the GPU's HBM.  One iteration t is
+ * the four calls, in this order,
+ *
+ *     ddef_grad            g_i = grad f_i(x_{t-tau}) + xi_i      (Assumption 2, Section 2.2.3)
+ *     ddef_ef_compress     Delta_i = C_delta(e_i + gamma g_i),
+ *                          e_i <- e_i + gamma g_i - Delta_i       (Algorithm 1, worker side)
+ *     ddef_aggregate       U = sum_i Delta_i                      (Algorithm 1, server side)
+ *     ddef_apply_delayed   x_{t+1} = x_t - U / n                  (Algorithm 1, server side)
+ *
+ * The delay tau lives in a ring of tau_max+1 parameter snapshots: iteration t takes its
+ * gradient at the snapshot x_{t-tau} and applies the resulting update at once, which gives
+ * the same iterates x_t as a server that holds every message for tau iterations.  While
+ * t - tau < 0 nothing has arrived yet (the paper's convention Delta_{t-tau} = 0, Section
+ * 3.2): those iterations leave x and every e_i unchanged and only advance t.
+ *
+ * C_delta is Top-k (Section 5.2: keep the k largest-magnitude entries) with
+ * k = ceil(delta * d) clamped to [1, d].  The order is total: larger |v| first, compared on
+ * the IEEE-754 bit pattern with the sign cleared, then lower index.  A message is the k
+ * pairs (index, value) in ascending index order.
+ *
+ * Conventions for every function
+ *   - returns DDEF_OK (0) or a negative DDEF_E* code; never throws, aborts or prints;
+ *   - pointers named host_* are host memory owned by the caller, read or filled before the
+ *     call returns; the library owns all device memory;
+ *   - a context is bound to the HIP device that was current at ddef_init and to one stream;
+ *     the four step calls only enqueue work on that stream, the getters and ddef_sync wait
+ *     for it.  A context is not thread-safe;
+ *   - all arithmetic is IEEE fp32 with every operation rounded separately (no fused
+ *     multiply-add), indices are uint32, d < 2^32.
+ */
+#ifndef DDEF_H
+#define DDEF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DDEF_OK 0
+#define DDEF_EINVAL (-1)     /* argument outside its domain, null pointer                 */
+#define DDEF_ESTATE (-2)     /* call order violated                                       */
+#define DDEF_ENOMEM (-3)     /* device or host allocation failed                          */
+#define DDEF_EHIP (-4)       /* a HIP runtime call failed; sticky for the context         */
+#define DDEF_ENONFINITE (-5) /* reserved: NaN/Inf met where finite input is required      */
+
+#define DDEF_NOISE_NONE 0
+#define DDEF_NOISE_GAUSS 1      /* N(0,1) * noise_scale                                    */
+#define DDEF_NOISE_STUDENT_T3 2 /* Student-t, 3 degrees of freedom, * noise_scale          */
+
+typedef struct ddef_ctx ddef_ctx;
+
+/* Problem statement of Algorithm 1: x in R^d, n workers, staleness at most tau_max.
+ * Allocates e[n][d] = 0, g[n][d], the snapshot ring [tau_max+1][d], U[d] and work buffers
+ * on the current device; tau starts at tau_max.  d in [1, 2^32), n >= 1, tau_max <= 4096.
+ * On failure *out is NULL.  ENOMEM when the device cannot hold the state. */
+int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out);
+int ddef_destroy(ddef_ctx* ctx);
+
+/* Use a caller-provided hipStream_t (passed as void*) for all later work; NULL restores
+ * the context's own stream.  The caller keeps the stream alive.  Only between iterations. */
+int ddef_set_stream(ddef_ctx* ctx, void* hip_stream);
+
+/* The synthetic objective f(x) = 1/2 sum_j lambda_j (x_j - xstar_j)^2 shared by all workers
+ * (IID data) and the start point: copies three host arrays of d floats, sets every snapshot
+ * to x0, every error buffer to 0 and t to 0.  Gradient noise xi = noise_scale * z with z a
+ * counter-based draw keyed by (seed, t, worker, j): Philox4x32-10, Box-Muller. */
+int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_xstar,
+                     const float* host_x0, uint64_t seed, int noise_kind, float noise_scale);
+
+/* Staleness for the following iterations, 0..tau_max (Algorithm 2 re-chooses it every E
+ * iterations).  Only between iterations, else ESTATE. */
+int ddef_set_tau(ddef_ctx* ctx, uint32_t tau);
+
+/* Stochastic gradient of every worker at the stale iterate:
+ * g_i[j] = lambda[j] * (x_{t-tau}[j] - xstar[j]) + noise_scale * z(seed, t, i, j).
+ * While t - tau < 0 the iteration is marked empty and no gradient is produced. */
+int ddef_grad(ddef_ctx* ctx);
+
+/* Test hook: replace worker `worker`'s gradient by d host floats (instead of, or after,
+ * ddef_grad) and mark the iteration as non-empty. */
+int ddef_load_grad(ddef_ctx* ctx, uint32_t worker, const float* host_g);
+
+/* Error feedback and Top-k for every worker: p = e + lr*g (two roundings), the k entries of
+ * p first in the order above become the message, e <- p with the sent entries set to +0.
+ * delta in (0, 1] (double, so that k = ceil(delta*d) is the intended integer); lr is the
+ * stepsize gamma.  On an empty iteration the messages are empty and e is untouched. */
+int ddef_ef_compress(ddef_ctx* ctx, double delta, float lr);
+
+/* Dense sum of the n messages, U[j] = ((0 + Delta_0[j]) + Delta_1[j]) + ..., in worker
+ * order, which makes the fp32 result reproducible. */
+int ddef_aggregate(ddef_ctx* ctx);
+
+/* x_{t+1} = x_t - U / (float)n, stored as the next snapshot; t <- t + 1.  lr must be the
+ * value given to ddef_ef_compress in this iteration (the stepsize acts inside the error
+ * feedback, as in Algorithm 1; it is checked, not applied a second time), else EINVAL. */
+int ddef_apply_delayed(ddef_ctx* ctx, float lr);
+
+/* Wait for the context's stream. */
+int ddef_sync(ddef_ctx* ctx);
+
+/* ---- inspection / checkpoint hooks (each waits for the stream) ------------------------ */
+int ddef_step_index(ddef_ctx* ctx, uint64_t* t);
+int ddef_get_model(ddef_ctx* ctx, float* host_x);                       /* x_t, d floats  */
+int ddef_set_model(ddef_ctx* ctx, const float* host_x);                 /* overwrite x_t  */
+int ddef_get_error(ddef_ctx* ctx, uint32_t worker, float* host_e);
+int ddef_set_error(ddef_ctx* ctx, uint32_t worker, const float* host_e);
+int ddef_get_grad(ddef_ctx* ctx, uint32_t worker, float* host_g);
+int ddef_get_update(ddef_ctx* ctx, float* host_U);
+/* Last message of a worker: *k entries (0 on an empty iteration), ascending index.
+ * host_idx / host_val may be NULL to query k only; otherwise they hold at least k items. */
+int ddef_get_message(ddef_ctx* ctx, uint32_t worker, uint32_t* host_idx, float* host_val,
+                     uint64_t* k);
+/* Threshold of the last selection: T = smallest selected magnitude pattern, r = how many
+ * selected entries carry exactly T. */
+int ddef_get_threshold(ddef_ctx* ctx, uint32_t worker, uint32_t* T, uint64_t* r);
+
+/* ---- host-side scalar pieces ------------------------------------------------------------ */
+/* k = ceil(delta*d) clamped to [1, d]; 0 when delta is outside (0, 1] or d is 0. */
+uint64_t ddef_k_from_delta(double delta, uint64_t d);
+/* DeCo (Algorithm 3): scan tau from ceil((b + V_g/a)/T_comp) down to ceil(b/T_comp) with
+ * delta = min{(tau T_comp - b) a / V_g, T_comp a / V_g, 1}, skip candidates with
+ * delta <= 0, keep the minimal phi = (1-delta) / (delta (1-delta/2)^tau), smallest tau on
+ * ties.  v_g_bits, a_bps (bits/s), b_s, t_comp_s > 0.  EINVAL when no candidate exists. */
+int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
+              double* delta);
+
+/* ---- measurement hooks ------------------------------------------------------------------ */
+/* With profiling on, every kernel launch is bracketed by HIP events on the context's
+ * stream; ddef_profile_read waits for the stream and returns, for kernel slot `slot`
+ * (0 .. ddef_profile_slots()-1), its name, the launches since profiling was switched on and
+ * their summed duration in milliseconds. */
+int ddef_profile_enable(ddef_ctx* ctx, int on);
+int ddef_profile_slots(void);
+int ddef_profile_read(ddef_ctx* ctx, int slot, const char** name, uint64_t* launches,
+                      double* total_ms);
+/* How many worker selections so far took the multi-pass path over the whole vector
+ * (counted over all workers and iterations since ddef_set_problem). */
+int ddef_full_select_count(ddef_ctx* ctx, uint64_t* count);
+/* Tuning / test knobs; see DDEF_OPT_*.  Only between iterations. */
+#define DDEF_OPT_FORCE_FULL_SELECT 1 /* 1: never use the candidate filter                 */
+#define DDEF_OPT_CANDIDATE_SLACK_X16 2 /* candidate target = k * value / 16 (default 40)  */
+int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
+
+const char* ddef_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDEF_H */

@@ -1,0 +1,257 @@
+"""Thin ctypes binding of libddef.so: same names as include/ddef.h, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; nothing here computes.  There is no
+fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+OK, EINVAL, ESTATE, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4, -5
+NOISE_NONE, NOISE_GAUSS, NOISE_STUDENT_T3 = 0, 1, 2
+OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16 = 1, 2
+
+_u32p, _f32p, _u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
+_ctx = C.c_void_p
+
+SIGNATURES = {
+    "ddef_init": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(_ctx)]),
+    "ddef_destroy": (C.c_int, [_ctx]),
+    "ddef_set_stream": (C.c_int, [_ctx, C.c_void_p]),
+    "ddef_set_problem": (C.c_int, [_ctx, _f32p, _f32p, _f32p, C.c_uint64, C.c_int, C.c_float]),
+    "ddef_set_tau": (C.c_int, [_ctx, C.c_uint32]),
+    "ddef_grad": (C.c_int, [_ctx]),
+    "ddef_load_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
+    "ddef_aggregate": (C.c_int, [_ctx]),
+    "ddef_apply_delayed": (C.c_int, [_ctx, C.c_float]),
+    "ddef_sync": (C.c_int, [_ctx]),
+    "ddef_step_index": (C.c_int, [_ctx, _u64p]),
+    "ddef_get_model": (C.c_int, [_ctx, _f32p]),
+    "ddef_set_model": (C.c_int, [_ctx, _f32p]),
+    "ddef_get_error": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_set_error": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_get_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_get_update": (C.c_int, [_ctx, _f32p]),
+    "ddef_get_message": (C.c_int, [_ctx, C.c_uint32, _u32p, _f32p, _u64p]),
+    "ddef_get_threshold": (C.c_int, [_ctx, C.c_uint32, _u32p, _u64p]),
+    "ddef_k_from_delta": (C.c_uint64, [C.c_double, C.c_uint64]),
+    "ddef_deco": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
+    "ddef_profile_enable": (C.c_int, [_ctx, C.c_int]),
+    "ddef_profile_slots": (C.c_int, []),
+    "ddef_profile_read": (C.c_int, [_ctx, C.c_int, C.POINTER(C.c_char_p), _u64p, C.POINTER(C.c_double)]),
+    "ddef_full_select_count": (C.c_int, [_ctx, _u64p]),
+    "ddef_set_option": (C.c_int, [_ctx, C.c_int, C.c_int64]),
+    "ddef_strerror": (C.c_char_p, [C.c_int]),
+}
+
+_lib = None
+
+
+class DdefError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libddef.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    lib = C.CDLL(_build.LIB)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)          # AttributeError if the library lacks a declared symbol
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().ddef_strerror(int(code)).decode()
+
+
+def k_from_delta(delta: float, d: int) -> int:
+    return int(load().ddef_k_from_delta(float(delta), int(d)))
+
+
+def deco(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> Optional[Tuple[int, float]]:
+    tau, delta = C.c_uint32(), C.c_double()
+    rc = load().ddef_deco(float(v_g_bits), float(a_bps), float(b_s), float(t_comp_s),
+                          C.byref(tau), C.byref(delta))
+    if rc == EINVAL:
+        return None
+    if rc != OK:
+        raise DdefError(rc, "ddef_deco")
+    return int(tau.value), float(delta.value)
+
+
+def _f32(a) -> Tuple[np.ndarray, "C._Pointer"]:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data_as(_f32p)
+
+
+class Context:
+    """One ddef_ctx.  Methods carry the C names without the prefix and raise on error codes;
+    `raw_*` variants return the code instead (for error-path tests)."""
+
+    def __init__(self, d: int, n: int, tau_max: int):
+        self._lib = load()
+        self.d, self.n, self.tau_max = int(d), int(n), int(tau_max)
+        h = _ctx()
+        rc = self._lib.ddef_init(self.d, self.n, self.tau_max, C.byref(h))
+        if rc != OK:
+            raise DdefError(rc, "ddef_init")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ddef_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def _check(self, rc: int, what: str):
+        if rc != OK:
+            raise DdefError(rc, what)
+
+    # ---- set-up -------------------------------------------------------------------------
+    def set_stream(self, hip_stream: Optional[int]):
+        self._check(self._lib.ddef_set_stream(self._h, C.c_void_p(hip_stream or 0)), "ddef_set_stream")
+
+    def set_problem(self, lam, xstar, x0, seed: int, noise_kind: int, noise_scale: float):
+        lam, lp = _f32(lam)
+        xstar, sp = _f32(xstar)
+        x0, xp = _f32(x0)
+        for a in (lam, xstar, x0):
+            if a.shape != (self.d,):
+                raise ValueError("problem vectors must have length d")
+        self._check(self._lib.ddef_set_problem(self._h, lp, sp, xp, int(seed), int(noise_kind),
+                                               float(noise_scale)), "ddef_set_problem")
+
+    def set_tau(self, tau: int):
+        self._check(self._lib.ddef_set_tau(self._h, int(tau)), "ddef_set_tau")
+
+    def set_option(self, option: int, value: int):
+        self._check(self._lib.ddef_set_option(self._h, int(option), int(value)), "ddef_set_option")
+
+    # ---- the step -----------------------------------------------------------------------
+    def grad(self):
+        self._check(self._lib.ddef_grad(self._h), "ddef_grad")
+
+    def load_grad(self, worker: int, g):
+        g, gp = _f32(g)
+        if g.shape != (self.d,):
+            raise ValueError("gradient must have length d")
+        self._check(self._lib.ddef_load_grad(self._h, int(worker), gp), "ddef_load_grad")
+
+    def ef_compress(self, delta: float, lr: float):
+        self._check(self._lib.ddef_ef_compress(self._h, float(delta), float(lr)), "ddef_ef_compress")
+
+    def aggregate(self):
+        self._check(self._lib.ddef_aggregate(self._h), "ddef_aggregate")
+
+    def apply_delayed(self, lr: float):
+        self._check(self._lib.ddef_apply_delayed(self._h, float(lr)), "ddef_apply_delayed")
+
+    def step(self, delta: float, lr: float):
+        self.grad()
+        self.ef_compress(delta, lr)
+        self.aggregate()
+        self.apply_delayed(lr)
+
+    def sync(self):
+        self._check(self._lib.ddef_sync(self._h), "ddef_sync")
+
+    # raw return codes, for error-path tests
+    def raw(self, name: str, *args) -> int:
+        return int(getattr(self._lib, "ddef_" + name)(self._h, *args))
+
+    # ---- inspection ---------------------------------------------------------------------
+    @property
+    def t(self) -> int:
+        t = C.c_uint64()
+        self._check(self._lib.ddef_step_index(self._h, C.byref(t)), "ddef_step_index")
+        return int(t.value)
+
+    def _get(self, fn, what, *args) -> np.ndarray:
+        out = np.empty(self.d, dtype=np.float32)
+        self._check(fn(self._h, *args, out.ctypes.data_as(_f32p)), what)
+        return out
+
+    def get_model(self):
+        return self._get(self._lib.ddef_get_model, "ddef_get_model")
+
+    def set_model(self, x):
+        x, xp = _f32(x)
+        self._check(self._lib.ddef_set_model(self._h, xp), "ddef_set_model")
+
+    def get_error(self, worker: int):
+        return self._get(self._lib.ddef_get_error, "ddef_get_error", int(worker))
+
+    def set_error(self, worker: int, e):
+        e, ep = _f32(e)
+        self._check(self._lib.ddef_set_error(self._h, int(worker), ep), "ddef_set_error")
+
+    def get_grad(self, worker: int):
+        return self._get(self._lib.ddef_get_grad, "ddef_get_grad", int(worker))
+
+    def get_update(self):
+        return self._get(self._lib.ddef_get_update, "ddef_get_update")
+
+    def get_message(self, worker: int):
+        k = C.c_uint64()
+        self._check(self._lib.ddef_get_message(self._h, int(worker), None, None, C.byref(k)), "ddef_get_message")
+        idx = np.empty(k.value, dtype=np.uint32)
+        val = np.empty(k.value, dtype=np.float32)
+        if k.value:
+            self._check(self._lib.ddef_get_message(self._h, int(worker), idx.ctypes.data_as(_u32p),
+                                                   val.ctypes.data_as(_f32p), C.byref(k)), "ddef_get_message")
+        return idx, val
+
+    def get_threshold(self, worker: int):
+        T, r = C.c_uint32(), C.c_uint64()
+        self._check(self._lib.ddef_get_threshold(self._h, int(worker), C.byref(T), C.byref(r)), "ddef_get_threshold")
+        return int(T.value), int(r.value)
+
+    def full_select_count(self) -> int:
+        cnt = C.c_uint64()
+        self._check(self._lib.ddef_full_select_count(self._h, C.byref(cnt)), "ddef_full_select_count")
+        return int(cnt.value)
+
+    # ---- measurement --------------------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._check(self._lib.ddef_profile_enable(self._h, 1 if on else 0), "ddef_profile_enable")
+
+    def profile_read(self):
+        """{kernel name: (launches, total_ms)} since profiling was switched on."""
+        out = {}
+        for s in range(self._lib.ddef_profile_slots()):
+            name, cnt, ms = C.c_char_p(), C.c_uint64(), C.c_double()
+            self._check(self._lib.ddef_profile_read(self._h, s, C.byref(name), C.byref(cnt), C.byref(ms)),
+                        "ddef_profile_read")
+            out[name.value.decode()] = (int(cnt.value), float(ms.value))
+        return out

@@ -1,0 +1,573 @@
+// C-ABI of the DD-EF-SGD hot path: context, state machine, launch sequences.
+// Every step of the path runs in the kernels of ddef_kernels.hip; this file validates
+// arguments, owns the device memory and enqueues launches on the context's stream.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ddef.h"
+#include "ddef_kernels.h"
+
+using namespace ddef;
+
+namespace {
+
+enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
+
+enum Slot {
+    SL_GRAD = 0, SL_EF_ACCUM, SL_SEL_BEGIN, SL_FILL, SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT,
+    SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_SCATTER_ADD, SL_APPLY, SL_COUNT
+};
+const char* const kSlotNames[SL_COUNT] = {
+    "k_grad", "k_ef_accumulate", "k_sel_begin", "k_fill_u32", "k_digit_hist", "k_digit_pick",
+    "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_scatter_add", "k_apply"};
+
+struct ProfRecord { int slot; hipEvent_t start, stop; };
+
+}  // namespace
+
+struct ddef_ctx {
+    int device = 0;
+    int cus = 256;
+    hipStream_t own_stream = nullptr, stream = nullptr;
+    uint64_t d = 0, ld = 0, t = 0;
+    uint32_t n = 0, tau_max = 0, tau = 0, nchunks = 0;
+    float *lambda = nullptr, *xstar = nullptr, *ring = nullptr, *e = nullptr, *g = nullptr, *U = nullptr;
+    uint32_t* msg_idx = nullptr;
+    float* msg_val = nullptr;
+    uint64_t msg_ld = 0;
+    SelState* sel = nullptr;
+    uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
+    Phase phase = PH_IDLE;
+    bool problem_set = false, step_empty = true;
+    float lr_step = 0.0f;
+    uint64_t k_step = 0;
+    uint64_t seed = 0;
+    int noise_kind = 0;
+    float noise_scale = 0.0f;
+    int sticky = DDEF_OK;
+    uint64_t full_selects = 0;
+    int64_t opt_force_full = 0, opt_slack_x16 = 40;
+    bool profiling = false;
+    std::vector<ProfRecord> pending;
+    std::vector<hipEvent_t> free_events;
+    uint64_t prof_launches[SL_COUNT] = {};
+    double prof_ms[SL_COUNT] = {};
+
+    float* slot(uint64_t step) const { return ring + (step % (uint64_t)(tau_max + 1)) * ld; }
+};
+
+namespace {
+
+int hip_fail(ddef_ctx* c, hipError_t err) {
+    if (err == hipSuccess) return DDEF_OK;
+    int code = (err == hipErrorOutOfMemory) ? DDEF_ENOMEM : DDEF_EHIP;
+    if (c && code == DDEF_EHIP) c->sticky = DDEF_EHIP;
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                         \
+    do {                                           \
+        hipError_t err__ = (expr);                 \
+        if (err__ != hipSuccess) return hip_fail((ctx), err__); \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && (prev == dev || hipSetDevice(dev) == hipSuccess)) ok = true;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+hipEvent_t take_event(ddef_ctx* c) {
+    if (!c->free_events.empty()) { hipEvent_t e = c->free_events.back(); c->free_events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct LaunchScope {
+    ddef_ctx* c;
+    hipEvent_t stop = nullptr;
+    int slot;
+    LaunchScope(ddef_ctx* ctx, int s) : c(ctx), slot(s) {
+        if (!c->profiling) return;
+        hipEvent_t start = take_event(c);
+        stop = take_event(c);
+        if (!start || !stop) { stop = nullptr; return; }
+        (void)hipEventRecord(start, c->stream);
+        c->pending.push_back(ProfRecord{slot, start, stop});
+    }
+    ~LaunchScope() { if (stop) (void)hipEventRecord(stop, c->stream); }
+};
+
+#define LAUNCH(ctx, slot, kernel, grid, block, ...)                                 \
+    do {                                                                            \
+        LaunchScope scope__((ctx), (slot));                                         \
+        hipLaunchKernelGGL(kernel, (grid), (block), 0, (ctx)->stream, __VA_ARGS__); \
+    } while (0)
+
+int resolve_profile(ddef_ctx* c) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (const ProfRecord& r : c->pending) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            c->prof_launches[r.slot] += 1;
+            c->prof_ms[r.slot] += (double)ms;
+        }
+        c->free_events.push_back(r.start);
+        c->free_events.push_back(r.stop);
+    }
+    c->pending.clear();
+    return DDEF_OK;
+}
+
+uint32_t blocks_for(ddef_ctx* c, uint64_t items_per_row_blocks, uint32_t rows, uint32_t per_cu) {
+    uint64_t budget = (uint64_t)c->cus * per_cu / (rows ? rows : 1u);
+    if (budget < 1) budget = 1;
+    uint64_t b = items_per_row_blocks < budget ? items_per_row_blocks : budget;
+    return (uint32_t)(b < 1 ? 1 : b);
+}
+
+int ensure_message_capacity(ddef_ctx* c, uint64_t k) {
+    if (k <= c->msg_ld) return DDEF_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->msg_idx) (void)hipFree(c->msg_idx);
+    if (c->msg_val) (void)hipFree(c->msg_val);
+    c->msg_idx = nullptr; c->msg_val = nullptr; c->msg_ld = 0;
+    uint64_t cap = (k + 1023u) & ~(uint64_t)1023u;
+    HIP_TRY(c, hipMalloc((void**)&c->msg_idx, (size_t)c->n * cap * 4u));
+    HIP_TRY(c, hipMalloc((void**)&c->msg_val, (size_t)c->n * cap * 4u));
+    HIP_TRY(c, hipMemset(c->msg_idx, 0, (size_t)c->n * cap * 4u));
+    HIP_TRY(c, hipMemset(c->msg_val, 0, (size_t)c->n * cap * 4u));
+    c->msg_ld = cap;
+    return DDEF_OK;
+}
+
+// Multi-pass selection over the whole row for every active worker, then ordered compaction.
+void enqueue_full_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
+    const uint32_t n = c->n, d = (uint32_t)c->d;
+    LAUNCH(c, SL_SEL_BEGIN, k_sel_begin, dim3((n + 63) / 64), dim3(64), c->sel, n, k, kb, 1u);
+    const uint64_t hist_words = (uint64_t)3 * n * 2 * 2048;
+    LAUNCH(c, SL_FILL, k_fill_u32, dim3((uint32_t)((hist_words + 255) / 256)), dim3(256), c->hist,
+           hist_words, 0u);
+    const uint32_t tiles = (uint32_t)((c->d + 1023) / 1024);
+    const uint32_t gx = blocks_for(c, tiles, n, 8);
+    for (int level = 0; level < 3; ++level) {
+        uint32_t* h = c->hist + (uint64_t)level * n * 2 * 2048;
+        LAUNCH(c, SL_DIGIT_HIST, k_digit_hist, dim3(gx, n), dim3(256), c->e, c->ld, d,
+               (const uint32_t*)nullptr, c->sel, h, level);
+        LAUNCH(c, SL_DIGIT_PICK, k_digit_pick, dim3(n, 2), dim3(256), c->sel, h, level);
+    }
+    const uint32_t gc = blocks_for(c, c->nchunks, n, 8);
+    LAUNCH(c, SL_CHUNK_COUNT, k_chunk_count, dim3(gc, n), dim3(256), c->e, c->ld, d, c->sel,
+           c->cnt_gt, c->cnt_eq, c->nchunks);
+    LAUNCH(c, SL_CHUNK_SCAN, k_chunk_scan, dim3(n), dim3(1024), c->sel, c->cnt_gt, c->cnt_eq, c->nchunks);
+    LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), c->e, c->ld, d, c->sel, c->cnt_gt,
+           c->cnt_eq, c->nchunks, c->msg_idx, c->msg_val, c->msg_ld, k);
+    c->full_selects += n;
+}
+
+int check_ctx(ddef_ctx* c) {
+    if (!c) return DDEF_EINVAL;
+    if (c->sticky != DDEF_OK) return c->sticky;
+    return DDEF_OK;
+}
+
+int copy_row_out(ddef_ctx* c, const float* dev_row, float* host) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host, dev_row, (size_t)c->d * 4u, hipMemcpyDeviceToHost));
+    return DDEF_OK;
+}
+
+int copy_row_in(ddef_ctx* c, float* dev_row, const float* host) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(dev_row, host, (size_t)c->d * 4u, hipMemcpyHostToDevice));
+    return DDEF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t ddef_k_from_delta(double delta, uint64_t d) {
+    if (!(delta > 0.0) || !(delta <= 1.0) || d == 0) return 0;
+    double want = std::ceil(delta * (double)d);
+    if (want < 1.0) return 1;
+    if (want >= (double)d) return d;
+    return (uint64_t)want;
+}
+
+int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau, double* delta) {
+    if (!tau || !delta) return DDEF_EINVAL;
+    if (!(v_g_bits > 0.0) || !(a_bps > 0.0) || !(b_s >= 0.0) || !(t_comp_s > 0.0)) return DDEF_EINVAL;
+    if (!std::isfinite(v_g_bits) || !std::isfinite(a_bps) || !std::isfinite(b_s) || !std::isfinite(t_comp_s))
+        return DDEF_EINVAL;
+    const double per_bit = a_bps / v_g_bits;               // fraction of the gradient sent per second
+    const double first = std::ceil((b_s + 1.0 / per_bit) / t_comp_s);
+    const double last = std::ceil(b_s / t_comp_s);
+    if (first > 4.0e9) return DDEF_EINVAL;
+    bool have = false;
+    double phi_min = INFINITY;
+    for (double cand = first; cand >= last; cand -= 1.0) {
+        double ratio = (cand * t_comp_s - b_s) * per_bit;   // transfer hidden behind tau compute slots
+        const double slot = t_comp_s * per_bit;             // transfer no longer than one compute slot
+        if (slot < ratio) ratio = slot;
+        if (ratio > 1.0) ratio = 1.0;
+        if (!(ratio > 0.0)) continue;
+        const double phi = (1.0 - ratio) / (ratio * std::pow(1.0 - ratio / 2.0, cand));
+        if (phi <= phi_min) { phi_min = phi; *tau = (uint32_t)cand; *delta = ratio; have = true; }
+    }
+    return have ? DDEF_OK : DDEF_EINVAL;
+}
+
+const char* ddef_strerror(int code) {
+    switch (code) {
+        case DDEF_OK: return "ok";
+        case DDEF_EINVAL: return "invalid argument";
+        case DDEF_ESTATE: return "call order violated";
+        case DDEF_ENOMEM: return "out of memory";
+        case DDEF_EHIP: return "HIP runtime error";
+        case DDEF_ENONFINITE: return "non-finite value";
+        default: return "unknown error";
+    }
+}
+
+int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
+    if (!out) return DDEF_EINVAL;
+    *out = nullptr;
+    if (d == 0 || d >= 0xFFFFE000ull || n == 0 || n > 65535u || tau_max > 4096u) return DDEF_EINVAL;
+    ddef_ctx* c = new (std::nothrow) ddef_ctx;
+    if (!c) return DDEF_ENOMEM;
+    int rc = DDEF_OK;
+    auto fail = [&](int code) { ddef_destroy(c); return code; };
+    hipError_t err = hipGetDevice(&c->device);
+    if (err != hipSuccess) return fail(DDEF_EHIP);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, c->device) == hipSuccess && prop.multiProcessorCount > 0)
+        c->cus = prop.multiProcessorCount;
+    c->d = d; c->n = n; c->tau_max = tau_max; c->tau = tau_max;
+    c->ld = (d + 4095u) & ~(uint64_t)4095u;
+    c->nchunks = (uint32_t)(c->ld / 4096u);
+    if (hipStreamCreateWithFlags(&c->own_stream, hipStreamNonBlocking) != hipSuccess) return fail(DDEF_EHIP);
+    c->stream = c->own_stream;
+    const size_t row = (size_t)c->ld * 4u;
+    struct Want { void** p; size_t bytes; };
+    Want wants[] = {
+        {(void**)&c->lambda, row}, {(void**)&c->xstar, row}, {(void**)&c->U, row},
+        {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
+        {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
+        {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
+    };
+    for (const Want& w : wants) {
+        err = hipMalloc(w.p, w.bytes);
+        if (err != hipSuccess) { (void)hipGetLastError(); return fail(err == hipErrorOutOfMemory ? DDEF_ENOMEM : DDEF_EHIP); }
+        err = hipMemsetAsync(*w.p, 0, w.bytes, c->stream);
+        if (err != hipSuccess) return fail(DDEF_EHIP);
+    }
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(DDEF_EHIP);
+    (void)rc;
+    *out = c;
+    return DDEF_OK;
+}
+
+int ddef_destroy(ddef_ctx* c) {
+    if (!c) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    if (c->stream) (void)hipStreamSynchronize(c->stream);
+    for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
+    void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
+                    c->cnt_eq, c->msg_idx, c->msg_val};
+    for (void* b : bufs) if (b) (void)hipFree(b);
+    if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
+    delete c;
+    return DDEF_OK;
+}
+
+int ddef_set_stream(ddef_ctx* c, void* hip_stream) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->stream = hip_stream ? (hipStream_t)hip_stream : c->own_stream;
+    return DDEF_OK;
+}
+
+int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xstar, const float* host_x0,
+                     uint64_t seed, int noise_kind, float noise_scale) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_lambda || !host_xstar || !host_x0) return DDEF_EINVAL;
+    if (noise_kind < DDEF_NOISE_NONE || noise_kind > DDEF_NOISE_STUDENT_T3) return DDEF_EINVAL;
+    if (!std::isfinite(noise_scale)) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const size_t bytes = (size_t)c->d * 4u;
+    HIP_TRY(c, hipMemcpy(c->lambda, host_lambda, bytes, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->xstar, host_xstar, bytes, hipMemcpyHostToDevice));
+    for (uint32_t s = 0; s <= c->tau_max; ++s)
+        HIP_TRY(c, hipMemcpy(c->ring + (uint64_t)s * c->ld, host_x0, bytes, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
+    HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
+    HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
+    c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
+    c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
+    c->full_selects = 0;
+    return DDEF_OK;
+}
+
+int ddef_set_tau(ddef_ctx* c, uint32_t tau) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (tau > c->tau_max) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    c->tau = tau;
+    return DDEF_OK;
+}
+
+int ddef_grad(ddef_ctx* c) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!c->problem_set || c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    c->step_empty = c->t < c->tau;
+    if (!c->step_empty) {
+        const uint64_t quads = (c->d + 3) / 4;
+        const uint32_t gx = blocks_for(c, (quads + 255) / 256, 1, 64);
+        LAUNCH(c, SL_GRAD, k_grad, dim3(gx), dim3(256), c->lambda, c->xstar, c->slot(c->t - c->tau), c->g,
+               c->ld, (uint32_t)c->d, c->n, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)c->t,
+               (uint32_t)(c->t >> 32), c->noise_kind, c->noise_scale);
+        HIP_TRY(c, hipGetLastError());
+    }
+    c->phase = PH_GRAD;
+    return DDEF_OK;
+}
+
+int ddef_load_grad(ddef_ctx* c, uint32_t worker, const float* host_g) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_g || worker >= c->n) return DDEF_EINVAL;
+    if (!c->problem_set || (c->phase != PH_IDLE && c->phase != PH_GRAD)) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    rc = copy_row_in(c, c->g + (uint64_t)worker * c->ld, host_g);
+    if (rc) return rc;
+    c->step_empty = false;
+    c->phase = PH_GRAD;
+    return DDEF_OK;
+}
+
+int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!(delta > 0.0) || !(delta <= 1.0) || !std::isfinite(lr)) return DDEF_EINVAL;
+    if (c->phase != PH_GRAD) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    c->lr_step = lr;
+    if (c->step_empty) {
+        c->k_step = 0;
+        c->phase = PH_COMPRESSED;
+        return DDEF_OK;
+    }
+    const uint64_t k = ddef_k_from_delta(delta, c->d);
+    rc = ensure_message_capacity(c, k);
+    if (rc) return rc;
+    uint64_t kb = k * (uint64_t)c->opt_slack_x16 / 16u;
+    if (kb < k) kb = k;
+    if (kb > c->d) kb = c->d;
+    const uint32_t tiles = (uint32_t)((c->d + 1023) / 1024);
+    const uint32_t gx = blocks_for(c, tiles, c->n, 8);
+    LAUNCH(c, SL_EF_ACCUM, k_ef_accumulate, dim3(gx, c->n), dim3(256), c->e, c->g, c->ld, (uint32_t)c->d, lr);
+    enqueue_full_select(c, (uint32_t)k, (uint32_t)kb);
+    HIP_TRY(c, hipGetLastError());
+    c->k_step = k;
+    c->phase = PH_COMPRESSED;
+    return DDEF_OK;
+}
+
+int ddef_aggregate(ddef_ctx* c) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (c->phase != PH_COMPRESSED) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    const uint64_t words = c->ld;
+    LAUNCH(c, SL_FILL, k_fill_u32, dim3(blocks_for(c, (words + 255) / 256, 1, 32)), dim3(256),
+           (uint32_t*)c->U, words, 0u);
+    if (c->k_step) {
+        const uint32_t k = (uint32_t)c->k_step;
+        const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
+        for (uint32_t i = 0; i < c->n; ++i)
+            LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U,
+                   c->msg_idx + (uint64_t)i * c->msg_ld, c->msg_val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
+    }
+    HIP_TRY(c, hipGetLastError());
+    c->phase = PH_AGGREGATED;
+    return DDEF_OK;
+}
+
+int ddef_apply_delayed(ddef_ctx* c, float lr) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (c->phase != PH_AGGREGATED) return DDEF_ESTATE;
+    if (std::memcmp(&lr, &c->lr_step, sizeof(float)) != 0) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    const uint64_t quads = (c->d + 3) / 4;
+    LAUNCH(c, SL_APPLY, k_apply, dim3(blocks_for(c, (quads + 255) / 256, 1, 32)), dim3(256), c->slot(c->t),
+           c->U, c->slot(c->t + 1), (uint32_t)c->d, (float)c->n);
+    HIP_TRY(c, hipGetLastError());
+    c->t += 1;
+    c->phase = PH_IDLE;
+    return DDEF_OK;
+}
+
+int ddef_sync(ddef_ctx* c) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return DDEF_OK;
+}
+
+int ddef_step_index(ddef_ctx* c, uint64_t* t) {
+    if (!c || !t) return DDEF_EINVAL;
+    *t = c->t;
+    return DDEF_OK;
+}
+
+int ddef_get_model(ddef_ctx* c, float* host_x) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_x) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    return copy_row_out(c, c->slot(c->t), host_x);
+}
+
+int ddef_set_model(ddef_ctx* c, const float* host_x) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_x) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    return copy_row_in(c, c->slot(c->t), host_x);
+}
+
+int ddef_get_error(ddef_ctx* c, uint32_t worker, float* host_e) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_e || worker >= c->n) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    return copy_row_out(c, c->e + (uint64_t)worker * c->ld, host_e);
+}
+
+int ddef_set_error(ddef_ctx* c, uint32_t worker, const float* host_e) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_e || worker >= c->n) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE && c->phase != PH_GRAD) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    return copy_row_in(c, c->e + (uint64_t)worker * c->ld, host_e);
+}
+
+int ddef_get_grad(ddef_ctx* c, uint32_t worker, float* host_g) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_g || worker >= c->n) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    return copy_row_out(c, c->g + (uint64_t)worker * c->ld, host_g);
+}
+
+int ddef_get_update(ddef_ctx* c, float* host_U) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_U) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    return copy_row_out(c, c->U, host_U);
+}
+
+int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* host_val, uint64_t* k) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!k || worker >= c->n) return DDEF_EINVAL;
+    if (c->phase != PH_COMPRESSED && c->phase != PH_AGGREGATED && c->phase != PH_IDLE) return DDEF_ESTATE;
+    *k = c->k_step;
+    if (!host_idx || !host_val || c->k_step == 0) return DDEF_OK;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host_idx, c->msg_idx + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
+                         hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(host_val, c->msg_val + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
+                         hipMemcpyDeviceToHost));
+    return DDEF_OK;
+}
+
+int ddef_get_threshold(ddef_ctx* c, uint32_t worker, uint32_t* T, uint64_t* r) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!T || !r || worker >= c->n) return DDEF_EINVAL;
+    if (c->k_step == 0) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    SelState s;
+    HIP_TRY(c, hipMemcpy(&s, c->sel + worker, sizeof(SelState), hipMemcpyDeviceToHost));
+    *T = s.T;
+    *r = s.r;
+    return DDEF_OK;
+}
+
+int ddef_profile_enable(ddef_ctx* c, int on) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    DeviceGuard guard(c->device);
+    rc = resolve_profile(c);
+    if (rc) return rc;
+    if (on) {
+        for (int s = 0; s < SL_COUNT; ++s) { c->prof_launches[s] = 0; c->prof_ms[s] = 0.0; }
+    }
+    c->profiling = on != 0;
+    return DDEF_OK;
+}
+
+int ddef_profile_slots(void) { return SL_COUNT; }
+
+int ddef_profile_read(ddef_ctx* c, int slot, const char** name, uint64_t* launches, double* total_ms) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (slot < 0 || slot >= SL_COUNT) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    rc = resolve_profile(c);
+    if (rc) return rc;
+    if (name) *name = kSlotNames[slot];
+    if (launches) *launches = c->prof_launches[slot];
+    if (total_ms) *total_ms = c->prof_ms[slot];
+    return DDEF_OK;
+}
+
+int ddef_full_select_count(ddef_ctx* c, uint64_t* count) {
+    if (!c || !count) return DDEF_EINVAL;
+    *count = c->full_selects;
+    return DDEF_OK;
+}
+
+int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    switch (option) {
+        case DDEF_OPT_FORCE_FULL_SELECT: c->opt_force_full = value != 0; return DDEF_OK;
+        case DDEF_OPT_CANDIDATE_SLACK_X16:
+            if (value < 16 || value > 1024) return DDEF_EINVAL;
+            c->opt_slack_x16 = value;
+            return DDEF_OK;
+        default: return DDEF_EINVAL;
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,498 @@
+// Device kernels of the DD-EF-SGD hot path for gfx950 (wave64).
+//
+// Layout in HBM: every length-d vector lives in a row of `ld` floats (d rounded up to the
+// 4096-element chunk), so rows of e[n][ld], g[n][ld] and the snapshot ring start 16 KiB
+// aligned and every 16-byte access of a row stays inside the row's allocation.  Entries
+// past d are never counted, selected or compared.
+//
+// Everything here is HBM-bound streaming, histogramming in LDS, wave ballots and prefix
+// scans; there is no dense contraction, hence no MFMA.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ddef_kernels.h"
+
+namespace ddef {
+
+// ------------------------------------------------------------------------------------
+// small device helpers
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+// number of set bits of `mask` strictly below this lane
+__device__ __forceinline__ uint32_t mask_rank(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t up = __shfl_up(v, off, 64);
+        if (lane_id() >= (uint32_t)off) v += up;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Exclusive prefix of `v` over the block in thread order; *total receives the block sum.
+// `lds` holds at least blockDim.x/64 + 1 words.  Contains two barriers; every thread of the
+// block must call it.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds, uint32_t* total) {
+    const uint32_t wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    uint32_t incl = wave_incl_scan(v);
+    if (lane_id() == 63u) lds[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (uint32_t w = 0; w < nw; ++w) {
+        uint32_t s = lds[w];
+        if (w < wave) before += s;
+        all += s;
+    }
+    __syncthreads();
+    *total = all;
+    return before + incl - v;
+}
+
+typedef float vec4f __attribute__((ext_vector_type(4)));
+
+// 16-byte load that does not displace reusable lines from the caches (streamed-once data)
+__device__ __forceinline__ float4 load_stream4(const float* p) {
+    const vec4f v = __builtin_nontemporal_load(reinterpret_cast<const vec4f*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ uint32_t mag_key(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+// ------------------------------------------------------------------------------------
+// gradient noise: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller out of +,-,*,/,sqrt.
+// Every fp32 operation is written out and rounded on its own (the file is compiled with
+// contraction off) so that the CPU can reproduce each draw bit for bit.
+// ------------------------------------------------------------------------------------
+struct U4 { uint32_t a, b, c, d; };
+
+__device__ __forceinline__ U4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                           uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t y0 = hi1 ^ c1 ^ k0, y2 = hi0 ^ c3 ^ k1;
+        c0 = y0; c1 = lo1; c2 = y2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// -2 ln u, u = ((w >> 8) + 1) 2^-24: split off the exponent, fold the mantissa into
+// (sqrt 1/2, sqrt 2], ln m = 2 atanh s with s = (m-1)/(m+1), odd series up to s^9.
+__device__ __forceinline__ float radius_sq(uint32_t w) {
+    const uint32_t fb = __float_as_uint((float)((w >> 8) + 1u));
+    int ex = (int)(fb >> 23) - 127;
+    const uint32_t mant = fb & 0x7fffffu;
+    float m = __uint_as_float(mant | 0x3f800000u);
+    if (mant > 0x3504f3u) { m = m * 0.5f; ex += 1; }
+    const float s = (m - 1.0f) / (m + 1.0f);
+    const float s2 = s * s;
+    float h = 1.0f / 9.0f;
+    h = h * s2 + 1.0f / 7.0f;
+    h = h * s2 + 1.0f / 5.0f;
+    h = h * s2 + 1.0f / 3.0f;
+    h = h * s2 + 1.0f;
+    const float lnm = (2.0f * s) * h;
+    float v = (float)(24 - ex) * 0x1.62e43p-1f - lnm;
+    v = v < 0.0f ? 0.0f : v;
+    return 2.0f * v;
+}
+
+// (cos, sin) of 2 pi ((w >> 8) + 1/2) 2^-24: quadrant after an eighth-turn shift, Taylor
+// series on (-pi/4, pi/4).
+__device__ __forceinline__ void circle_point(uint32_t w, float& co, float& si) {
+    const uint32_t b = ((w >> 8) + 0x200000u) & 0xffffffu;
+    const uint32_t quad = b >> 22;
+    const int rem = (int)(b & 0x3fffffu) - 0x200000;
+    const float phi = (float)(2 * rem + 1) * 0x1.921fb6p-23f;
+    const float p2 = phi * phi;
+    float a = 1.0f / 362880.0f;
+    a = a * p2 - 1.0f / 5040.0f;
+    a = a * p2 + 1.0f / 120.0f;
+    a = a * p2 - 1.0f / 6.0f;
+    a = a * p2 + 1.0f;
+    const float s = phi * a;
+    float c = -1.0f / 3628800.0f;
+    c = c * p2 + 1.0f / 40320.0f;
+    c = c * p2 - 1.0f / 720.0f;
+    c = c * p2 + 1.0f / 24.0f;
+    c = c * p2 - 0.5f;
+    c = c * p2 + 1.0f;
+    co = (quad == 0u) ? c : (quad == 1u) ? -s : (quad == 2u) ? -c : s;
+    si = (quad == 0u) ? s : (quad == 1u) ? c : (quad == 2u) ? -s : -c;
+}
+
+__device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
+                                        uint32_t seed_lo, uint32_t seed_hi, int kind) {
+    const U4 w = philox_block(j, worker, t_lo, t_hi, seed_lo, seed_hi);
+    float c01, s01;
+    const float r01 = __builtin_sqrtf(radius_sq(w.a));
+    circle_point(w.b, c01, s01);
+    const float z0 = r01 * c01;
+    if (kind == 1) return z0;
+    const float z1 = r01 * s01;
+    float c23, s23;
+    const float r23 = __builtin_sqrtf(radius_sq(w.c));
+    circle_point(w.d, c23, s23);
+    const float z2 = r23 * c23, z3 = r23 * s23;
+    const float q = ((z1 * z1 + z2 * z2) + z3 * z3) / 3.0f;
+    const float den = __builtin_sqrtf(q);
+    return den == 0.0f ? 0.0f : z0 / den;
+}
+
+// ------------------------------------------------------------------------------------
+// S0  g_i = lambda * (x_{t-tau} - x*) + scale * z      (Assumption 2; stale iterate)
+// One thread owns four consecutive coordinates and loops over the workers, so lambda,
+// x* and the snapshot are read once for all n workers.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_grad(const float* __restrict__ lambda,
+                                              const float* __restrict__ xstar,
+                                              const float* __restrict__ xs, float* __restrict__ g,
+                                              uint64_t ld, uint32_t d, uint32_t n, uint32_t seed_lo,
+                                              uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi,
+                                              int kind, float scale) {
+    const uint32_t quads = (d + 3u) >> 2;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+        const uint32_t j = q << 2;
+        const float4 lam = *reinterpret_cast<const float4*>(lambda + j);
+        const float4 xo = *reinterpret_cast<const float4*>(xstar + j);
+        const float4 xv = *reinterpret_cast<const float4*>(xs + j);
+        float mean[4];
+        mean[0] = lam.x * (xv.x - xo.x);
+        mean[1] = lam.y * (xv.y - xo.y);
+        mean[2] = lam.z * (xv.z - xo.z);
+        mean[3] = lam.w * (xv.w - xo.w);
+        for (uint32_t i = 0; i < n; ++i) {
+            float out[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float xi = 0.0f;
+                if (kind != 0) xi = scale * draw_z(j + c, i, t_lo, t_hi, seed_lo, seed_hi, kind);
+                out[c] = (j + c < d) ? mean[c] + xi : 0.0f;      // keep the row padding at zero
+            }
+            *reinterpret_cast<float4*>(g + (uint64_t)i * ld + j) = make_float4(out[0], out[1], out[2], out[3]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// S1  p = e + lr * g, written over e                         (Algorithm 1, worker side)
+// grid (gx, n): blockIdx.y is the worker, blocks stride over 1024-element tiles.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ef_accumulate(float* __restrict__ e,
+                                                       const float* __restrict__ g, uint64_t ld,
+                                                       uint32_t d, float lr) {
+    const uint32_t quads = (d + 3u) >> 2;
+    float* er = e + (uint64_t)blockIdx.y * ld;
+    const float* gr = g + (uint64_t)blockIdx.y * ld;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+        const float4 ev = reinterpret_cast<const float4*>(er)[q];
+        const float4 gv = load_stream4(gr + ((uint64_t)q << 2));
+        float4 p;
+        p.x = ev.x + lr * gv.x;
+        p.y = ev.y + lr * gv.y;
+        p.z = ev.z + lr * gv.z;
+        p.w = ev.w + lr * gv.w;
+        reinterpret_cast<float4*>(er)[q] = p;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// S2  radix select of the k-th entry under (|v| descending, index ascending), done on the
+// 31-bit magnitude pattern in three digits of 11, 10 and 10 bits, for two ranks at once:
+// rank 0 is k (gives the threshold T and r), rank 1 is the candidate target used to place
+// the next iteration's filter bound.
+// ------------------------------------------------------------------------------------
+// digit geometry per level: bits [hi, lo)
+__device__ __forceinline__ uint32_t lvl_lo(int level) { return level == 0 ? 20u : level == 1 ? 10u : 0u; }
+__device__ __forceinline__ uint32_t lvl_hi(int level) { return level == 0 ? 31u : level == 1 ? 20u : 10u; }
+__device__ __forceinline__ uint32_t lvl_bins(int level) { return level == 0 ? 2048u : 1024u; }
+
+// Histogram of one digit over a worker's row (values = fp32 entries of `src` row, `count`
+// valid entries taken from cnt_fixed, or from cnt_dev[worker] when cnt_dev is not null).
+// Level 0 builds one histogram shared by both ranks; levels 1, 2 build one per rank, over the
+// entries whose higher bits match that rank's prefix.  hist layout: [worker][2][2048].
+// Workers whose `active` flag is 0 are skipped.
+__global__ __launch_bounds__(256) void k_digit_hist(const float* __restrict__ src, uint64_t ld,
+                                                    uint32_t cnt_fixed,
+                                                    const uint32_t* __restrict__ cnt_dev,
+                                                    const SelState* __restrict__ sel,
+                                                    uint32_t* __restrict__ hist, int level) {
+    __shared__ uint32_t h[2][2048];
+    const uint32_t w = blockIdx.y;
+    if (!sel[w].active) return;
+    const uint32_t count = cnt_dev ? cnt_dev[w] : cnt_fixed;
+    const uint32_t lo = lvl_lo(level), hi = lvl_hi(level), bins = lvl_bins(level);
+    const int nrank = level == 0 ? 1 : 2;
+    for (uint32_t b = threadIdx.x; b < 2048u; b += blockDim.x) { h[0][b] = 0; h[1][b] = 0; }
+    __syncthreads();
+    const uint32_t pre0 = sel[w].prefix[0] >> hi, pre1 = sel[w].prefix[1] >> hi;
+    const float* row = src + (uint64_t)w * ld;
+    const uint32_t quads = (count + 3u) >> 2;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+        const float4 v = reinterpret_cast<const float4*>(row)[q];
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t j = q << 2;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (j + c < count) {
+                const uint32_t key = mag_key(vv[c]);
+                const uint32_t digit = (key >> lo) & (bins - 1u);
+                if (level == 0) {
+                    atomicAdd(&h[0][digit], 1u);
+                } else {
+                    if ((key >> hi) == pre0) atomicAdd(&h[0][digit], 1u);
+                    if ((key >> hi) == pre1) atomicAdd(&h[1][digit], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* out = hist + (uint64_t)w * 2u * 2048u;
+    for (int r = 0; r < nrank; ++r)
+        for (uint32_t b = threadIdx.x; b < bins; b += blockDim.x) {
+            const uint32_t c = h[r][b];
+            if (c) atomicAdd(&out[r * 2048u + b], c);
+        }
+}
+
+// Pick the digit holding each rank: grid (n, 2), block 256.  For rank `rk`, walks the
+// histogram from the top digit down until the running count reaches krem[rk]; appends the
+// digit to prefix[rk] and reduces krem[rk] by the count of the digits above it.  After the
+// last level publishes T, r (rank 0) and the bound for the next filter (rank 1).
+__global__ __launch_bounds__(256) void k_digit_pick(SelState* __restrict__ sel,
+                                                    uint32_t* __restrict__ hist, int level) {
+    __shared__ uint32_t lds[8];
+    __shared__ uint32_t found_digit, found_above;
+    const uint32_t w = blockIdx.x, rk = blockIdx.y;
+    if (!sel[w].active) return;
+    const uint32_t bins = lvl_bins(level), lo = lvl_lo(level);
+    const uint32_t per = bins / 256u;
+    // level 0 has a single histogram (slot 0) read by both ranks
+    uint32_t* hsrc = hist + (uint64_t)w * 2u * 2048u + (level == 0 ? 0u : rk * 2048u);
+    const uint32_t krem = sel[w].krem[rk];
+    if (threadIdx.x == 0) { found_digit = 0; found_above = 0; }
+    // thread 0 owns the top `per` digits
+    const uint32_t top = bins - threadIdx.x * per;      // exclusive upper digit of this thread
+    uint32_t mine = 0;
+    for (uint32_t q = 0; q < per; ++q) mine += hsrc[top - 1u - q];
+    uint32_t total;
+    const uint32_t above = block_excl_scan(mine, lds, &total);
+    if (above < krem && krem <= above + mine) {
+        uint32_t run = above;
+        for (uint32_t q = 0; q < per; ++q) {
+            const uint32_t c = hsrc[top - 1u - q];
+            if (krem <= run + c) { found_digit = top - 1u - q; found_above = run; break; }
+            run += c;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t pre = sel[w].prefix[rk] | (found_digit << lo);
+        const uint32_t rem = krem - found_above;
+        sel[w].prefix[rk] = pre;
+        sel[w].krem[rk] = rem;
+        if (level == 2) {
+            if (rk == 0) { sel[w].T = pre; sel[w].r = rem; }
+            else sel[w].next_bound = pre;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// S3  ordered compaction over the whole row, given (T, r): count per 4096-element chunk,
+// scan over chunks, emit.  An entry is sent iff key > T, or key == T and fewer than r
+// entries with key == T precede it in index order.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_chunk_count(const float* __restrict__ e, uint64_t ld,
+                                                     uint32_t d, const SelState* __restrict__ sel,
+                                                     uint32_t* __restrict__ cnt_gt,
+                                                     uint32_t* __restrict__ cnt_eq, uint32_t nchunks) {
+    __shared__ uint32_t red[8];
+    const uint32_t w = blockIdx.y;
+    if (!sel[w].active) return;
+    const uint32_t T = sel[w].T;
+    const float* row = e + (uint64_t)w * ld;
+    for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t j = c * 4096u + s * 1024u + threadIdx.x * 4u;
+            if (j < d) {
+                const float4 v = *reinterpret_cast<const float4*>(row + j);
+                const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    if (j + m < d) {
+                        const uint32_t key = mag_key(vv[m]);
+                        gt += key > T;
+                        eq += key == T;
+                    }
+            }
+        }
+        const uint32_t wave_gt = wave_sum(gt), wave_eq = wave_sum(eq);
+        if (lane_id() == 0) { red[threadIdx.x >> 6] = wave_gt; red[4 + (threadIdx.x >> 6)] = wave_eq; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            cnt_gt[(uint64_t)w * nchunks + c] = red[0] + red[1] + red[2] + red[3];
+            cnt_eq[(uint64_t)w * nchunks + c] = red[4] + red[5] + red[6] + red[7];
+        }
+        __syncthreads();
+    }
+}
+
+// One block of 1024 threads per worker walks the chunk counts in order and turns them into
+// eq_before[c] (entries equal to T before chunk c) and out_base[c] (message offset of the
+// chunk's first sent entry).  In place: cnt_eq -> eq_before, cnt_gt -> out_base.
+__global__ __launch_bounds__(1024) void k_chunk_scan(const SelState* __restrict__ sel,
+                                                     uint32_t* __restrict__ cnt_gt,
+                                                     uint32_t* __restrict__ cnt_eq, uint32_t nchunks) {
+    __shared__ uint32_t lds[17];
+    const uint32_t w = blockIdx.x;
+    if (!sel[w].active) return;
+    const uint32_t r = sel[w].r;
+    uint32_t* gtp = cnt_gt + (uint64_t)w * nchunks;
+    uint32_t* eqp = cnt_eq + (uint64_t)w * nchunks;
+    uint32_t eq_carry = 0, out_carry = 0;
+    for (uint32_t base = 0; base < nchunks; base += 1024u) {
+        const uint32_t c = base + threadIdx.x;
+        const uint32_t gt = c < nchunks ? gtp[c] : 0u;
+        const uint32_t eq = c < nchunks ? eqp[c] : 0u;
+        uint32_t eq_total, out_total;
+        const uint32_t eq_before = eq_carry + block_excl_scan(eq, lds, &eq_total);
+        const uint32_t room = r > eq_before ? r - eq_before : 0u;
+        const uint32_t sent = gt + (eq < room ? eq : room);
+        const uint32_t out_base = out_carry + block_excl_scan(sent, lds, &out_total);
+        if (c < nchunks) { eqp[c] = eq_before; gtp[c] = out_base; }
+        eq_carry += eq_total;
+        out_carry += out_total;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_chunk_emit(float* __restrict__ e, uint64_t ld, uint32_t d,
+                                                    const SelState* __restrict__ sel,
+                                                    const uint32_t* __restrict__ out_base,
+                                                    const uint32_t* __restrict__ eq_before,
+                                                    uint32_t nchunks, uint32_t* __restrict__ msg_idx,
+                                                    float* __restrict__ msg_val, uint64_t msg_ld,
+                                                    uint32_t k) {
+    __shared__ uint32_t lds[5];
+    const uint32_t w = blockIdx.y;
+    if (!sel[w].active) return;
+    const uint32_t T = sel[w].T, r = sel[w].r;
+    float* row = e + (uint64_t)w * ld;
+    uint32_t* oi = msg_idx + (uint64_t)w * msg_ld;
+    float* ov = msg_val + (uint64_t)w * msg_ld;
+    for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        uint32_t eq_run = eq_before[(uint64_t)w * nchunks + c];
+        uint32_t out_run = out_base[(uint64_t)w * nchunks + c];
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t j = c * 4096u + s * 1024u + threadIdx.x * 4u;
+            float vv[4] = {0.f, 0.f, 0.f, 0.f};
+            uint32_t key[4] = {0, 0, 0, 0};
+            bool valid[4] = {false, false, false, false};
+            if (j < d) {
+                const float4 v = *reinterpret_cast<const float4*>(row + j);
+                vv[0] = v.x; vv[1] = v.y; vv[2] = v.z; vv[3] = v.w;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) { valid[m] = j + m < d; key[m] = mag_key(vv[m]); }
+            }
+            uint32_t neq = 0;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) neq += valid[m] && key[m] == T;
+            uint32_t eq_total;
+            uint32_t eq_rank = eq_run + block_excl_scan(neq, lds, &eq_total);
+            bool send[4];
+            uint32_t nsend = 0;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                bool take = false;
+                if (valid[m]) {
+                    if (key[m] > T) take = true;
+                    else if (key[m] == T) { take = eq_rank < r; ++eq_rank; }
+                }
+                send[m] = take;
+                nsend += take;
+            }
+            uint32_t send_total;
+            uint32_t pos = out_run + block_excl_scan(nsend, lds, &send_total);
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                if (send[m]) {
+                    if (pos < k) { oi[pos] = j + m; ov[pos] = vv[m]; }
+                    ++pos;
+                    row[j + m] = 0.0f;
+                }
+            eq_run += eq_total;
+            out_run += send_total;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// S4  U += Delta_i for one worker (launched once per worker, in worker order, on one
+// stream: indices inside one message are distinct, so plain read-modify-write is exact
+// and the summation order is the worker order).
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_scatter_add(float* __restrict__ U,
+                                                     const uint32_t* __restrict__ idx,
+                                                     const float* __restrict__ val, uint32_t k,
+                                                     uint32_t d) {
+    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
+        const uint32_t j = idx[m];
+        if (j < d) U[j] = U[j] + val[m];
+    }
+}
+
+// S5  x_{t+1} = x_t - U / n, written into the next ring slot (may alias x_t when the ring
+// has a single slot: element-wise, so in place is fine).
+__global__ __launch_bounds__(256) void k_apply(const float* x, const float* __restrict__ U,
+                                               float* xn, uint32_t d, float nf) {
+    const uint32_t quads = (d + 3u) >> 2;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+        const float4 xv = reinterpret_cast<const float4*>(x)[q];
+        const float4 uv = reinterpret_cast<const float4*>(U)[q];
+        float4 o;
+        o.x = xv.x - uv.x / nf;
+        o.y = xv.y - uv.y / nf;
+        o.z = xv.z - uv.z / nf;
+        o.w = xv.w - uv.w / nf;
+        reinterpret_cast<float4*>(xn)[q] = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value) {
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < count;
+         q += (uint64_t)gridDim.x * blockDim.x)
+        p[q] = value;
+}
+
+__global__ __launch_bounds__(256) void k_copy_f4(const float* __restrict__ src, float* __restrict__ dst,
+                                                 uint64_t quads) {
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads;
+         q += (uint64_t)gridDim.x * blockDim.x)
+        reinterpret_cast<float4*>(dst)[q] = reinterpret_cast<const float4*>(src)[q];
+}
+
+// Start of a selection: rank 0 looks for the k-th entry, rank 1 for the kb-th.
+__global__ void k_sel_begin(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t all_active) {
+    const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= n) return;
+    if (all_active) sel[w].active = 1;
+    sel[w].prefix[0] = 0; sel[w].prefix[1] = 0;
+    sel[w].krem[0] = k; sel[w].krem[1] = kb;
+}
+
+}  // namespace ddef

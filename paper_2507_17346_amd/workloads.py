@@ -159,8 +159,9 @@ def random_vector(seed: int, d: int, kind: str = "normal") -> np.ndarray:
         bits = rng.integers(0, 1 << 12, size=d, dtype=np.uint32)
         bits |= rng.integers(0, 2, size=d, dtype=np.uint32) << np.uint32(31)
         return bits.view(np.float32)
-    if kind == "wide":             # magnitudes over the whole finite exponent range
-        bits = rng.integers(0, 0x7F800000, size=d, dtype=np.uint32)
+    if kind == "wide":             # magnitudes over (almost) the whole finite exponent range;
+        # the top is left free so that a handful of such vectors can be summed without overflow
+        bits = rng.integers(0, 0x7D800000, size=d, dtype=np.uint32)
         bits |= rng.integers(0, 2, size=d, dtype=np.uint32) << np.uint32(31)
         return bits.view(np.float32)
     raise ValueError(kind)

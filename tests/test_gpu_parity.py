@@ -1,0 +1,277 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the same
+seeded inputs.  Bar: selected indices, message values, error buffers and gradients bit-exact;
+the aggregated update and the model bit-exact too (the GPU sums in worker order like the
+oracle), asserted at the stated tolerance of 1e-6 relative and reported when not exact."""
+import numpy as np
+import pytest
+
+from paper_2507_17346_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+
+
+def bits(a):
+    return np.asarray(a, dtype=F32).view(np.uint32)
+
+
+def rel_err(a, b):
+    """max |a-b| / max(|b|, 1e-3 * ||b||_inf): the floor keeps exact zeros of b comparable."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    floor = 1e-3 * max(np.abs(b).max(), 1e-30)
+    return float((np.abs(a - b) / np.maximum(np.abs(b), floor)).max())
+
+
+@pytest.fixture(scope="module")
+def ddef():
+    from paper_2507_17346_amd import binding
+    binding.load()
+    return binding
+
+
+def make_pair(ddef, oracle_mod, w, tau=None, tau_max=None, threads=4):
+    lam, xstar, x0 = workloads.make_problem(w)
+    tau = w.tau if tau is None else tau
+    tau_max = max(tau, w.tau_max) if tau_max is None else tau_max
+    g = ddef.Context(w.d, w.n, tau_max)
+    g.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    g.set_tau(tau)
+    o = oracle_mod.Oracle(w.d, w.n, tau_max, threads=threads)
+    o.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    o.set_tau(tau)
+    return g, o, (lam, xstar, x0)
+
+
+def assert_step_state_equal(g, o, n, check_grad=True, what=""):
+    for i in range(n):
+        gi, gv = g.get_message(i)
+        oi, ov = o.get_message(i)
+        assert len(gi) == len(oi), (what, i)
+        assert np.array_equal(gi, oi), (what, "indices", i)
+        assert np.array_equal(bits(gv), bits(ov)), (what, "values", i)
+        assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), (what, "error buffer", i)
+        if len(oi):
+            assert g.get_threshold(i) == o.get_threshold(i), (what, "threshold", i)
+            if check_grad:
+                assert np.array_equal(bits(g.get_grad(i)), bits(o.get_grad(i))), (what, "gradient", i)
+
+
+def assert_model_equal(g, o, what=""):
+    gu, ou = g.get_update(), o.get_update()
+    gx, ox = g.get_model(), o.get_model()
+    assert rel_err(gu, ou) <= 1e-6, what
+    assert rel_err(gx, ox) <= 1e-6, what
+    # worker-ordered summation on both sides: expected to agree to the bit
+    assert np.array_equal(bits(gu), bits(ou)), what
+    assert np.array_equal(bits(gx), bits(ox)), what
+
+
+# ---- S0: gradient with counter-based noise -------------------------------------------------
+@pytest.mark.parametrize("kind,scale", [(1, 0.1), (2, 0.05), (0, 0.0)])
+@pytest.mark.parametrize("d", [1, 5, 4097, 300_001])
+def test_gradient_bit_exact(ddef, oracle_mod, kind, scale, d):
+    w = workloads.replace(workloads.get("C1", d=d, n=3), noise_kind=kind, noise_scale=scale, seed=0xABCDEF0123)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=0)
+    for _ in range(2):
+        g.grad()
+        o.grad()
+        for i in range(w.n):
+            assert np.array_equal(bits(g.get_grad(i)), bits(o.get_grad(i))), (kind, d, i)
+        g.ef_compress(0.5, 0.05); g.aggregate(); g.apply_delayed(0.05)
+        o.ef_compress(0.5, 0.05); o.aggregate(); o.apply_delayed()
+    g.close()
+
+
+def test_gradient_noise_far_counters(ddef, oracle_mod):
+    # step index beyond 2^32 is not reachable by stepping; large j and several workers are
+    w = workloads.replace(workloads.get("C3", d=70_001, n=5), seed=(0xFEEDFACE << 32) | 0x1234)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=0)
+    for _ in range(3):
+        g.step(0.01, 0.05)
+        o.step(0.01, 0.05)
+    g.grad(); o.grad()
+    for i in range(w.n):
+        assert np.array_equal(bits(g.get_grad(i)), bits(o.get_grad(i)))
+    g.close()
+
+
+# ---- S1-S3: error feedback + Top-k on crafted inputs -----------------------------------------
+KINDS = ["normal", "heavy", "few_values", "all_equal", "signed_zero", "denormal", "wide"]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("d", [1, 3, 1023, 4096, 4097, 20_000])
+def test_compress_crafted_vectors(ddef, oracle_mod, kind, d):
+    n = 2
+    g = ddef.Context(d, n, 0)
+    o = oracle_mod.Oracle(d, n, 0)
+    zero = np.zeros(d, dtype=F32)
+    for h in (g, o):
+        h.set_problem(np.ones(d, dtype=F32), zero, zero, 1, 0, 0.0)
+    ks = sorted({1, max(1, d // 1000), max(1, d // 7), max(1, d - 1), d})
+    for step, k in enumerate(ks):
+        delta = k / d if k < d else 1.0
+        assert oracle_mod.k_from_delta(delta, d) == k == ddef.k_from_delta(delta, d)
+        for i in range(n):
+            v = workloads.random_vector(1000 * step + 10 * i + d, d, kind)
+            g.load_grad(i, v)
+            o.load_grad(i, v)
+        g.ef_compress(delta, 1.0)
+        o.ef_compress(delta, 1.0)
+        assert_step_state_equal(g, o, n, check_grad=False, what=(kind, d, k))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(1.0); o.apply_delayed()
+        assert_model_equal(g, o, what=(kind, d, k))
+    g.close()
+
+
+def test_compress_ties_across_chunks(ddef, oracle_mod):
+    # the threshold group straddles several 4096-element chunks and only part of it is sent
+    d, n = 40_000, 1
+    v = np.full(d, 0.25, dtype=F32)
+    v[::3] = -0.25
+    v[5::1000] = 2.0
+    g = ddef.Context(d, n, 0)
+    o = oracle_mod.Oracle(d, n, 0)
+    zero = np.zeros(d, dtype=F32)
+    for h in (g, o):
+        h.set_problem(np.ones(d, dtype=F32), zero, zero, 1, 0, 0.0)
+    for k in [1, 39, 40, 41, 5000, 12_345, 39_999, 40_000]:
+        g.load_grad(0, v); o.load_grad(0, v)
+        g.ef_compress(k / d, 1.0); o.ef_compress(k / d, 1.0)
+        assert_step_state_equal(g, o, n, check_grad=False, what=k)
+        g.aggregate(); o.aggregate(); g.apply_delayed(1.0); o.apply_delayed()
+    g.close()
+
+
+# ---- whole trajectories, free running ----------------------------------------------------------
+@pytest.mark.parametrize("name,d,n,tau,delta,steps", [
+    ("C1", 50_000, 4, 2, 0.01, 12),
+    ("C1", 9_999, 1, 0, 0.05, 8),
+    ("C2", 200_003, 8, 4, 0.01, 10),
+    ("C3", 150_001, 8, 3, 0.001, 9),
+    ("C4", 131_072, 4, 1, 0.1, 6),
+    ("C1", 4_096, 3, 5, 1.0, 9),
+])
+def test_trajectory_free_running(ddef, oracle_mod, name, d, n, tau, delta, steps):
+    w = workloads.get(name, d=d, n=n)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=tau)
+    for t in range(steps):
+        g.grad(); o.grad()
+        g.ef_compress(delta, w.lr); o.ef_compress(delta, w.lr)
+        assert_step_state_equal(g, o, n, check_grad=(t >= tau), what=(name, t))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert g.t == o.t == t + 1
+        assert_model_equal(g, o, what=(name, t))
+    g.close()
+
+
+def test_c1_full_configuration(ddef, oracle_mod):
+    w = workloads.get("C1")
+    g, o, _ = make_pair(ddef, oracle_mod, w, threads=4)
+    for t in range(w.steps):
+        g.step(w.deltas[0], w.lr)
+        o.step(w.deltas[0], w.lr)
+        if t in (2, 3, 10, w.steps - 1):
+            assert_step_state_equal(g, o, w.n, what=("C1", t))
+            assert_model_equal(g, o, what=("C1", t))
+    g.close()
+
+
+def test_adaptive_schedule_changing_delta_and_tau(ddef, oracle_mod):
+    # Algorithm 2: (delta, tau) re-chosen every E iterations.  Shrunk version of the adaptive
+    # workload; the schedule comes from the library's DeCo on the seeded network trace.
+    w = workloads.get("C5", d=120_000, n=4)
+    w = workloads.replace(w, steps=40, adaptive_period=5)
+    trace = workloads.network_trace(w)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=0, tau_max=w.tau_max)
+    for t in range(w.steps):
+        if t % w.adaptive_period == 0:
+            p = t // w.adaptive_period
+            tau, delta = ddef.deco(trace.v_g_bits, trace.bandwidth_bps[p], trace.latency_s[p], trace.t_comp_s)
+            assert (tau, pytest.approx(delta, rel=1e-12)) == oracle_mod.deco(
+                trace.v_g_bits, trace.bandwidth_bps[p], trace.latency_s[p], trace.t_comp_s)
+            tau = int(np.clip(tau, *trace.tau_bounds))
+            delta = float(np.clip(delta, *trace.delta_bounds))
+            g.set_tau(tau); o.set_tau(tau)
+        g.grad(); o.grad()
+        g.ef_compress(delta, w.lr); o.ef_compress(delta, w.lr)
+        assert_step_state_equal(g, o, w.n, check_grad=False, what=("C5", t))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert_model_equal(g, o, what=("C5", t))
+    g.close()
+
+
+# ---- checkpoint hooks and teacher forcing ---------------------------------------------------------
+def test_teacher_forced_step(ddef, oracle_mod):
+    w = workloads.get("C1", d=30_000, n=2)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=0)
+    rng = np.random.default_rng(5)
+    for t in range(3):
+        x = rng.standard_normal(w.d, dtype=F32)
+        g.set_model(x); o.set_model(x)
+        for i in range(w.n):
+            e = (rng.standard_normal(w.d, dtype=F32) * F32(0.01))
+            g.set_error(i, e); o.set_error(i, e)
+        g.step(0.02, w.lr); o.step(0.02, w.lr)
+        assert_step_state_equal(g, o, w.n, what=t)
+        assert_model_equal(g, o, what=t)
+    g.close()
+
+
+# ---- boundary behaviour: call order and argument checks ---------------------------------------------
+def test_state_machine_and_errors(ddef):
+    import ctypes as C
+    lib = ddef.load()
+    h = C.c_void_p()
+    assert lib.ddef_init(0, 1, 0, C.byref(h)) == ddef.EINVAL
+    assert lib.ddef_init(10, 0, 0, C.byref(h)) == ddef.EINVAL
+    assert lib.ddef_init(1 << 32, 1, 0, C.byref(h)) == ddef.EINVAL
+    assert lib.ddef_init(10, 1, 0, None) == ddef.EINVAL
+    d = 1000
+    c = ddef.Context(d, 2, 3)
+    one = np.ones(d, dtype=F32)
+    assert c.raw("grad") == ddef.ESTATE                       # no problem yet
+    c.set_problem(one, one, one, 0, 1, 0.1)
+    assert c.raw("set_tau", 4) == ddef.EINVAL
+    assert c.raw("ef_compress", C.c_double(0.1), C.c_float(0.1)) == ddef.ESTATE
+    assert c.raw("aggregate") == ddef.ESTATE
+    assert c.raw("apply_delayed", C.c_float(0.1)) == ddef.ESTATE
+    c.set_tau(0)
+    c.grad()
+    assert c.raw("grad") == ddef.ESTATE
+    assert c.raw("set_tau", 1) == ddef.ESTATE
+    for bad in (0.0, -0.5, 1.5, float("nan")):
+        assert c.raw("ef_compress", C.c_double(bad), C.c_float(0.1)) == ddef.EINVAL
+    assert c.raw("ef_compress", C.c_double(0.1), C.c_float(float("inf"))) == ddef.EINVAL
+    c.ef_compress(0.1, 0.05)
+    assert c.raw("apply_delayed", C.c_float(0.05)) == ddef.ESTATE
+    c.aggregate()
+    assert c.raw("apply_delayed", C.c_float(0.06)) == ddef.EINVAL      # not this step's stepsize
+    c.apply_delayed(0.05)
+    assert c.t == 1
+    assert c.raw("get_error", 2, one.ctypes.data_as(C.POINTER(C.c_float))) == ddef.EINVAL
+    assert c.raw("load_grad", 0, None) == ddef.EINVAL
+    c.close()
+
+
+def test_empty_iterations_before_tau(ddef):
+    d, tau = 5000, 3
+    w = workloads.get("C1", d=d, n=2)
+    lam, xstar, x0 = workloads.make_problem(w)
+    c = ddef.Context(d, 2, tau)
+    c.set_problem(lam, xstar, x0, 0, 1, 0.1)
+    for t in range(tau):
+        c.step(0.1, 0.05)
+        assert len(c.get_message(0)[0]) == 0
+        assert np.array_equal(bits(c.get_model()), bits(x0))
+        assert np.all(bits(c.get_update()) == 0)
+        assert np.all(bits(c.get_error(1)) == 0)
+    c.step(0.1, 0.05)
+    assert len(c.get_message(0)[0]) == 500
+    assert not np.array_equal(bits(c.get_model()), bits(x0))
+    c.close()
