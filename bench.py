@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the DD-EF-SGD hot path on one MI355X.
+
+A "step" is one full iteration of the path through the C-ABI: ddef_grad, ddef_ef_compress,
+ddef_aggregate, ddef_apply_delayed, for all n workers, on the GPT-2-small-sized workload
+(d = 124e6 fp32, n = 8, delta = 0.001, tau = 8, Student-t3 gradient noise).  Inputs are
+synthetic, generated from the workload's seed and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-step throughput in gradient elements/s (n*d per step), a roofline
+object for the dominant kernel (algorithmic bytes per launch / its average duration, measured
+here with HIP events on the library's stream), and the CPU oracle timed on this machine's cores on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
+ALGO_BYTES_PER_ELEM = {
+    "k_ef_accumulate": 12.0,   # read e, read g, write p
+    "k_ef_filter": 12.0,       # same pass, with the candidate filter fused in
+    "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
+    "k_digit_hist": 4.0, "k_chunk_count": 4.0, "k_chunk_emit": 4.0,
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note):
+    """The oracle, as it stands, on a bounded sample: one non-empty iteration over the first
+    sample_d coordinates of the workload (all n workers, one thread per worker)."""
+    import oracle
+    cores = os.cpu_count() or 1
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except Exception:
+        pass
+    env_cap = os.environ.get("OMP_NUM_THREADS")
+    if env_cap and env_cap.isdigit():
+        cores = min(cores, int(env_cap))
+    threads = max(1, min(w.n, cores))
+    o = oracle.Oracle(sample_d, w.n, 0, threads=threads)
+    o.set_problem(lam[:sample_d], xstar[:sample_d], x0[:sample_d], w.seed, w.noise_kind, w.noise_scale)
+    o.set_tau(0)
+    t0 = time.perf_counter()
+    o.step(w.deltas[0], w.lr)
+    dt = time.perf_counter() - t0
+    o.close()
+    return {"value": w.n * sample_d / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 non-empty iteration, all {w.n} workers, first {sample_d} of {w.d} coordinates "
+                      f"({dt:.1f} s wall, {threads} threads){budget_note}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--d", type=int, default=None, help="shrink d (debug only; not a valid bench)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-d", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all workers' shares resident in one HBM); "
+                 "--gpus N with N > 1 is not supported")
+
+    import numpy as np
+    from paper_2507_17346_amd import binding, workloads
+
+    w = workloads.get(args.workload, d=args.d)
+    delta = w.deltas[0]
+    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (k={w.k()}) tau={w.tau} lr={w.lr} "
+        f"noise kind {w.noise_kind} scale {w.noise_scale} seed {w.seed}")
+    t0 = time.perf_counter()
+    lam, xstar, x0 = workloads.make_problem(w)
+    log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
+    ctx = binding.Context(w.d, w.n, w.tau_max)
+    ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    ctx.set_tau(w.tau)
+
+    # warm-up: the tau empty iterations, then W real ones so that the error buffers are
+    # populated and the selection runs in its steady state
+    for _ in range(w.tau + args.warmup):
+        ctx.step(delta, w.lr)
+    ctx.sync()
+
+    # ---- timed region: exactly K whole steps ------------------------------------------------
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.step(delta, w.lr)
+    ctx.sync()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    elems = w.n * w.d
+    value = elems * args.steps / elapsed
+
+    # ---- the same K steps again, once with a wait after each call (time per call), once with
+    # HIP events around every kernel launch on the library's stream (time per kernel) -----------
+    phase = {"grad": 0.0, "ef_compress": 0.0, "aggregate": 0.0, "apply_delayed": 0.0}
+    for _ in range(args.steps):
+        for name, call in (("grad", ctx.grad), ("ef_compress", lambda: ctx.ef_compress(delta, w.lr)),
+                           ("aggregate", ctx.aggregate), ("apply_delayed", lambda: ctx.apply_delayed(w.lr))):
+            ctx.sync()
+            p0 = time.perf_counter()
+            call()
+            ctx.sync()
+            phase[name] += time.perf_counter() - p0
+    phase_ms = {k: 1e3 * v / args.steps for k, v in phase.items()}
+    full0 = ctx.full_select_count()
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        ctx.step(delta, w.lr)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    full_selects = ctx.full_select_count() - full0
+    kernels = {k: {"launches": c, "avg_ms": ms / c, "ms_per_step": ms / args.steps}
+               for k, (c, ms) in prof.items() if c}
+    for k, v in sorted(kernels.items(), key=lambda kv: -kv[1]["ms_per_step"]):
+        log(f"  {k:18s} launches/step {v['launches'] / args.steps:6.1f}  avg {v['avg_ms']:.4f} ms  "
+            f"per step {v['ms_per_step']:.4f} ms")
+    log("  per call (ms): " + ", ".join(f"{k} {v:.3f}" for k, v in phase_ms.items()))
+
+    hot = [k for k in kernels if k != "k_grad"]
+    dominant = max(hot, key=lambda k: kernels[k]["ms_per_step"])
+    per_elem = ALGO_BYTES_PER_ELEM.get(dominant, 4.0)
+    algo_bytes = per_elem * elems
+    achieved = algo_bytes / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": algo_bytes,
+                "avg_launch_ms": kernels[dominant]["avg_ms"]}
+
+    # metric of the path proper (EF + top-k + aggregate + apply), gradient generation aside
+    path_ms = phase_ms["ef_compress"] + phase_ms["aggregate"] + phase_ms["apply_delayed"]
+    floor_bytes = (12.0 + 24.0 * (w.k() / w.d) + 16.0 / w.n) * elems
+    path = {"ms": path_ms, "elements_per_s": elems / (path_ms * 1e-3),
+            "floor_bytes_per_step": floor_bytes,
+            "floor_GBps": floor_bytes / (path_ms * 1e-3) / 1e9,
+            "floor_frac_of_peak": floor_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    out = {
+        "metric": "EF+top-k+aggregate step: gradient elements/s and achieved HBM GB/s (% of peak)",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: d={w.d} fp32, n={w.n} workers, delta={delta} (k={w.k()}), "
+                               f"tau={w.tau}, lr={w.lr}, Student-t3 noise x{w.noise_scale}, seed {w.seed}",
+                   "d": w.d, "n": w.n, "k": w.k(), "tau": w.tau,
+                   "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
+        "roofline": roofline,
+        "ef_topk_aggregate_apply": path,
+        "ms_per_call": phase_ms,
+        "kernels_ms_per_step": {k: round(v["ms_per_step"], 5) for k, v in kernels.items()},
+        "full_row_selects_per_step": full_selects / args.steps,
+    }
+
+    if not args.no_cpu_baseline:
+        sample_d = args.cpu_sample_d or w.d
+        note = ""
+        try:
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note)
+        except MemoryError:
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory")
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

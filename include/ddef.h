@@ -141,6 +141,11 @@ int ddef_profile_read(ddef_ctx* ctx, int slot, const char** name, uint64_t* laun
 /* How many worker selections so far took the multi-pass path over the whole vector
  * (counted over all workers and iterations since ddef_set_problem). */
 int ddef_full_select_count(ddef_ctx* ctx, uint64_t* count);
+/* Diagnostics of a worker's last selection: the magnitude bound its candidate filter will use
+ * next, how many candidates the filter caught this time, and whether the selection had to
+ * search the whole row (1) or found the top-k among the candidates (0). */
+int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, uint32_t* candidates,
+                          uint32_t* searched_row);
 /* Tuning / test knobs; see DDEF_OPT_*.  Only between iterations. */
 #define DDEF_OPT_FORCE_FULL_SELECT 1 /* 1: never use the candidate filter                 */
 #define DDEF_OPT_CANDIDATE_SLACK_X16 2 /* candidate target = k * value / 16 (default 40)  */

@@ -48,6 +48,7 @@ SIGNATURES = {
     "ddef_profile_read": (C.c_int, [_ctx, C.c_int, C.POINTER(C.c_char_p), _u64p, C.POINTER(C.c_double)]),
     "ddef_full_select_count": (C.c_int, [_ctx, _u64p]),
     "ddef_set_option": (C.c_int, [_ctx, C.c_int, C.c_int64]),
+    "ddef_get_filter_state": (C.c_int, [_ctx, C.c_uint32, _u32p, _u32p, _u32p]),
     "ddef_strerror": (C.c_char_p, [C.c_int]),
 }
 
@@ -236,6 +237,13 @@ class Context:
         T, r = C.c_uint32(), C.c_uint64()
         self._check(self._lib.ddef_get_threshold(self._h, int(worker), C.byref(T), C.byref(r)), "ddef_get_threshold")
         return int(T.value), int(r.value)
+
+    def get_filter_state(self, worker: int):
+        """(next bound pattern, candidates caught, searched whole row) of the last selection."""
+        b, m, a = C.c_uint32(), C.c_uint32(), C.c_uint32()
+        self._check(self._lib.ddef_get_filter_state(self._h, int(worker), C.byref(b), C.byref(m), C.byref(a)),
+                    "ddef_get_filter_state")
+        return int(b.value), int(m.value), bool(a.value)
 
     def full_select_count(self) -> int:
         cnt = C.c_uint64()

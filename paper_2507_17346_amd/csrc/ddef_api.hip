@@ -19,12 +19,14 @@ namespace {
 enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
-    SL_GRAD = 0, SL_EF_ACCUM, SL_SEL_BEGIN, SL_FILL, SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT,
-    SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_SCATTER_ADD, SL_APPLY, SL_COUNT
+    SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_OFFSETS, SL_CAND_GATHER, SL_SEL_BEGIN_ROWS,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_FILL, SL_SCATTER_ADD,
+    SL_APPLY, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
-    "k_grad", "k_ef_accumulate", "k_sel_begin", "k_fill_u32", "k_digit_hist", "k_digit_pick",
-    "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_scatter_add", "k_apply"};
+    "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_offsets", "k_cand_gather",
+    "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
+    "k_fill_u32", "k_scatter_add", "k_apply"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -42,6 +44,19 @@ struct ddef_ctx {
     uint64_t msg_ld = 0;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
+    // candidate filter: per-worker words [bound | cand_count | overflow | stat_full | cand_total],
+    // the run table per 1024-entry wave-chunk with its prefixes, and the candidate buffers of
+    // `cap` entries per worker
+    uint32_t* filt = nullptr;
+    uint2* tab = nullptr;
+    uint32_t* obase = nullptr;
+    uint32_t* span_sum = nullptr;
+    uint32_t nwc = 0, nspans = 0;
+    uint2* cand = nullptr;
+    uint32_t* sorted_idx = nullptr;
+    float* sorted_val = nullptr;
+    uint64_t cap = 0;
+    bool have_bound = false;
     Phase phase = PH_IDLE;
     bool problem_set = false, step_empty = true;
     float lr_step = 0.0f;
@@ -136,43 +151,63 @@ uint32_t blocks_for(ddef_ctx* c, uint64_t items_per_row_blocks, uint32_t rows, u
     return (uint32_t)(b < 1 ? 1 : b);
 }
 
-int ensure_message_capacity(ddef_ctx* c, uint64_t k) {
-    if (k <= c->msg_ld) return DDEF_OK;
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (c->msg_idx) (void)hipFree(c->msg_idx);
-    if (c->msg_val) (void)hipFree(c->msg_val);
-    c->msg_idx = nullptr; c->msg_val = nullptr; c->msg_ld = 0;
-    uint64_t cap = (k + 1023u) & ~(uint64_t)1023u;
-    HIP_TRY(c, hipMalloc((void**)&c->msg_idx, (size_t)c->n * cap * 4u));
-    HIP_TRY(c, hipMalloc((void**)&c->msg_val, (size_t)c->n * cap * 4u));
-    HIP_TRY(c, hipMemset(c->msg_idx, 0, (size_t)c->n * cap * 4u));
-    HIP_TRY(c, hipMemset(c->msg_val, 0, (size_t)c->n * cap * 4u));
-    c->msg_ld = cap;
+int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
+    if (k > c->msg_ld) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (c->msg_idx) (void)hipFree(c->msg_idx);
+        if (c->msg_val) (void)hipFree(c->msg_val);
+        c->msg_idx = nullptr; c->msg_val = nullptr; c->msg_ld = 0;
+        const uint64_t len = (k + 1023u) & ~(uint64_t)1023u;
+        HIP_TRY(c, hipMalloc((void**)&c->msg_idx, (size_t)c->n * len * 4u));
+        HIP_TRY(c, hipMalloc((void**)&c->msg_val, (size_t)c->n * len * 4u));
+        HIP_TRY(c, hipMemset(c->msg_idx, 0, (size_t)c->n * len * 4u));
+        HIP_TRY(c, hipMemset(c->msg_val, 0, (size_t)c->n * len * 4u));
+        c->msg_ld = len;
+    }
+    // room for the candidates: three times the target while messages are sparse, twice otherwise
+    const bool sparse = k * 32u <= c->d;
+    // plus one page per wave of the filter kernel's grid: the unused end of a wave's last page
+    const uint64_t waves = (uint64_t)blocks_for(c, c->nchunks, c->n, 8) * 4u;
+    uint64_t want = ((sparse ? 3u : 2u) * kb + waves * kPage + 8191u) & ~(uint64_t)4095u;
+    if (want > c->ld) want = c->ld;
+    if (want > c->cap) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (c->cand) (void)hipFree(c->cand);
+        if (c->sorted_idx) (void)hipFree(c->sorted_idx);
+        if (c->sorted_val) (void)hipFree(c->sorted_val);
+        c->cand = nullptr; c->sorted_idx = nullptr; c->sorted_val = nullptr; c->cap = 0;
+        HIP_TRY(c, hipMalloc((void**)&c->cand, (size_t)c->n * want * 8u));
+        HIP_TRY(c, hipMalloc((void**)&c->sorted_idx, (size_t)c->n * want * 4u));
+        HIP_TRY(c, hipMalloc((void**)&c->sorted_val, (size_t)c->n * want * 4u));
+        HIP_TRY(c, hipMemset(c->sorted_idx, 0, (size_t)c->n * want * 4u));
+        HIP_TRY(c, hipMemset(c->sorted_val, 0, (size_t)c->n * want * 4u));
+        c->cap = want;
+    }
     return DDEF_OK;
 }
 
-// Multi-pass selection over the whole row for every active worker, then ordered compaction.
-void enqueue_full_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
-    const uint32_t n = c->n, d = (uint32_t)c->d;
-    LAUNCH(c, SL_SEL_BEGIN, k_sel_begin, dim3((n + 63) / 64), dim3(64), c->sel, n, k, kb, 1u);
-    const uint64_t hist_words = (uint64_t)3 * n * 2 * 2048;
-    LAUNCH(c, SL_FILL, k_fill_u32, dim3((uint32_t)((hist_words + 255) / 256)), dim3(256), c->hist,
-           hist_words, 0u);
-    const uint32_t tiles = (uint32_t)((c->d + 1023) / 1024);
-    const uint32_t gx = blocks_for(c, tiles, n, 8);
+// Radix select and ordered compaction of every worker through its view (candidates or row).
+void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, bool rows_only) {
+    const uint32_t n = c->n;
+    uint32_t *bound = c->filt, *cand_count = c->filt + n, *overflow = c->filt + 2 * n, *cand_total = c->filt + 4 * n;
+    const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sorted_val, c->sorted_idx, c->cap, cand_total};
+    // grids sized for the longest view that can occur (any worker may have to search its row)
+    (void)rows_only;
+    const uint64_t span = c->ld;
+    const uint32_t gx = blocks_for(c, (span + 1023) / 1024, n, 8);
     for (int level = 0; level < 3; ++level) {
         uint32_t* h = c->hist + (uint64_t)level * n * 2 * 2048;
-        LAUNCH(c, SL_DIGIT_HIST, k_digit_hist, dim3(gx, n), dim3(256), c->e, c->ld, d,
-               (const uint32_t*)nullptr, c->sel, h, level);
-        LAUNCH(c, SL_DIGIT_PICK, k_digit_pick, dim3(n, 2), dim3(256), c->sel, h, level);
+        LAUNCH(c, SL_DIGIT_HIST, k_digit_hist, dim3(gx, n), dim3(256), vs, (const SelState*)c->sel, h, level);
+        LAUNCH(c, SL_DIGIT_PICK, k_digit_pick, dim3(n, 2), dim3(256), c->sel, (const uint32_t*)h, level);
     }
-    const uint32_t gc = blocks_for(c, c->nchunks, n, 8);
-    LAUNCH(c, SL_CHUNK_COUNT, k_chunk_count, dim3(gc, n), dim3(256), c->e, c->ld, d, c->sel,
-           c->cnt_gt, c->cnt_eq, c->nchunks);
-    LAUNCH(c, SL_CHUNK_SCAN, k_chunk_scan, dim3(n), dim3(1024), c->sel, c->cnt_gt, c->cnt_eq, c->nchunks);
-    LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), c->e, c->ld, d, c->sel, c->cnt_gt,
-           c->cnt_eq, c->nchunks, c->msg_idx, c->msg_val, c->msg_ld, k);
-    c->full_selects += n;
+    const uint32_t gc = blocks_for(c, (span + 4095) / 4096, n, 8);
+    LAUNCH(c, SL_CHUNK_COUNT, k_chunk_count, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel, c->cnt_gt,
+           c->cnt_eq, c->nchunks);
+    LAUNCH(c, SL_CHUNK_SCAN, k_chunk_scan, dim3(n), dim3(1024), vs, c->sel, c->cnt_gt, c->cnt_eq, c->nchunks,
+           k, kb, bound, cand_count, overflow);
+    LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel,
+           (const uint32_t*)c->cnt_gt, (const uint32_t*)c->cnt_eq, c->nchunks, c->e, c->msg_idx, c->msg_val,
+           c->msg_ld, k);
 }
 
 int check_ctx(ddef_ctx* c) {
@@ -256,6 +291,8 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     c->d = d; c->n = n; c->tau_max = tau_max; c->tau = tau_max;
     c->ld = (d + 4095u) & ~(uint64_t)4095u;
     c->nchunks = (uint32_t)(c->ld / 4096u);
+    c->nwc = (uint32_t)(c->ld / 1024u);
+    c->nspans = (c->nwc + 8191u) / 8192u;
     if (hipStreamCreateWithFlags(&c->own_stream, hipStreamNonBlocking) != hipSuccess) return fail(DDEF_EHIP);
     c->stream = c->own_stream;
     const size_t row = (size_t)c->ld * 4u;
@@ -265,6 +302,8 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
         {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
+        {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->obase, (size_t)n * c->nwc * 4}, {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
     };
     for (const Want& w : wants) {
         err = hipMalloc(w.p, w.bytes);
@@ -285,7 +324,8 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val};
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->tab, c->obase, c->span_sum, c->cand,
+                    c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
     delete c;
@@ -319,6 +359,8 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
+    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)5 * c->n * 4));
+    c->have_bound = false;
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
@@ -378,15 +420,39 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         return DDEF_OK;
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
-    rc = ensure_message_capacity(c, k);
-    if (rc) return rc;
-    uint64_t kb = k * (uint64_t)c->opt_slack_x16 / 16u;
+    // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
+    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
     if (kb < k) kb = k;
     if (kb > c->d) kb = c->d;
-    const uint32_t tiles = (uint32_t)((c->d + 1023) / 1024);
-    const uint32_t gx = blocks_for(c, tiles, c->n, 8);
-    LAUNCH(c, SL_EF_ACCUM, k_ef_accumulate, dim3(gx, c->n), dim3(256), c->e, c->g, c->ld, (uint32_t)c->d, lr);
-    enqueue_full_select(c, (uint32_t)k, (uint32_t)kb);
+    rc = ensure_capacity(c, k, kb);
+    if (rc) return rc;
+    const uint32_t n = c->n;
+    uint32_t *bound = c->filt, *cand_count = c->filt + n, *overflow = c->filt + 2 * n, *stat_full = c->filt + 3 * n;
+    // the filter needs a bound from an earlier selection and pays off only for sparse messages
+    const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
+    const uint32_t gx = blocks_for(c, c->nchunks, n, 8);
+    LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(gx, n), dim3(256), c->e, c->g, c->ld, (uint32_t)c->d, lr,
+           (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
+    uint32_t* cand_total = c->filt + 4 * n;
+    if (use_filter) {
+        LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               c->span_sum, c->nspans);
+        LAUNCH(c, SL_TAB_DECIDE, k_tab_decide, dim3(n), dim3(256), c->span_sum, c->nspans,
+               (const uint32_t*)overflow, (uint32_t)k, (uint32_t)kb, (uint32_t)c->d, n, c->sel, cand_total,
+               stat_full, c->hist);
+        LAUNCH(c, SL_TAB_OFFSETS, k_tab_offsets, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, c->obase);
+        const uint32_t gg = blocks_for(c, (c->cap + 255) / 256, n, 8);
+        LAUNCH(c, SL_CAND_GATHER, k_cand_gather, dim3(gg, n), dim3(256), (const uint2*)c->cand, c->cap,
+               (const uint2*)c->tab, (const uint32_t*)c->obase, c->nwc, (const uint32_t*)cand_total,
+               (const SelState*)c->sel, c->sorted_idx, c->sorted_val);
+    } else {
+        LAUNCH(c, SL_SEL_BEGIN_ROWS, k_sel_begin_rows, dim3(n), dim3(256), c->sel, n, (uint32_t)k, (uint32_t)kb,
+               (uint32_t)c->d, cand_total, c->hist);
+        c->full_selects += n;
+    }
+    enqueue_select(c, (uint32_t)k, (uint32_t)kb, !use_filter);
+    c->have_bound = true;
     HIP_TRY(c, hipGetLastError());
     c->k_step = k;
     c->phase = PH_COMPRESSED;
@@ -522,6 +588,22 @@ int ddef_get_threshold(ddef_ctx* c, uint32_t worker, uint32_t* T, uint64_t* r) {
     return DDEF_OK;
 }
 
+int ddef_get_filter_state(ddef_ctx* c, uint32_t worker, uint32_t* next_bound, uint32_t* candidates,
+                          uint32_t* searched_row) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!next_bound || !candidates || !searched_row || worker >= c->n) return DDEF_EINVAL;
+    if (c->k_step == 0) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    SelState s;
+    HIP_TRY(c, hipMemcpy(&s, c->sel + worker, sizeof(SelState), hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(next_bound, c->filt + worker, 4u, hipMemcpyDeviceToHost));
+    *candidates = s.seen;
+    *searched_row = s.active;
+    return DDEF_OK;
+}
+
 int ddef_profile_enable(ddef_ctx* c, int on) {
     int rc = check_ctx(c);
     if (rc) return rc;
@@ -551,8 +633,16 @@ int ddef_profile_read(ddef_ctx* c, int slot, const char** name, uint64_t* launch
 }
 
 int ddef_full_select_count(ddef_ctx* c, uint64_t* count) {
-    if (!c || !count) return DDEF_EINVAL;
-    *count = c->full_selects;
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!count) return DDEF_EINVAL;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::vector<uint32_t> fell_back(c->n, 0u);
+    HIP_TRY(c, hipMemcpy(fell_back.data(), c->filt + 3 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
+    uint64_t total = c->full_selects;
+    for (uint32_t v : fell_back) total += v;
+    *count = total;
     return DDEF_OK;
 }
 

@@ -6,33 +6,65 @@
 
 namespace ddef {
 
+// Candidate slots are handed to a wave in pages of this many entries.
+constexpr uint32_t kPage = 128;
+
 // Per-worker selection state in device memory.
 struct SelState {
-    uint32_t active;      // 1: this worker's selection runs over the whole row
+    uint32_t active;      // 1: search the whole row; 0: search the filtered candidates
     uint32_t prefix[2];   // magnitude pattern built so far for rank 0 (k) and rank 1 (filter)
     uint32_t krem[2];     // rank still to find inside the current prefix group (1-based)
     uint32_t T, r;        // threshold pattern and how many entries equal to T are sent
     uint32_t next_bound;  // magnitude pattern of the rank-1 entry
+    uint32_t seen;        // candidates the filter caught in the last selection
+    uint32_t T_prev;      // threshold pattern of the selection before the last one
+    uint32_t k_prev;      // its k (0: none)
+};
+
+// Where the selection kernels find a worker's entries: its whole row of e (d entries, the
+// position is the coordinate) or its ordered candidates (cand_total[w] entries of
+// cand_val / cand_idx rows of `cap` entries), chosen per worker by SelState::active.
+struct SelViews {
+    const float* e;
+    uint64_t ld;
+    uint32_t d;
+    const float* cand_val;
+    const uint32_t* cand_idx;
+    uint64_t cap;
+    const uint32_t* cand_total;
 };
 
 __global__ void k_grad(const float* lambda, const float* xstar, const float* xs, float* g,
                        uint64_t ld, uint32_t d, uint32_t n, uint32_t seed_lo, uint32_t seed_hi,
                        uint32_t t_lo, uint32_t t_hi, int kind, float scale);
-__global__ void k_ef_accumulate(float* e, const float* g, uint64_t ld, uint32_t d, float lr);
-__global__ void k_digit_hist(const float* src, uint64_t ld, uint32_t cnt_fixed,
-                             const uint32_t* cnt_dev, const SelState* sel, uint32_t* hist, int level);
-__global__ void k_digit_pick(SelState* sel, uint32_t* hist, int level);
-__global__ void k_chunk_count(const float* e, uint64_t ld, uint32_t d, const SelState* sel,
-                              uint32_t* cnt_gt, uint32_t* cnt_eq, uint32_t nchunks);
-__global__ void k_chunk_scan(const SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq, uint32_t nchunks);
-__global__ void k_chunk_emit(float* e, uint64_t ld, uint32_t d, const SelState* sel,
-                             const uint32_t* out_base, const uint32_t* eq_before, uint32_t nchunks,
-                             uint32_t* msg_idx, float* msg_val, uint64_t msg_ld, uint32_t k);
+__global__ void k_ef_filter(float* e, const float* g, uint64_t ld, uint32_t d, float lr,
+                            const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
+                            uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t nwc);
+__global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
+__global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
+                             uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,
+                             uint32_t* stat_full, uint32_t* hist);
+__global__ void k_sel_begin_rows(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t d,
+                                 uint32_t* cand_total, uint32_t* hist);
+__global__ void k_tab_offsets(const uint2* tab, uint32_t nwc, const uint32_t* span_off, uint32_t nspans,
+                              const SelState* sel, uint32_t* obase);
+__global__ void k_cand_gather(const uint2* cand, uint64_t cap, const uint2* tab, const uint32_t* obase,
+                              uint32_t nwc, const uint32_t* cand_total, const SelState* sel,
+                              uint32_t* sorted_idx, float* sorted_val);
+__global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);
+__global__ void k_digit_pick(SelState* sel, const uint32_t* hist, int level);
+__global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
+                              uint32_t stride);
+__global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
+                             uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound,
+                             uint32_t* cand_count, uint32_t* overflow);
+__global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
+                             const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,
+                             float* msg_val, uint64_t msg_ld, uint32_t k);
 __global__ void k_scatter_add(float* U, const uint32_t* idx, const float* val, uint32_t k, uint32_t d);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
 __global__ void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);
-__global__ void k_sel_begin(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t all_active);
 
 }  // namespace ddef
 #endif

@@ -188,24 +188,249 @@ __global__ __launch_bounds__(256) void k_grad(const float* __restrict__ lambda,
 }
 
 // ------------------------------------------------------------------------------------
-// S1  p = e + lr * g, written over e                         (Algorithm 1, worker side)
-// grid (gx, n): blockIdx.y is the worker, blocks stride over 1024-element tiles.
+// S1 (+ candidate filter of S2/S3)   p = e + lr * g, written over e   (Algorithm 1, worker side)
+//
+// grid (gx, n): blockIdx.y is the worker; a block strides over 4096-element chunks and each
+// of its four waves owns 1024 consecutive coordinates of the chunk (four 16-byte accesses
+// per lane, all issued before the first use).  While p is in registers, every entry whose
+// magnitude pattern is >= bound[w] is a *candidate* for the top-k.  The wave counts its
+// candidates with ballots and writes them as (index, value) pairs, in index order, into a
+// run of slots of the worker's candidate buffer; tab[w][wave-chunk] records (first slot,
+// count), so that the runs can be read back in coordinate order although slots are handed
+// out in arbitrary order.  Slots come from pages of kPage entries that a wave reserves with
+// one atomic add and fills with consecutive runs (a run never straddles pages; the unused
+// end of a page is lost), which keeps the atomics off the critical path.
+// With use_filter == 0 this is the plain accumulate pass.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_ef_accumulate(float* __restrict__ e,
-                                                       const float* __restrict__ g, uint64_t ld,
-                                                       uint32_t d, float lr) {
-    const uint32_t quads = (d + 3u) >> 2;
-    float* er = e + (uint64_t)blockIdx.y * ld;
-    const float* gr = g + (uint64_t)blockIdx.y * ld;
-    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
-        const float4 ev = reinterpret_cast<const float4*>(er)[q];
-        const float4 gv = load_stream4(gr + ((uint64_t)q << 2));
-        float4 p;
-        p.x = ev.x + lr * gv.x;
-        p.y = ev.y + lr * gv.y;
-        p.z = ev.z + lr * gv.z;
-        p.w = ev.w + lr * gv.w;
-        reinterpret_cast<float4*>(er)[q] = p;
+__global__ __launch_bounds__(256) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
+                                                   uint64_t ld, uint32_t d, float lr,
+                                                   const uint32_t* __restrict__ bound, int use_filter,
+                                                   uint2* __restrict__ cand, uint64_t cap,
+                                                   uint32_t* __restrict__ cand_count,
+                                                   uint32_t* __restrict__ overflow,
+                                                   uint2* __restrict__ tab, uint32_t nwc) {
+    const uint32_t w = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
+    const uint32_t L = use_filter ? bound[w] : 0xffffffffu;
+    float* er = e + (uint64_t)w * ld;
+    const float* gr = g + (uint64_t)w * ld;
+    uint2* cw = cand + (uint64_t)w * cap;
+    uint2* tw = tab + (uint64_t)w * nwc;
+    const uint32_t nchunks = nwc >> 2;
+    uint32_t page_pos = 0, page_end = 0;      // this wave's current page: free slots [pos, end)
+    bool lost = false;                        // the candidate buffer ran out
+    for (uint32_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
+        const uint32_t wc = chunk * 4u + wave;
+        const uint32_t j0 = wc * 1024u + lane * 4u;
+        float4 ev[4], gv[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const uint32_t j = j0 + it * 256u;
+            if (j < d) {
+                ev[it] = *reinterpret_cast<const float4*>(er + j);
+                gv[it] = load_stream4(gr + j);
+            } else {
+                ev[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                gv[it] = ev[it];
+            }
+        }
+        float pv[4][4];
+        uint32_t total = 0;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const uint32_t j = j0 + it * 256u;
+            pv[it][0] = ev[it].x + lr * gv[it].x;
+            pv[it][1] = ev[it].y + lr * gv[it].y;
+            pv[it][2] = ev[it].z + lr * gv[it].z;
+            pv[it][3] = ev[it].w + lr * gv[it].w;
+            if (j < d) *reinterpret_cast<float4*>(er + j) = make_float4(pv[it][0], pv[it][1], pv[it][2], pv[it][3]);
+            bool any = false;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) any |= (j + c < d) && mag_key(pv[it][c]) >= L;
+            // cheap test first: most 256-entry groups hold no candidate at all
+            if (__ballot(any)) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    total += (uint32_t)__popcll(__ballot((j + c < d) && mag_key(pv[it][c]) >= L));
+            }
+        }
+        uint32_t base = 0;
+        if (total) {
+            if (page_pos + total > page_end && !lost) {
+                const uint32_t want = (total + kPage - 1u) / kPage * kPage;
+                uint32_t got = 0;
+                if (lane == 0) got = atomicAdd(&cand_count[w], want);
+                got = __shfl(got, 0, 64);
+                if ((uint64_t)got + want > cap) {
+                    lost = true;
+                    if (lane == 0) overflow[w] = 1u;
+                } else {
+                    page_pos = got;
+                    page_end = got + want;
+                }
+            }
+            if (!lost) {
+                base = page_pos;
+                page_pos += total;
+                uint32_t run = base;
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const uint32_t j = j0 + it * 256u;
+                    uint32_t below = 0, in_group = 0;
+                    bool f[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        f[c] = (j + c < d) && mag_key(pv[it][c]) >= L;
+                        const uint64_t m = __ballot(f[c]);
+                        below += mask_rank(m);
+                        in_group += (uint32_t)__popcll(m);
+                    }
+                    uint32_t pos = run + below;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[it][c])); ++pos; }
+                    run += in_group;
+                }
+            }
+        }
+        if (lane == 0) tw[wc] = make_uint2(base, total);
+    }
+}
+
+// ---- run table -> coordinate order ------------------------------------------------------
+// tab[w][c].y is the run length of wave-chunk c.  Three small kernels turn the lengths into
+// exclusive prefixes obase[w][c]: sums over spans of 8192 wave-chunks, a scan of the span
+// sums that also decides whether the filter caught enough, and the prefixes inside a span.
+constexpr uint32_t kSpan = 8192;
+
+__global__ __launch_bounds__(1024) void k_tab_sum(const uint2* __restrict__ tab, uint32_t nwc,
+                                                  uint32_t* __restrict__ span_sum, uint32_t nspans) {
+    __shared__ uint32_t red[16];
+    const uint32_t w = blockIdx.y, sp = blockIdx.x;
+    const uint2* tw = tab + (uint64_t)w * nwc;
+    const uint32_t c0 = sp * kSpan + threadIdx.x * 8u;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) mine += (c0 + q < nwc) ? tw[c0 + q].y : 0u;
+    mine = wave_sum(mine);
+    if (lane_id() == 0) red[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int q = 0; q < 16; ++q) t += red[q];
+        span_sum[(uint64_t)w * nspans + sp] = t;
+    }
+}
+
+// Start of a worker's selection (any thread count): rank 0 looks for the k-th entry of the
+// view, rank 1 for the kb-th (or the last one if the view is shorter); clears the worker's
+// digit histograms of all three levels.
+__device__ __forceinline__ void begin_selection(SelState* sel, uint32_t w, uint32_t n, uint32_t k,
+                                                uint32_t kb, uint32_t view_len, uint32_t* hist) {
+    if (threadIdx.x == 0) {
+        sel[w].prefix[0] = 0; sel[w].prefix[1] = 0;
+        sel[w].krem[0] = k;
+        sel[w].krem[1] = kb < view_len ? kb : view_len;
+    }
+    for (int level = 0; level < 3; ++level) {
+        uint32_t* h = hist + ((uint64_t)level * n + w) * 2u * 2048u;
+        for (uint32_t b = threadIdx.x; b < 4096u; b += blockDim.x) h[b] = 0u;
+    }
+}
+
+// One block per worker.  The filter is usable when nothing overflowed and it caught at
+// least k entries: then the top-k is among the candidates, because every entry outside the
+// candidate set is smaller than every entry inside.  Otherwise sel[w].active = 1 sends the
+// worker's selection over its whole row.
+__global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_sum, uint32_t nspans,
+                                                    const uint32_t* __restrict__ overflow, uint32_t k,
+                                                    uint32_t kb, uint32_t d, uint32_t n,
+                                                    SelState* __restrict__ sel,
+                                                    uint32_t* __restrict__ cand_total,
+                                                    uint32_t* __restrict__ stat_full,
+                                                    uint32_t* __restrict__ hist) {
+    __shared__ uint32_t lds[5];
+    const uint32_t w = blockIdx.x;
+    uint32_t* sw = span_sum + (uint64_t)w * nspans;
+    uint32_t carry = 0;
+    for (uint32_t first = 0; first < nspans; first += 256u) {       // span sums -> span offsets
+        const uint32_t sp = first + threadIdx.x;
+        const uint32_t v = sp < nspans ? sw[sp] : 0u;
+        uint32_t total;
+        const uint32_t at = carry + block_excl_scan(v, lds, &total);
+        if (sp < nspans) sw[sp] = at;
+        carry += total;
+    }
+    const uint32_t M = carry;
+    const bool usable = overflow[w] == 0u && M >= k;
+    if (threadIdx.x == 0) {
+        cand_total[w] = M;
+        sel[w].active = usable ? 0u : 1u;
+        if (!usable) stat_full[w] += 1u;
+    }
+    begin_selection(sel, w, n, k, kb, usable ? M : d, hist);
+}
+
+// No filter in this iteration: every worker searches its whole row.
+__global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ sel, uint32_t n, uint32_t k,
+                                                        uint32_t kb, uint32_t d,
+                                                        uint32_t* __restrict__ cand_total,
+                                                        uint32_t* __restrict__ hist) {
+    const uint32_t w = blockIdx.x;
+    if (threadIdx.x == 0) { sel[w].active = 1u; cand_total[w] = 0u; }
+    begin_selection(sel, w, n, k, kb, d, hist);
+}
+
+__global__ __launch_bounds__(1024) void k_tab_offsets(const uint2* __restrict__ tab, uint32_t nwc,
+                                                      const uint32_t* __restrict__ span_off,
+                                                      uint32_t nspans, const SelState* __restrict__ sel,
+                                                      uint32_t* __restrict__ obase) {
+    __shared__ uint32_t lds[17];
+    const uint32_t w = blockIdx.y, sp = blockIdx.x;
+    if (sel[w].active) return;
+    const uint2* tw = tab + (uint64_t)w * nwc;
+    uint32_t* ow = obase + (uint64_t)w * nwc;
+    const uint32_t c0 = sp * kSpan + threadIdx.x * 8u;
+    uint32_t len[8], mine = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        len[q] = (c0 + q < nwc) ? tw[c0 + q].y : 0u;
+        mine += len[q];
+    }
+    uint32_t total;
+    uint32_t at = span_off[(uint64_t)w * nspans + sp] + block_excl_scan(mine, lds, &total);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        if (c0 + q < nwc) ow[c0 + q] = at;
+        at += len[q];
+    }
+}
+
+// Candidate m in coordinate order lives in the run of the last wave-chunk c with
+// obase[c] <= m, at offset m - obase[c] from the run's first slot.  Writes the ordered
+// candidates as two arrays (index, value).
+__global__ __launch_bounds__(256) void k_cand_gather(const uint2* __restrict__ cand, uint64_t cap,
+                                                     const uint2* __restrict__ tab,
+                                                     const uint32_t* __restrict__ obase, uint32_t nwc,
+                                                     const uint32_t* __restrict__ cand_total,
+                                                     const SelState* __restrict__ sel,
+                                                     uint32_t* __restrict__ sorted_idx,
+                                                     float* __restrict__ sorted_val) {
+    const uint32_t w = blockIdx.y;
+    if (sel[w].active) return;
+    const uint32_t M = cand_total[w];
+    const uint2* cw = cand + (uint64_t)w * cap;
+    const uint2* tw = tab + (uint64_t)w * nwc;
+    const uint32_t* ow = obase + (uint64_t)w * nwc;
+    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < M; m += gridDim.x * blockDim.x) {
+        uint32_t lo = 0, hi = nwc;                 // first c in [lo, hi) with obase[c] > m
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (ow[mid] > m) hi = mid; else lo = mid + 1u;
+        }
+        const uint32_t c = lo - 1u;                // obase[0] = 0 <= m, so lo >= 1
+        const uint2 item = cw[tw[c].x + (m - ow[c])];
+        sorted_idx[(uint64_t)w * cap + m] = item.x;
+        sorted_val[(uint64_t)w * cap + m] = __uint_as_float(item.y);
     }
 }
 
@@ -213,41 +438,48 @@ __global__ __launch_bounds__(256) void k_ef_accumulate(float* __restrict__ e,
 // S2  radix select of the k-th entry under (|v| descending, index ascending), done on the
 // 31-bit magnitude pattern in three digits of 11, 10 and 10 bits, for two ranks at once:
 // rank 0 is k (gives the threshold T and r), rank 1 is the candidate target used to place
-// the next iteration's filter bound.
+// the next iteration's filter bound.  Each worker is searched through its *view*: its
+// ordered candidates (active == 0) or its whole row of e (active == 1).
 // ------------------------------------------------------------------------------------
-// digit geometry per level: bits [hi, lo)
 __device__ __forceinline__ uint32_t lvl_lo(int level) { return level == 0 ? 20u : level == 1 ? 10u : 0u; }
 __device__ __forceinline__ uint32_t lvl_hi(int level) { return level == 0 ? 31u : level == 1 ? 20u : 10u; }
 __device__ __forceinline__ uint32_t lvl_bins(int level) { return level == 0 ? 2048u : 1024u; }
 
-// Histogram of one digit over a worker's row (values = fp32 entries of `src` row, `count`
-// valid entries taken from cnt_fixed, or from cnt_dev[worker] when cnt_dev is not null).
-// Level 0 builds one histogram shared by both ranks; levels 1, 2 build one per rank, over the
-// entries whose higher bits match that rank's prefix.  hist layout: [worker][2][2048].
-// Workers whose `active` flag is 0 are skipped.
-__global__ __launch_bounds__(256) void k_digit_hist(const float* __restrict__ src, uint64_t ld,
-                                                    uint32_t cnt_fixed,
-                                                    const uint32_t* __restrict__ cnt_dev,
-                                                    const SelState* __restrict__ sel,
+struct View { const float* row; const uint32_t* map; uint32_t count; };
+
+__device__ __forceinline__ View view_of(const SelViews& vs, const SelState* sel, uint32_t w) {
+    View v;
+    if (sel[w].active) { v.row = vs.e + (uint64_t)w * vs.ld; v.map = nullptr; v.count = vs.d; }
+    else {
+        v.row = vs.cand_val + (uint64_t)w * vs.cap;
+        v.map = vs.cand_idx + (uint64_t)w * vs.cap;
+        v.count = vs.cand_total[w];
+    }
+    return v;
+}
+
+// Histogram of one digit over each worker's view.  Level 0 builds one histogram shared by
+// both ranks; levels 1, 2 build one per rank, over the entries whose higher bits match that
+// rank's prefix.  hist layout: [worker][2][2048].
+__global__ __launch_bounds__(256) void k_digit_hist(SelViews vs, const SelState* __restrict__ sel,
                                                     uint32_t* __restrict__ hist, int level) {
     __shared__ uint32_t h[2][2048];
     const uint32_t w = blockIdx.y;
-    if (!sel[w].active) return;
-    const uint32_t count = cnt_dev ? cnt_dev[w] : cnt_fixed;
+    const View v = view_of(vs, sel, w);
+    const uint32_t quads = (v.count + 3u) >> 2;
+    if (blockIdx.x * blockDim.x >= quads) return;         // nothing for this block (uniform)
     const uint32_t lo = lvl_lo(level), hi = lvl_hi(level), bins = lvl_bins(level);
     const int nrank = level == 0 ? 1 : 2;
     for (uint32_t b = threadIdx.x; b < 2048u; b += blockDim.x) { h[0][b] = 0; h[1][b] = 0; }
     __syncthreads();
     const uint32_t pre0 = sel[w].prefix[0] >> hi, pre1 = sel[w].prefix[1] >> hi;
-    const float* row = src + (uint64_t)w * ld;
-    const uint32_t quads = (count + 3u) >> 2;
     for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
-        const float4 v = reinterpret_cast<const float4*>(row)[q];
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+        const float4 x = reinterpret_cast<const float4*>(v.row)[q];
+        const float vv[4] = {x.x, x.y, x.z, x.w};
         const uint32_t j = q << 2;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (j + c < count) {
+            if (j + c < v.count) {
                 const uint32_t key = mag_key(vv[c]);
                 const uint32_t digit = (key >> lo) & (bins - 1u);
                 if (level == 0) {
@@ -271,17 +503,16 @@ __global__ __launch_bounds__(256) void k_digit_hist(const float* __restrict__ sr
 // Pick the digit holding each rank: grid (n, 2), block 256.  For rank `rk`, walks the
 // histogram from the top digit down until the running count reaches krem[rk]; appends the
 // digit to prefix[rk] and reduces krem[rk] by the count of the digits above it.  After the
-// last level publishes T, r (rank 0) and the bound for the next filter (rank 1).
+// last level publishes T, r (rank 0) and the magnitude at the filter rank (rank 1).
 __global__ __launch_bounds__(256) void k_digit_pick(SelState* __restrict__ sel,
-                                                    uint32_t* __restrict__ hist, int level) {
+                                                    const uint32_t* __restrict__ hist, int level) {
     __shared__ uint32_t lds[8];
     __shared__ uint32_t found_digit, found_above;
     const uint32_t w = blockIdx.x, rk = blockIdx.y;
-    if (!sel[w].active) return;
     const uint32_t bins = lvl_bins(level), lo = lvl_lo(level);
     const uint32_t per = bins / 256u;
     // level 0 has a single histogram (slot 0) read by both ranks
-    uint32_t* hsrc = hist + (uint64_t)w * 2u * 2048u + (level == 0 ? 0u : rk * 2048u);
+    const uint32_t* hsrc = hist + (uint64_t)w * 2u * 2048u + (level == 0 ? 0u : rk * 2048u);
     const uint32_t krem = sel[w].krem[rk];
     if (threadIdx.x == 0) { found_digit = 0; found_above = 0; }
     // thread 0 owns the top `per` digits
@@ -312,30 +543,29 @@ __global__ __launch_bounds__(256) void k_digit_pick(SelState* __restrict__ sel,
 }
 
 // ------------------------------------------------------------------------------------
-// S3  ordered compaction over the whole row, given (T, r): count per 4096-element chunk,
-// scan over chunks, emit.  An entry is sent iff key > T, or key == T and fewer than r
-// entries with key == T precede it in index order.
+// S3  ordered compaction of a view, given (T, r): count per 4096-entry chunk, scan over
+// chunks, emit.  An entry is sent iff key > T, or key == T and fewer than r entries with
+// key == T precede it in coordinate order.  Count arrays are laid out [worker][stride].
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_chunk_count(const float* __restrict__ e, uint64_t ld,
-                                                     uint32_t d, const SelState* __restrict__ sel,
+__global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState* __restrict__ sel,
                                                      uint32_t* __restrict__ cnt_gt,
-                                                     uint32_t* __restrict__ cnt_eq, uint32_t nchunks) {
+                                                     uint32_t* __restrict__ cnt_eq, uint32_t stride) {
     __shared__ uint32_t red[8];
     const uint32_t w = blockIdx.y;
-    if (!sel[w].active) return;
+    const View v = view_of(vs, sel, w);
+    const uint32_t nchunks = (v.count + 4095u) >> 12;
     const uint32_t T = sel[w].T;
-    const float* row = e + (uint64_t)w * ld;
     for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
         uint32_t gt = 0, eq = 0;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const uint32_t j = c * 4096u + s * 1024u + threadIdx.x * 4u;
-            if (j < d) {
-                const float4 v = *reinterpret_cast<const float4*>(row + j);
-                const float vv[4] = {v.x, v.y, v.z, v.w};
+            if (j < v.count) {
+                const float4 x = *reinterpret_cast<const float4*>(v.row + j);
+                const float vv[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    if (j + m < d) {
+                    if (j + m < v.count) {
                         const uint32_t key = mag_key(vv[m]);
                         gt += key > T;
                         eq += key == T;
@@ -346,25 +576,75 @@ __global__ __launch_bounds__(256) void k_chunk_count(const float* __restrict__ e
         if (lane_id() == 0) { red[threadIdx.x >> 6] = wave_gt; red[4 + (threadIdx.x >> 6)] = wave_eq; }
         __syncthreads();
         if (threadIdx.x == 0) {
-            cnt_gt[(uint64_t)w * nchunks + c] = red[0] + red[1] + red[2] + red[3];
-            cnt_eq[(uint64_t)w * nchunks + c] = red[4] + red[5] + red[6] + red[7];
+            cnt_gt[(uint64_t)w * stride + c] = red[0] + red[1] + red[2] + red[3];
+            cnt_eq[(uint64_t)w * stride + c] = red[4] + red[5] + red[6] + red[7];
         }
         __syncthreads();
     }
 }
 
+// Filter bound for the next iteration and reset of the slot counters (one thread per worker,
+// called from k_chunk_scan).  After a whole-row search the bound starts from the exact
+// magnitude of rank kb.  After a candidate search it starts from the magnitude of rank
+// min(kb, M) among the M candidates; when fewer than kb were caught it is lowered further,
+// assuming the count keeps growing towards smaller magnitudes at the rate seen between T and
+// the old bound.  The error buffers drift (they ramp up while the model is far from its
+// optimum and relax later), so the bound is then moved by the factor the threshold is
+// expected to move by: linear extrapolation of the last two thresholds,
+// T_next / T = 2 - T_prev / T.  The bound only decides which search runs; the selection
+// itself is exact either way.
+__device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k, uint32_t kb,
+                                           uint32_t* bound, const uint32_t* cand_total,
+                                           uint32_t* cand_count, uint32_t* overflow) {
+    uint32_t nb = sel[w].next_bound;
+    const uint32_t T = sel[w].T;
+    if (sel[w].active == 0u) {
+        const uint32_t M = cand_total[w], L = bound[w];
+        if (M < kb) {
+            uint32_t drop = 1u << 19;                                   // about 6 % in magnitude
+            if (M > k && T > L) {
+                const float per_key = (float)(T - L) / (float)(M - k);   // pattern units per entry
+                const float want = per_key * (float)(kb - M);
+                drop = want >= 2097152.0f ? (1u << 21) : (uint32_t)want + 1u;
+            }
+            if (drop > (1u << 21)) drop = 1u << 21;
+            nb = L > drop ? L - drop : 0u;
+        }
+    }
+    if (sel[w].k_prev == k && sel[w].T_prev != 0u && T != 0u && T < 0x7f800000u && nb != 0u) {
+        float ratio = 2.0f - __uint_as_float(sel[w].T_prev) / __uint_as_float(T);
+        // a jump is not a trend: leave the bound where the last selection put it
+        if (ratio < 0.75f || ratio > 1.34f) ratio = 1.0f;
+        // a bound that is too high costs a whole-row search, one that is too low only a few
+        // more candidates: follow a rising threshold half way, a falling one fully
+        if (ratio > 1.0f) ratio = 1.0f + 0.5f * (ratio - 1.0f);
+        const float moved = __uint_as_float(nb) * ratio;
+        if (moved > 0.0f && moved < 3.0e38f) nb = __float_as_uint(moved);
+    }
+    sel[w].T_prev = T;
+    sel[w].k_prev = k;
+    sel[w].seen = cand_total[w];
+    bound[w] = nb;
+    cand_count[w] = 0u;
+    overflow[w] = 0u;
+}
+
 // One block of 1024 threads per worker walks the chunk counts in order and turns them into
 // eq_before[c] (entries equal to T before chunk c) and out_base[c] (message offset of the
 // chunk's first sent entry).  In place: cnt_eq -> eq_before, cnt_gt -> out_base.
-__global__ __launch_bounds__(1024) void k_chunk_scan(const SelState* __restrict__ sel,
+__global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __restrict__ sel,
                                                      uint32_t* __restrict__ cnt_gt,
-                                                     uint32_t* __restrict__ cnt_eq, uint32_t nchunks) {
+                                                     uint32_t* __restrict__ cnt_eq, uint32_t stride,
+                                                     uint32_t k, uint32_t kb, uint32_t* __restrict__ bound,
+                                                     uint32_t* __restrict__ cand_count,
+                                                     uint32_t* __restrict__ overflow) {
     __shared__ uint32_t lds[17];
     const uint32_t w = blockIdx.x;
-    if (!sel[w].active) return;
+    const View v = view_of(vs, sel, w);
+    const uint32_t nchunks = (v.count + 4095u) >> 12;
     const uint32_t r = sel[w].r;
-    uint32_t* gtp = cnt_gt + (uint64_t)w * nchunks;
-    uint32_t* eqp = cnt_eq + (uint64_t)w * nchunks;
+    uint32_t* gtp = cnt_gt + (uint64_t)w * stride;
+    uint32_t* eqp = cnt_eq + (uint64_t)w * stride;
     uint32_t eq_carry = 0, out_carry = 0;
     for (uint32_t base = 0; base < nchunks; base += 1024u) {
         const uint32_t c = base + threadIdx.x;
@@ -379,35 +659,40 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(const SelState* __restrict_
         eq_carry += eq_total;
         out_carry += out_total;
     }
+    if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, vs.cand_total, cand_count, overflow);
 }
 
-__global__ __launch_bounds__(256) void k_chunk_emit(float* __restrict__ e, uint64_t ld, uint32_t d,
-                                                    const SelState* __restrict__ sel,
+// Writes the message (ascending coordinate) and sets the sent entries of e to +0.  In a
+// candidate view map[pos] is the coordinate of entry pos; in a row view the position is the
+// coordinate.
+__global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState* __restrict__ sel,
                                                     const uint32_t* __restrict__ out_base,
                                                     const uint32_t* __restrict__ eq_before,
-                                                    uint32_t nchunks, uint32_t* __restrict__ msg_idx,
+                                                    uint32_t stride, float* __restrict__ e,
+                                                    uint32_t* __restrict__ msg_idx,
                                                     float* __restrict__ msg_val, uint64_t msg_ld,
                                                     uint32_t k) {
     __shared__ uint32_t lds[5];
     const uint32_t w = blockIdx.y;
-    if (!sel[w].active) return;
+    const View v = view_of(vs, sel, w);
+    const uint32_t nchunks = (v.count + 4095u) >> 12;
     const uint32_t T = sel[w].T, r = sel[w].r;
-    float* row = e + (uint64_t)w * ld;
+    float* erow = e + (uint64_t)w * vs.ld;
     uint32_t* oi = msg_idx + (uint64_t)w * msg_ld;
     float* ov = msg_val + (uint64_t)w * msg_ld;
     for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        uint32_t eq_run = eq_before[(uint64_t)w * nchunks + c];
-        uint32_t out_run = out_base[(uint64_t)w * nchunks + c];
+        uint32_t eq_run = eq_before[(uint64_t)w * stride + c];
+        uint32_t out_run = out_base[(uint64_t)w * stride + c];
         for (int s = 0; s < 4; ++s) {
             const uint32_t j = c * 4096u + s * 1024u + threadIdx.x * 4u;
             float vv[4] = {0.f, 0.f, 0.f, 0.f};
             uint32_t key[4] = {0, 0, 0, 0};
             bool valid[4] = {false, false, false, false};
-            if (j < d) {
-                const float4 v = *reinterpret_cast<const float4*>(row + j);
-                vv[0] = v.x; vv[1] = v.y; vv[2] = v.z; vv[3] = v.w;
+            if (j < v.count) {
+                const float4 x = *reinterpret_cast<const float4*>(v.row + j);
+                vv[0] = x.x; vv[1] = x.y; vv[2] = x.z; vv[3] = x.w;
 #pragma unroll
-                for (int m = 0; m < 4; ++m) { valid[m] = j + m < d; key[m] = mag_key(vv[m]); }
+                for (int m = 0; m < 4; ++m) { valid[m] = j + m < v.count; key[m] = mag_key(vv[m]); }
             }
             uint32_t neq = 0;
 #pragma unroll
@@ -431,9 +716,10 @@ __global__ __launch_bounds__(256) void k_chunk_emit(float* __restrict__ e, uint6
 #pragma unroll
             for (int m = 0; m < 4; ++m)
                 if (send[m]) {
-                    if (pos < k) { oi[pos] = j + m; ov[pos] = vv[m]; }
+                    const uint32_t coord = v.map ? v.map[j + m] : j + m;
+                    if (pos < k) { oi[pos] = coord; ov[pos] = vv[m]; }
                     ++pos;
-                    row[j + m] = 0.0f;
+                    erow[coord] = 0.0f;
                 }
             eq_run += eq_total;
             out_run += send_total;
@@ -484,15 +770,6 @@ __global__ __launch_bounds__(256) void k_copy_f4(const float* __restrict__ src, 
     for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads;
          q += (uint64_t)gridDim.x * blockDim.x)
         reinterpret_cast<float4*>(dst)[q] = reinterpret_cast<const float4*>(src)[q];
-}
-
-// Start of a selection: rank 0 looks for the k-th entry, rank 1 for the kb-th.
-__global__ void k_sel_begin(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t all_active) {
-    const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
-    if (w >= n) return;
-    if (all_active) sel[w].active = 1;
-    sel[w].prefix[0] = 0; sel[w].prefix[1] = 0;
-    sel[w].krem[0] = k; sel[w].krem[1] = kb;
 }
 
 }  // namespace ddef

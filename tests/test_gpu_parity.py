@@ -275,3 +275,76 @@ def test_empty_iterations_before_tau(ddef):
     assert len(c.get_message(0)[0]) == 500
     assert not np.array_equal(bits(c.get_model()), bits(x0))
     c.close()
+
+
+# ---- candidate filter: used in the steady state, abandoned safely when its bound is off -------------
+def test_filter_path_is_used_and_matches_full_search(ddef, oracle_mod):
+    w = workloads.get("C3", d=400_000, n=4)
+    lam, xstar, x0 = workloads.make_problem(w)
+    a = ddef.Context(w.d, w.n, 0)
+    b = ddef.Context(w.d, w.n, 0)
+    b.set_option(ddef.OPT_FORCE_FULL_SELECT, 1)
+    o = oracle_mod.Oracle(w.d, w.n, 0, threads=4)
+    for h in (a, b, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(0)
+    steps = 12
+    for t in range(steps):
+        a.step(0.002, w.lr); b.step(0.002, w.lr); o.step(0.002, w.lr)
+        assert_step_state_equal(a, o, w.n, what=("filter", t))
+        assert_step_state_equal(b, o, w.n, what=("full", t))
+        assert_model_equal(a, o, what=("filter", t))
+    assert b.full_select_count() == steps * w.n
+    # the first step has no bound and the second no trend yet; afterwards the filter should
+    # carry nearly every selection
+    assert a.full_select_count() <= 3 * w.n, a.full_select_count()
+    a.close(); b.close()
+
+
+def test_filter_bound_too_high_and_too_low_fall_back(ddef, oracle_mod):
+    d, n = 300_000, 2
+    g = ddef.Context(d, n, 0)
+    o = oracle_mod.Oracle(d, n, 0)
+    zero = np.zeros(d, dtype=F32)
+    for h in (g, o):
+        h.set_problem(np.ones(d, dtype=F32), zero, zero, 1, 0, 0.0)
+    delta = 0.004
+    scales = [1.0, 1.0, 1e-3, 1e-3, 1e3, 1e3, 1.0, 0.5, 2.0, 1.0]
+    fulls = []
+    for step, sc in enumerate(scales):
+        for i in range(n):
+            v = workloads.random_vector(77 * step + i, d, "normal") * F32(sc)
+            g.set_error(i, zero); o.set_error(i, zero)
+            g.load_grad(i, v); o.load_grad(i, v)
+        g.ef_compress(delta, 1.0); o.ef_compress(delta, 1.0)
+        assert_step_state_equal(g, o, n, check_grad=False, what=("scale", step, sc))
+        g.aggregate(); o.aggregate(); g.apply_delayed(1.0); o.apply_delayed()
+        assert_model_equal(g, o, what=("scale", step))
+        fulls.append(g.full_select_count())
+    # step 0: no bound. step 2: magnitudes dropped 1000x -> too few candidates. step 4: rose
+    # 10^6x -> candidate buffer overflows.  Each must have taken the whole-row search.
+    assert fulls[0] == n and fulls[1] == n
+    assert fulls[2] == 2 * n and fulls[3] == 2 * n
+    assert fulls[4] == 3 * n and fulls[5] == 3 * n
+    g.close()
+
+
+def test_filter_with_ties_at_the_threshold(ddef, oracle_mod):
+    d, n = 200_000, 1
+    g = ddef.Context(d, n, 0)
+    o = oracle_mod.Oracle(d, n, 0)
+    zero = np.zeros(d, dtype=F32)
+    for h in (g, o):
+        h.set_problem(np.ones(d, dtype=F32), zero, zero, 1, 0, 0.0)
+    rng = np.random.default_rng(3)
+    for step in range(6):
+        # few distinct magnitudes: the threshold group is large and only partly sent
+        v = (rng.integers(0, 40, size=d).astype(F32) * F32(0.125)) * rng.choice([-1, 1], size=d).astype(F32)
+        g.set_error(0, zero); o.set_error(0, zero)
+        g.load_grad(0, v); o.load_grad(0, v)
+        delta = [0.01, 0.01, 0.012, 0.03, 0.03, 0.005][step]
+        g.ef_compress(delta, 1.0); o.ef_compress(delta, 1.0)
+        assert_step_state_equal(g, o, n, check_grad=False, what=("ties", step))
+        g.aggregate(); o.aggregate(); g.apply_delayed(1.0); o.apply_delayed()
+    assert g.full_select_count() < 6
+    g.close()
