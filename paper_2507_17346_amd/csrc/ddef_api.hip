@@ -44,10 +44,11 @@ struct ddef_ctx {
     uint64_t msg_ld = 0;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
-    // candidate filter: per-worker words [bound | cand_count | overflow | stat_full | cand_total],
-    // the run table per 1024-entry wave-chunk with its prefixes, and the candidate buffers of
-    // `cap` entries per worker
+    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total], slot
+    // counters [n][kSubs], the run table per 256-entry group with its prefixes, and the
+    // candidate buffers of `cap` entries per worker
     uint32_t* filt = nullptr;
+    uint32_t* cand_count = nullptr;
     uint2* tab = nullptr;
     uint32_t* obase = nullptr;
     uint32_t* span_sum = nullptr;
@@ -166,9 +167,10 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
     }
     // room for the candidates: three times the target while messages are sparse, twice otherwise
     const bool sparse = k * 32u <= c->d;
-    // plus one page per wave of the filter kernel's grid: the unused end of a wave's last page
-    const uint64_t waves = (uint64_t)blocks_for(c, c->nchunks, c->n, 8) * 4u;
-    uint64_t want = ((sparse ? 3u : 2u) * kb + waves * kPage + 8191u) & ~(uint64_t)4095u;
+    // and at least 32 slots in each of the kSubs parts of the buffer
+    uint64_t want = (sparse ? 3u : 2u) * kb;
+    if (want < 32u * kSubs) want = 32u * kSubs;
+    want = (want + 4095u) & ~(uint64_t)4095u;
     if (want > c->ld) want = c->ld;
     if (want > c->cap) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -189,7 +191,7 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
 // Radix select and ordered compaction of every worker through its view (candidates or row).
 void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, bool rows_only) {
     const uint32_t n = c->n;
-    uint32_t *bound = c->filt, *cand_count = c->filt + n, *overflow = c->filt + 2 * n, *cand_total = c->filt + 4 * n;
+    uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *cand_total = c->filt + 3 * n;
     const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sorted_val, c->sorted_idx, c->cap, cand_total};
     // grids sized for the longest view that can occur (any worker may have to search its row)
     (void)rows_only;
@@ -291,7 +293,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     c->d = d; c->n = n; c->tau_max = tau_max; c->tau = tau_max;
     c->ld = (d + 4095u) & ~(uint64_t)4095u;
     c->nchunks = (uint32_t)(c->ld / 4096u);
-    c->nwc = (uint32_t)(c->ld / 1024u);
+    c->nwc = (uint32_t)(c->ld / 256u);          // 256-entry groups of the filter kernel
     c->nspans = (c->nwc + 8191u) / 8192u;
     if (hipStreamCreateWithFlags(&c->own_stream, hipStreamNonBlocking) != hipSuccess) return fail(DDEF_EHIP);
     c->stream = c->own_stream;
@@ -302,7 +304,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
         {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
-        {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->filt, (size_t)4 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->obase, (size_t)n * c->nwc * 4}, {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
     };
     for (const Want& w : wants) {
@@ -324,7 +326,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->tab, c->obase, c->span_sum, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->obase, c->span_sum, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -359,7 +361,8 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
-    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)5 * c->n * 4));
+    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)4 * c->n * 4));
+    HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * 4));
     c->have_bound = false;
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
@@ -427,13 +430,12 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     rc = ensure_capacity(c, k, kb);
     if (rc) return rc;
     const uint32_t n = c->n;
-    uint32_t *bound = c->filt, *cand_count = c->filt + n, *overflow = c->filt + 2 * n, *stat_full = c->filt + 3 * n;
+    uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
-    const uint32_t gx = blocks_for(c, c->nchunks, n, 8);
-    LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(gx, n), dim3(256), c->e, c->g, c->ld, (uint32_t)c->d, lr,
+    LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
            (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
-    uint32_t* cand_total = c->filt + 4 * n;
+    uint32_t* cand_total = c->filt + 3 * n;
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
@@ -639,7 +641,7 @@ int ddef_full_select_count(ddef_ctx* c, uint64_t* count) {
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     std::vector<uint32_t> fell_back(c->n, 0u);
-    HIP_TRY(c, hipMemcpy(fell_back.data(), c->filt + 3 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(fell_back.data(), c->filt + 2 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
     uint64_t total = c->full_selects;
     for (uint32_t v : fell_back) total += v;
     *count = total;

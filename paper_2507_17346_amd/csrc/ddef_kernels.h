@@ -6,8 +6,8 @@
 
 namespace ddef {
 
-// Candidate slots are handed to a wave in pages of this many entries.
-constexpr uint32_t kPage = 128;
+// A worker's candidate buffer is split into this many parts, each with its own slot counter.
+constexpr uint32_t kSubs = 256;
 
 // Per-worker selection state in device memory.
 struct SelState {
@@ -39,7 +39,7 @@ __global__ void k_grad(const float* lambda, const float* xstar, const float* xs,
                        uint32_t t_lo, uint32_t t_hi, int kind, float scale);
 __global__ void k_ef_filter(float* e, const float* g, uint64_t ld, uint32_t d, float lr,
                             const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
-                            uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t nwc);
+                            uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups);
 __global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
 __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
                              uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,

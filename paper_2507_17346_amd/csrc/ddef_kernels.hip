@@ -67,6 +67,11 @@ __device__ __forceinline__ float4 load_stream4(const float* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ void store_stream4(float* p, const float (&v)[4]) {
+    const vec4f x = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(x, reinterpret_cast<vec4f*>(p));
+}
+
 __device__ __forceinline__ uint32_t mag_key(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
 // ------------------------------------------------------------------------------------
@@ -190,115 +195,75 @@ __global__ __launch_bounds__(256) void k_grad(const float* __restrict__ lambda,
 // ------------------------------------------------------------------------------------
 // S1 (+ candidate filter of S2/S3)   p = e + lr * g, written over e   (Algorithm 1, worker side)
 //
-// grid (gx, n): blockIdx.y is the worker; a block strides over 4096-element chunks and each
-// of its four waves owns 1024 consecutive coordinates of the chunk (four 16-byte accesses
-// per lane, all issued before the first use).  While p is in registers, every entry whose
-// magnitude pattern is >= bound[w] is a *candidate* for the top-k.  The wave counts its
-// candidates with ballots and writes them as (index, value) pairs, in index order, into a
-// run of slots of the worker's candidate buffer; tab[w][wave-chunk] records (first slot,
-// count), so that the runs can be read back in coordinate order although slots are handed
-// out in arbitrary order.  Slots come from pages of kPage entries that a wave reserves with
-// one atomic add and fills with consecutive runs (a run never straddles pages; the unused
-// end of a page is lost), which keeps the atomics off the critical path.
+// grid (ld/256, n), one wave per block: the wave owns 256 consecutive coordinates of worker
+// blockIdx.y, one 16-byte access per lane and array.  (Single-wave blocks over a grid in
+// address order stream markedly faster on this chip than persistent blocks striding over
+// the row.)  While p is in registers, every entry whose magnitude pattern is >= bound[w] is
+// a *candidate* for the top-k.  The wave counts its candidates with ballots, reserves that
+// many slots with one atomic add and writes (index, value) pairs there in index order;
+// tab[w][group] records (first slot, count), so that the runs can be read back in coordinate
+// order although slots are handed out in arbitrary order.  To keep the atomics from
+// serialising on one address, a worker's candidate buffer is split into kSubs equal parts
+// with a counter each, and group number mod kSubs picks the part.
 // With use_filter == 0 this is the plain accumulate pass.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
-                                                   uint64_t ld, uint32_t d, float lr,
-                                                   const uint32_t* __restrict__ bound, int use_filter,
-                                                   uint2* __restrict__ cand, uint64_t cap,
-                                                   uint32_t* __restrict__ cand_count,
-                                                   uint32_t* __restrict__ overflow,
-                                                   uint2* __restrict__ tab, uint32_t nwc) {
-    const uint32_t w = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
-    const uint32_t L = use_filter ? bound[w] : 0xffffffffu;
-    float* er = e + (uint64_t)w * ld;
-    const float* gr = g + (uint64_t)w * ld;
-    uint2* cw = cand + (uint64_t)w * cap;
-    uint2* tw = tab + (uint64_t)w * nwc;
-    const uint32_t nchunks = nwc >> 2;
-    uint32_t page_pos = 0, page_end = 0;      // this wave's current page: free slots [pos, end)
-    bool lost = false;                        // the candidate buffer ran out
-    for (uint32_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
-        const uint32_t wc = chunk * 4u + wave;
-        const uint32_t j0 = wc * 1024u + lane * 4u;
-        float4 ev[4], gv[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const uint32_t j = j0 + it * 256u;
-            if (j < d) {
-                ev[it] = *reinterpret_cast<const float4*>(er + j);
-                gv[it] = load_stream4(gr + j);
-            } else {
-                ev[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                gv[it] = ev[it];
-            }
-        }
-        float pv[4][4];
-        uint32_t total = 0;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const uint32_t j = j0 + it * 256u;
-            pv[it][0] = ev[it].x + lr * gv[it].x;
-            pv[it][1] = ev[it].y + lr * gv[it].y;
-            pv[it][2] = ev[it].z + lr * gv[it].z;
-            pv[it][3] = ev[it].w + lr * gv[it].w;
-            if (j < d) *reinterpret_cast<float4*>(er + j) = make_float4(pv[it][0], pv[it][1], pv[it][2], pv[it][3]);
-            bool any = false;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) any |= (j + c < d) && mag_key(pv[it][c]) >= L;
-            // cheap test first: most 256-entry groups hold no candidate at all
-            if (__ballot(any)) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    total += (uint32_t)__popcll(__ballot((j + c < d) && mag_key(pv[it][c]) >= L));
-            }
-        }
-        uint32_t base = 0;
-        if (total) {
-            if (page_pos + total > page_end && !lost) {
-                const uint32_t want = (total + kPage - 1u) / kPage * kPage;
-                uint32_t got = 0;
-                if (lane == 0) got = atomicAdd(&cand_count[w], want);
-                got = __shfl(got, 0, 64);
-                if ((uint64_t)got + want > cap) {
-                    lost = true;
-                    if (lane == 0) overflow[w] = 1u;
-                } else {
-                    page_pos = got;
-                    page_end = got + want;
-                }
-            }
-            if (!lost) {
-                base = page_pos;
-                page_pos += total;
-                uint32_t run = base;
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    const uint32_t j = j0 + it * 256u;
-                    uint32_t below = 0, in_group = 0;
-                    bool f[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        f[c] = (j + c < d) && mag_key(pv[it][c]) >= L;
-                        const uint64_t m = __ballot(f[c]);
-                        below += mask_rank(m);
-                        in_group += (uint32_t)__popcll(m);
-                    }
-                    uint32_t pos = run + below;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[it][c])); ++pos; }
-                    run += in_group;
-                }
-            }
-        }
-        if (lane == 0) tw[wc] = make_uint2(base, total);
+__global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
+                                                  uint64_t ld, uint32_t d, float lr,
+                                                  const uint32_t* __restrict__ bound, int use_filter,
+                                                  uint2* __restrict__ cand, uint64_t cap,
+                                                  uint32_t* __restrict__ cand_count,
+                                                  uint32_t* __restrict__ overflow,
+                                                  uint2* __restrict__ tab, uint32_t ngroups) {
+    const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
+    const uint32_t j = grp * 256u + lane * 4u;
+    float pv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j < d) {
+        float* ep = e + (uint64_t)w * ld + j;
+        const float4 ev = load_stream4(ep);
+        const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
+        pv[0] = ev.x + lr * gv.x;
+        pv[1] = ev.y + lr * gv.y;
+        pv[2] = ev.z + lr * gv.z;
+        pv[3] = ev.w + lr * gv.w;
+        store_stream4(ep, pv);
     }
+    if (!use_filter) return;
+    const uint32_t L = bound[w];
+    bool f[4];
+    bool any = false;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { f[c] = (j + c < d) && mag_key(pv[c]) >= L; any |= f[c]; }
+    uint32_t first = 0, total = 0;
+    if (__ballot(any)) {                       // most groups hold no candidate at all
+        uint32_t below = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint64_t m = __ballot(f[c]);
+            below += mask_rank(m);
+            total += (uint32_t)__popcll(m);
+        }
+        const uint32_t sub = grp & (kSubs - 1u);
+        const uint32_t sub_cap = (uint32_t)(cap / kSubs);
+        uint32_t got = 0;
+        if (lane == 0) got = atomicAdd(&cand_count[w * kSubs + sub], total);
+        got = __shfl(got, 0, 64);
+        if (got + total > sub_cap) {
+            if (lane == 0) overflow[w] = 1u;
+        } else {
+            first = sub * sub_cap + got;
+            uint2* cw = cand + (uint64_t)w * cap;
+            uint32_t pos = first + below;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
+        }
+    }
+    if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
 }
 
 // ---- run table -> coordinate order ------------------------------------------------------
-// tab[w][c].y is the run length of wave-chunk c.  Three small kernels turn the lengths into
-// exclusive prefixes obase[w][c]: sums over spans of 8192 wave-chunks, a scan of the span
+// tab[w][c].y is the run length of group c.  Three small kernels turn the lengths into
+// exclusive prefixes obase[w][c]: sums over spans of 8192 groups, a scan of the span
 // sums that also decides whether the filter caught enough, and the prefixes inside a span.
 constexpr uint32_t kSpan = 8192;
 
@@ -405,7 +370,7 @@ __global__ __launch_bounds__(1024) void k_tab_offsets(const uint2* __restrict__ 
     }
 }
 
-// Candidate m in coordinate order lives in the run of the last wave-chunk c with
+// Candidate m in coordinate order lives in the run of the last group c with
 // obase[c] <= m, at offset m - obase[c] from the run's first slot.  Writes the ordered
 // candidates as two arrays (index, value).
 __global__ __launch_bounds__(256) void k_cand_gather(const uint2* __restrict__ cand, uint64_t cap,
@@ -583,8 +548,7 @@ __global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState
     }
 }
 
-// Filter bound for the next iteration and reset of the slot counters (one thread per worker,
-// called from k_chunk_scan).  After a whole-row search the bound starts from the exact
+// Filter bound for the next iteration (one thread per worker, called from k_chunk_scan).  After a whole-row search the bound starts from the exact
 // magnitude of rank kb.  After a candidate search it starts from the magnitude of rank
 // min(kb, M) among the M candidates; when fewer than kb were caught it is lowered further,
 // assuming the count keeps growing towards smaller magnitudes at the rate seen between T and
@@ -595,7 +559,7 @@ __global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState
 // itself is exact either way.
 __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k, uint32_t kb,
                                            uint32_t* bound, const uint32_t* cand_total,
-                                           uint32_t* cand_count, uint32_t* overflow) {
+                                           uint32_t* overflow) {
     uint32_t nb = sel[w].next_bound;
     const uint32_t T = sel[w].T;
     if (sel[w].active == 0u) {
@@ -625,7 +589,6 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
     sel[w].k_prev = k;
     sel[w].seen = cand_total[w];
     bound[w] = nb;
-    cand_count[w] = 0u;
     overflow[w] = 0u;
 }
 
@@ -659,7 +622,8 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __re
         eq_carry += eq_total;
         out_carry += out_total;
     }
-    if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, vs.cand_total, cand_count, overflow);
+    if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, vs.cand_total, overflow);
+    for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[w * kSubs + q] = 0u;
 }
 
 // Writes the message (ascending coordinate) and sets the sent entries of e to +0.  In a
