@@ -19,14 +19,14 @@ namespace {
 enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
-    SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_OFFSETS, SL_CAND_GATHER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_FILL, SL_SCATTER_ADD,
+    SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_SCATTER_ADD,
     SL_APPLY, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
-    "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_offsets", "k_cand_gather",
+    "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_fill_u32", "k_scatter_add", "k_apply"};
+    "k_unscatter", "k_scatter_add", "k_apply"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -50,7 +50,6 @@ struct ddef_ctx {
     uint32_t* filt = nullptr;
     uint32_t* cand_count = nullptr;
     uint2* tab = nullptr;
-    uint32_t* obase = nullptr;
     uint32_t* span_sum = nullptr;
     uint32_t nwc = 0, nspans = 0;
     uint2* cand = nullptr;
@@ -58,6 +57,8 @@ struct ddef_ctx {
     float* sorted_val = nullptr;
     uint64_t cap = 0;
     bool have_bound = false;
+    // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each)
+    uint64_t u_dirty_k = 0;
     Phase phase = PH_IDLE;
     bool problem_set = false, step_empty = true;
     float lr_step = 0.0f;
@@ -212,6 +213,16 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, bool rows_only) {
            c->msg_ld, k);
 }
 
+// Puts U back to all-zero by clearing only the coordinates the last aggregate wrote.  Must
+// run before the message buffers are overwritten or reallocated.
+void clean_update(ddef_ctx* c) {
+    if (!c->u_dirty_k) return;
+    const uint32_t k = (uint32_t)c->u_dirty_k;
+    LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256), c->U,
+           (const uint32_t*)c->msg_idx, c->msg_ld, k, (uint32_t)c->d);
+    c->u_dirty_k = 0;
+}
+
 int check_ctx(ddef_ctx* c) {
     if (!c) return DDEF_EINVAL;
     if (c->sticky != DDEF_OK) return c->sticky;
@@ -305,7 +316,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
         {(void**)&c->filt, (size_t)4 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
-        {(void**)&c->obase, (size_t)n * c->nwc * 4}, {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
+        {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
     };
     for (const Want& w : wants) {
         err = hipMalloc(w.p, w.bytes);
@@ -326,7 +337,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->obase, c->span_sum, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -367,6 +378,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
+    c->u_dirty_k = 0;
     return DDEF_OK;
 }
 
@@ -423,6 +435,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         return DDEF_OK;
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
+    clean_update(c);
     // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
     uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
     if (kb < k) kb = k;
@@ -442,12 +455,9 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide, dim3(n), dim3(256), c->span_sum, c->nspans,
                (const uint32_t*)overflow, (uint32_t)k, (uint32_t)kb, (uint32_t)c->d, n, c->sel, cand_total,
                stat_full, c->hist);
-        LAUNCH(c, SL_TAB_OFFSETS, k_tab_offsets, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
-               (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, c->obase);
-        const uint32_t gg = blocks_for(c, (c->cap + 255) / 256, n, 8);
-        LAUNCH(c, SL_CAND_GATHER, k_cand_gather, dim3(gg, n), dim3(256), (const uint2*)c->cand, c->cap,
-               (const uint2*)c->tab, (const uint32_t*)c->obase, c->nwc, (const uint32_t*)cand_total,
-               (const SelState*)c->sel, c->sorted_idx, c->sorted_val);
+        LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
+               c->sorted_idx, c->sorted_val);
     } else {
         LAUNCH(c, SL_SEL_BEGIN_ROWS, k_sel_begin_rows, dim3(n), dim3(256), c->sel, n, (uint32_t)k, (uint32_t)kb,
                (uint32_t)c->d, cand_total, c->hist);
@@ -466,15 +476,14 @@ int ddef_aggregate(ddef_ctx* c) {
     if (rc) return rc;
     if (c->phase != PH_COMPRESSED) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
-    const uint64_t words = c->ld;
-    LAUNCH(c, SL_FILL, k_fill_u32, dim3(blocks_for(c, (words + 255) / 256, 1, 32)), dim3(256),
-           (uint32_t*)c->U, words, 0u);
+    clean_update(c);
     if (c->k_step) {
         const uint32_t k = (uint32_t)c->k_step;
         const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
         for (uint32_t i = 0; i < c->n; ++i)
             LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U,
                    c->msg_idx + (uint64_t)i * c->msg_ld, c->msg_val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
+        c->u_dirty_k = c->k_step;
     }
     HIP_TRY(c, hipGetLastError());
     c->phase = PH_AGGREGATED;
@@ -488,7 +497,7 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
     if (std::memcmp(&lr, &c->lr_step, sizeof(float)) != 0) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     const uint64_t quads = (c->d + 3) / 4;
-    LAUNCH(c, SL_APPLY, k_apply, dim3(blocks_for(c, (quads + 255) / 256, 1, 32)), dim3(256), c->slot(c->t),
+    LAUNCH(c, SL_APPLY, k_apply, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->slot(c->t),
            c->U, c->slot(c->t + 1), (uint32_t)c->d, (float)c->n);
     HIP_TRY(c, hipGetLastError());
     c->t += 1;

@@ -46,11 +46,9 @@ __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t
                              uint32_t* stat_full, uint32_t* hist);
 __global__ void k_sel_begin_rows(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t d,
                                  uint32_t* cand_total, uint32_t* hist);
-__global__ void k_tab_offsets(const uint2* tab, uint32_t nwc, const uint32_t* span_off, uint32_t nspans,
-                              const SelState* sel, uint32_t* obase);
-__global__ void k_cand_gather(const uint2* cand, uint64_t cap, const uint2* tab, const uint32_t* obase,
-                              uint32_t nwc, const uint32_t* cand_total, const SelState* sel,
-                              uint32_t* sorted_idx, float* sorted_val);
+__global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* span_off, uint32_t nspans,
+                            const SelState* sel, const uint2* cand, uint64_t cap, uint32_t* sorted_idx,
+                            float* sorted_val);
 __global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);
 __global__ void k_digit_pick(SelState* sel, const uint32_t* hist, int level);
 __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
@@ -63,6 +61,7 @@ __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* o
                              float* msg_val, uint64_t msg_ld, uint32_t k);
 __global__ void k_scatter_add(float* U, const uint32_t* idx, const float* val, uint32_t k, uint32_t d);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
+__global__ void k_unscatter(float* U, const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t d);
 __global__ void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);
 

@@ -85,10 +85,11 @@ __device__ __forceinline__ U4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2
                                            uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        const uint32_t y0 = hi1 ^ c1 ^ k0, y2 = hi0 ^ c3 ^ k1;
-        c0 = y0; c1 = lo1; c2 = y2; c3 = lo0;
+        // one 32x32->64 multiply per product (both halves are needed)
+        const uint64_t prod0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t prod1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t y0 = (uint32_t)(prod1 >> 32) ^ c1 ^ k0, y2 = (uint32_t)(prod0 >> 32) ^ c3 ^ k1;
+        c0 = y0; c1 = (uint32_t)prod1; c2 = y2; c3 = (uint32_t)prod0;
         k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
     }
     return U4{c0, c1, c2, c3};
@@ -264,7 +265,8 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
 // ---- run table -> coordinate order ------------------------------------------------------
 // tab[w][c].y is the run length of group c.  Three small kernels turn the lengths into
 // exclusive prefixes obase[w][c]: sums over spans of 8192 groups, a scan of the span
-// sums that also decides whether the filter caught enough, and the prefixes inside a span.
+// sums that also decides whether the filter caught enough, and the prefixes inside a span,
+// which drive the copy of the runs into coordinate order.
 constexpr uint32_t kSpan = 8192;
 
 __global__ __launch_bounds__(1024) void k_tab_sum(const uint2* __restrict__ tab, uint32_t nwc,
@@ -345,57 +347,41 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
     begin_selection(sel, w, n, k, kb, d, hist);
 }
 
-__global__ __launch_bounds__(1024) void k_tab_offsets(const uint2* __restrict__ tab, uint32_t nwc,
-                                                      const uint32_t* __restrict__ span_off,
-                                                      uint32_t nspans, const SelState* __restrict__ sel,
-                                                      uint32_t* __restrict__ obase) {
+// Prefixes inside a span, and with them the candidates in coordinate order: group c's run
+// cand[first .. first+len) goes to positions [at, at+len) of the ordered arrays (index,
+// value).  A run holds at most 256 entries, so the per-thread copy loops are short.
+__global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ tab, uint32_t ngroups,
+                                                    const uint32_t* __restrict__ span_off,
+                                                    uint32_t nspans, const SelState* __restrict__ sel,
+                                                    const uint2* __restrict__ cand, uint64_t cap,
+                                                    uint32_t* __restrict__ sorted_idx,
+                                                    float* __restrict__ sorted_val) {
     __shared__ uint32_t lds[17];
     const uint32_t w = blockIdx.y, sp = blockIdx.x;
     if (sel[w].active) return;
-    const uint2* tw = tab + (uint64_t)w * nwc;
-    uint32_t* ow = obase + (uint64_t)w * nwc;
+    const uint2* tw = tab + (uint64_t)w * ngroups;
+    const uint2* cw = cand + (uint64_t)w * cap;
+    uint32_t* oi = sorted_idx + (uint64_t)w * cap;
+    float* ov = sorted_val + (uint64_t)w * cap;
     const uint32_t c0 = sp * kSpan + threadIdx.x * 8u;
-    uint32_t len[8], mine = 0;
+    uint2 run[8];
+    uint32_t mine = 0;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        len[q] = (c0 + q < nwc) ? tw[c0 + q].y : 0u;
-        mine += len[q];
+        run[q] = (c0 + q < ngroups) ? tw[c0 + q] : make_uint2(0u, 0u);
+        mine += run[q].y;
     }
     uint32_t total;
     uint32_t at = span_off[(uint64_t)w * nspans + sp] + block_excl_scan(mine, lds, &total);
+    if (mine == 0u) return;
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        if (c0 + q < nwc) ow[c0 + q] = at;
-        at += len[q];
-    }
-}
-
-// Candidate m in coordinate order lives in the run of the last group c with
-// obase[c] <= m, at offset m - obase[c] from the run's first slot.  Writes the ordered
-// candidates as two arrays (index, value).
-__global__ __launch_bounds__(256) void k_cand_gather(const uint2* __restrict__ cand, uint64_t cap,
-                                                     const uint2* __restrict__ tab,
-                                                     const uint32_t* __restrict__ obase, uint32_t nwc,
-                                                     const uint32_t* __restrict__ cand_total,
-                                                     const SelState* __restrict__ sel,
-                                                     uint32_t* __restrict__ sorted_idx,
-                                                     float* __restrict__ sorted_val) {
-    const uint32_t w = blockIdx.y;
-    if (sel[w].active) return;
-    const uint32_t M = cand_total[w];
-    const uint2* cw = cand + (uint64_t)w * cap;
-    const uint2* tw = tab + (uint64_t)w * nwc;
-    const uint32_t* ow = obase + (uint64_t)w * nwc;
-    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < M; m += gridDim.x * blockDim.x) {
-        uint32_t lo = 0, hi = nwc;                 // first c in [lo, hi) with obase[c] > m
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (ow[mid] > m) hi = mid; else lo = mid + 1u;
+        for (uint32_t m = 0; m < run[q].y; ++m) {
+            const uint2 item = cw[run[q].x + m];
+            oi[at + m] = item.x;
+            ov[at + m] = __uint_as_float(item.y);
         }
-        const uint32_t c = lo - 1u;                // obase[0] = 0 <= m, so lo >= 1
-        const uint2 item = cw[tw[c].x + (m - ow[c])];
-        sorted_idx[(uint64_t)w * cap + m] = item.x;
-        sorted_val[(uint64_t)w * cap + m] = __uint_as_float(item.y);
+        at += run[q].y;
     }
 }
 
@@ -707,19 +693,30 @@ __global__ __launch_bounds__(256) void k_scatter_add(float* __restrict__ U,
 }
 
 // S5  x_{t+1} = x_t - U / n, written into the next ring slot (may alias x_t when the ring
-// has a single slot: element-wise, so in place is fine).
-__global__ __launch_bounds__(256) void k_apply(const float* x, const float* __restrict__ U,
-                                               float* xn, uint32_t d, float nf) {
-    const uint32_t quads = (d + 3u) >> 2;
-    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
-        const float4 xv = reinterpret_cast<const float4*>(x)[q];
-        const float4 uv = reinterpret_cast<const float4*>(U)[q];
-        float4 o;
-        o.x = xv.x - uv.x / nf;
-        o.y = xv.y - uv.y / nf;
-        o.z = xv.z - uv.z / nf;
-        o.w = xv.w - uv.w / nf;
-        reinterpret_cast<float4*>(xn)[q] = o;
+// has a single slot: element-wise, so in place is fine).  One quad per thread, single-wave
+// blocks in address order.
+__global__ __launch_bounds__(64) void k_apply(const float* x, const float* __restrict__ U, float* xn,
+                                              uint32_t d, float nf) {
+    const uint32_t q = blockIdx.x * 64u + threadIdx.x;
+    if (q >= ((d + 3u) >> 2)) return;
+    const float4 xv = reinterpret_cast<const float4*>(x)[q];
+    const float4 uv = load_stream4(U + ((uint64_t)q << 2));
+    float4 o;
+    o.x = xv.x - uv.x / nf;
+    o.y = xv.y - uv.y / nf;
+    o.z = xv.z - uv.z / nf;
+    o.w = xv.w - uv.w / nf;
+    reinterpret_cast<float4*>(xn)[q] = o;
+}
+
+// U[j] <- +0 at every coordinate of the last messages (all workers, grid (gx, n)): puts U
+// back to all-zero without touching the other d - n*k entries.
+__global__ __launch_bounds__(256) void k_unscatter(float* __restrict__ U, const uint32_t* __restrict__ idx,
+                                                   uint64_t msg_ld, uint32_t k, uint32_t d) {
+    const uint32_t* row = idx + (uint64_t)blockIdx.y * msg_ld;
+    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
+        const uint32_t j = row[m];
+        if (j < d) U[j] = 0.0f;
     }
 }
 
