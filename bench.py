@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--d", type=int, default=None, help="shrink d (debug only; not a valid bench)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="launch the plain copy yardstick this many times (for hardware byte counters)")
     ap.add_argument("--cpu-sample-d", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -132,6 +134,12 @@ def main():
         log(f"  {k:18s} launches/step {v['launches'] / args.steps:6.1f}  avg {v['avg_ms']:.4f} ms  "
             f"per step {v['ms_per_step']:.4f} ms")
     log("  per call (ms): " + ", ".join(f"{k} {v:.3f}" for k, v in phase_ms.items()))
+
+    if args.copy_probe:
+        for _ in range(args.copy_probe):
+            probe_bytes = ctx.copy_probe()
+        ctx.sync()
+        log(f"  copy yardstick: {args.copy_probe} launches of k_copy_f4, {probe_bytes} bytes read and written each")
 
     hot = [k for k in kernels if k != "k_grad"]
     dominant = max(hot, key=lambda k: kernels[k]["ms_per_step"])

@@ -138,6 +138,11 @@ int ddef_profile_enable(ddef_ctx* ctx, int on);
 int ddef_profile_slots(void);
 int ddef_profile_read(ddef_ctx* ctx, int slot, const char** name, uint64_t* launches,
                       double* total_ms);
+/* Yardstick for hardware byte counters: one launch of a plain copy kernel (k_copy_f4) that
+ * reads and rewrites the gradient scratch row of worker 0 in place; *bytes_each_way is the
+ * number of bytes it reads (= writes).  Between iterations only; the gradient scratch is
+ * rewritten by the next ddef_grad anyway. */
+int ddef_copy_probe(ddef_ctx* ctx, uint64_t* bytes_each_way);
 /* How many worker selections so far took the multi-pass path over the whole vector
  * (counted over all workers and iterations since ddef_set_problem). */
 int ddef_full_select_count(ddef_ctx* ctx, uint64_t* count);

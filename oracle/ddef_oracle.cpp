@@ -68,7 +68,8 @@ void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// -2 ln(u) for u = ((w >> 8) + 1) / 2^24 in (0, 1], using only +,-,*,/ in fp32:
+// -2 ln(u) for u = ((w >> 8) + 1) / 2^24 in (0, 1], from +,-,*,/ and fused multiply-add
+// (std::fmaf: one rounding, the same on every IEEE machine):
 // u = 2^(e-24) * m, m folded into (sqrt(1/2), sqrt(2)], ln m = 2 atanh((m-1)/(m+1)).
 float neg2ln_uniform(uint32_t w) {
     uint32_t a = (w >> 8) + 1u;                       // 1 .. 2^24, exact as a float
@@ -80,19 +81,18 @@ float neg2ln_uniform(uint32_t w) {
     float s = (m - 1.0f) / (m + 1.0f);
     float s2 = s * s;
     float poly = 1.0f / 9.0f;
-    poly = poly * s2 + 1.0f / 7.0f;
-    poly = poly * s2 + 1.0f / 5.0f;
-    poly = poly * s2 + 1.0f / 3.0f;
-    poly = poly * s2 + 1.0f;
+    poly = std::fmaf(poly, s2, 1.0f / 7.0f);
+    poly = std::fmaf(poly, s2, 1.0f / 5.0f);
+    poly = std::fmaf(poly, s2, 1.0f / 3.0f);
+    poly = std::fmaf(poly, s2, 1.0f);
     float lnm = (2.0f * s) * poly;
-    float big = (float)(24 - e) * 0x1.62e43p-1f;   // ln 2 rounded to fp32
-    float v = big - lnm;                              // -ln u >= 0
+    float v = std::fmaf((float)(24 - e), 0x1.62e43p-1f, -lnm);   // (24-e) ln 2 - ln m = -ln u >= 0
     v = v < 0.0f ? 0.0f : v;
     return 2.0f * v;
 }
 
 // cos and sin of the angle 2*pi*((w >> 8) + 1/2) / 2^24: quadrant from the top bits after
-// an eighth-turn shift, Taylor polynomials on (-pi/4, pi/4) for the rest.
+// an eighth-turn shift, Taylor polynomials on (-pi/4, pi/4) for the rest (Horner with fmaf).
 void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
     uint32_t b = ((w >> 8) + 0x200000u) & 0xffffffu;
     uint32_t q = b >> 22;
@@ -100,17 +100,17 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
     float phi = (float)(2 * r + 1) * 0x1.921fb6p-23f;   // pi / 2^24 rounded to fp32
     float p2 = phi * phi;
     float sp = 1.0f / 362880.0f;
-    sp = sp * p2 - 1.0f / 5040.0f;
-    sp = sp * p2 + 1.0f / 120.0f;
-    sp = sp * p2 - 1.0f / 6.0f;
-    sp = sp * p2 + 1.0f;
+    sp = std::fmaf(sp, p2, -1.0f / 5040.0f);
+    sp = std::fmaf(sp, p2, 1.0f / 120.0f);
+    sp = std::fmaf(sp, p2, -1.0f / 6.0f);
+    sp = std::fmaf(sp, p2, 1.0f);
     float s = phi * sp;
     float cp = -1.0f / 3628800.0f;
-    cp = cp * p2 + 1.0f / 40320.0f;
-    cp = cp * p2 - 1.0f / 720.0f;
-    cp = cp * p2 + 1.0f / 24.0f;
-    cp = cp * p2 - 0.5f;
-    float c = cp * p2 + 1.0f;
+    cp = std::fmaf(cp, p2, 1.0f / 40320.0f);
+    cp = std::fmaf(cp, p2, -1.0f / 720.0f);
+    cp = std::fmaf(cp, p2, 1.0f / 24.0f);
+    cp = std::fmaf(cp, p2, -0.5f);
+    float c = std::fmaf(cp, p2, 1.0f);
     switch (q) {
         case 0: *cos_out = c;  *sin_out = s;  break;
         case 1: *cos_out = -s; *sin_out = c;  break;
@@ -119,9 +119,13 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
     }
 }
 
-// Standard draw z(seed, t, worker, j).  kind 1: Box-Muller normal (cosine branch of words
-// 0,1).  kind 2: Student-t with 3 degrees of freedom, z0 / sqrt((z1^2+z2^2+z3^2)/3) from
-// the four normals of one Philox block.  kind 0: no noise.
+// Standard draw z(seed, t, worker, j) from one Philox block (w0..w3).
+// kind 1: Box-Muller normal, z0 = sqrt(-2 ln u(w0)) cos(angle(w1)).
+// kind 2: Student-t with 3 degrees of freedom, z0 / sqrt(chi2_3 / 3), where chi2_3 is the
+//   square of the second Box-Muller normal z1 = sqrt(-2 ln u(w0)) sin(angle(w1)) plus an
+//   independent chi-square with 2 degrees of freedom, -2 ln u(w2) (the squared radius of a
+//   second Box-Muller pair, which needs no angle).  w3 is not used.
+// kind 0: no noise.
 float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) {
     if (kind == 0) return 0.0f;
     uint32_t ctr[4] = {j, worker, (uint32_t)t, (uint32_t)(t >> 32)};
@@ -134,12 +138,8 @@ float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) 
     float z0 = r01 * c01;
     if (kind == 1) return z0;
     float z1 = r01 * s01;
-    float c23, s23;
-    float r23 = std::sqrt(neg2ln_uniform(w[2]));
-    unit_circle_point(w[3], &c23, &s23);
-    float z2 = r23 * c23;
-    float z3 = r23 * s23;
-    float q = ((z1 * z1 + z2 * z2) + z3 * z3) / 3.0f;
+    float chi2_2 = neg2ln_uniform(w[2]);
+    float q = std::fmaf(z1, z1, chi2_2) / 3.0f;
     float den = std::sqrt(q);
     if (den == 0.0f) return 0.0f;
     return z0 / den;

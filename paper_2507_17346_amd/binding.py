@@ -46,7 +46,8 @@ SIGNATURES = {
     "ddef_profile_enable": (C.c_int, [_ctx, C.c_int]),
     "ddef_profile_slots": (C.c_int, []),
     "ddef_profile_read": (C.c_int, [_ctx, C.c_int, C.POINTER(C.c_char_p), _u64p, C.POINTER(C.c_double)]),
-    "ddef_full_select_count": (C.c_int, [_ctx, _u64p]),
+    "ddef_copy_probe": (C.c_int, [_ctx, _u64p]),
+    "ddef_full_select_count":  (C.c_int, [_ctx, _u64p]),
     "ddef_set_option": (C.c_int, [_ctx, C.c_int, C.c_int64]),
     "ddef_get_filter_state": (C.c_int, [_ctx, C.c_uint32, _u32p, _u32p, _u32p]),
     "ddef_strerror": (C.c_char_p, [C.c_int]),
@@ -253,6 +254,12 @@ class Context:
     # ---- measurement --------------------------------------------------------------------
     def profile_enable(self, on: bool):
         self._check(self._lib.ddef_profile_enable(self._h, 1 if on else 0), "ddef_profile_enable")
+
+    def copy_probe(self) -> int:
+        """Launch the plain copy yardstick once; returns the bytes it reads (= writes)."""
+        b = C.c_uint64()
+        self._check(self._lib.ddef_copy_probe(self._h, C.byref(b)), "ddef_copy_probe")
+        return int(b.value)
 
     def profile_read(self):
         """{kernel name: (launches, total_ms)} since profiling was switched on."""

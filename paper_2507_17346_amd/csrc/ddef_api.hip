@@ -21,12 +21,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_SCATTER_ADD,
-    SL_APPLY, SL_COUNT
+    SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_unscatter", "k_scatter_add", "k_apply"};
+    "k_unscatter", "k_scatter_add", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -612,6 +612,18 @@ int ddef_get_filter_state(ddef_ctx* c, uint32_t worker, uint32_t* next_bound, ui
     HIP_TRY(c, hipMemcpy(next_bound, c->filt + worker, 4u, hipMemcpyDeviceToHost));
     *candidates = s.seen;
     *searched_row = s.active;
+    return DDEF_OK;
+}
+
+int ddef_copy_probe(ddef_ctx* c, uint64_t* bytes_each_way) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    const uint64_t quads = c->ld / 4u;
+    LAUNCH(c, SL_COPY_PROBE, k_copy_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), (const float*)c->g, c->g, quads);
+    HIP_TRY(c, hipGetLastError());
+    if (bytes_each_way) *bytes_each_way = c->ld * 4u;
     return DDEF_OK;
 }
 

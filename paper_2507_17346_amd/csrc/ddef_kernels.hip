@@ -75,9 +75,10 @@ __device__ __forceinline__ void store_stream4(float* p, const float (&v)[4]) {
 __device__ __forceinline__ uint32_t mag_key(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
 // ------------------------------------------------------------------------------------
-// gradient noise: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller out of +,-,*,/,sqrt.
-// Every fp32 operation is written out and rounded on its own (the file is compiled with
-// contraction off) so that the CPU can reproduce each draw bit for bit.
+// gradient noise: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller out of +,-,*,/,sqrt and
+// explicit fused multiply-adds.  Every fp32 operation is written out (the file is compiled
+// with contraction off, so the compiler fuses nothing on its own) so that the CPU can
+// reproduce each draw bit for bit.
 // ------------------------------------------------------------------------------------
 struct U4 { uint32_t a, b, c, d; };
 
@@ -96,7 +97,8 @@ __device__ __forceinline__ U4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2
 }
 
 // -2 ln u, u = ((w >> 8) + 1) 2^-24: split off the exponent, fold the mantissa into
-// (sqrt 1/2, sqrt 2], ln m = 2 atanh s with s = (m-1)/(m+1), odd series up to s^9.
+// (sqrt 1/2, sqrt 2], ln m = 2 atanh s with s = (m-1)/(m+1), odd series up to s^9 in Horner
+// form with explicit fused multiply-adds (single rounding, reproducible on the CPU).
 __device__ __forceinline__ float radius_sq(uint32_t w) {
     const uint32_t fb = __float_as_uint((float)((w >> 8) + 1u));
     int ex = (int)(fb >> 23) - 127;
@@ -106,12 +108,12 @@ __device__ __forceinline__ float radius_sq(uint32_t w) {
     const float s = (m - 1.0f) / (m + 1.0f);
     const float s2 = s * s;
     float h = 1.0f / 9.0f;
-    h = h * s2 + 1.0f / 7.0f;
-    h = h * s2 + 1.0f / 5.0f;
-    h = h * s2 + 1.0f / 3.0f;
-    h = h * s2 + 1.0f;
+    h = __builtin_fmaf(h, s2, 1.0f / 7.0f);
+    h = __builtin_fmaf(h, s2, 1.0f / 5.0f);
+    h = __builtin_fmaf(h, s2, 1.0f / 3.0f);
+    h = __builtin_fmaf(h, s2, 1.0f);
     const float lnm = (2.0f * s) * h;
-    float v = (float)(24 - ex) * 0x1.62e43p-1f - lnm;
+    float v = __builtin_fmaf((float)(24 - ex), 0x1.62e43p-1f, -lnm);
     v = v < 0.0f ? 0.0f : v;
     return 2.0f * v;
 }
@@ -125,21 +127,23 @@ __device__ __forceinline__ void circle_point(uint32_t w, float& co, float& si) {
     const float phi = (float)(2 * rem + 1) * 0x1.921fb6p-23f;
     const float p2 = phi * phi;
     float a = 1.0f / 362880.0f;
-    a = a * p2 - 1.0f / 5040.0f;
-    a = a * p2 + 1.0f / 120.0f;
-    a = a * p2 - 1.0f / 6.0f;
-    a = a * p2 + 1.0f;
+    a = __builtin_fmaf(a, p2, -1.0f / 5040.0f);
+    a = __builtin_fmaf(a, p2, 1.0f / 120.0f);
+    a = __builtin_fmaf(a, p2, -1.0f / 6.0f);
+    a = __builtin_fmaf(a, p2, 1.0f);
     const float s = phi * a;
     float c = -1.0f / 3628800.0f;
-    c = c * p2 + 1.0f / 40320.0f;
-    c = c * p2 - 1.0f / 720.0f;
-    c = c * p2 + 1.0f / 24.0f;
-    c = c * p2 - 0.5f;
-    c = c * p2 + 1.0f;
+    c = __builtin_fmaf(c, p2, 1.0f / 40320.0f);
+    c = __builtin_fmaf(c, p2, -1.0f / 720.0f);
+    c = __builtin_fmaf(c, p2, 1.0f / 24.0f);
+    c = __builtin_fmaf(c, p2, -0.5f);
+    c = __builtin_fmaf(c, p2, 1.0f);
     co = (quad == 0u) ? c : (quad == 1u) ? -s : (quad == 2u) ? -c : s;
     si = (quad == 0u) ? s : (quad == 1u) ? c : (quad == 2u) ? -s : -c;
 }
 
+// kind 1: normal z0 = R cos.  kind 2: Student-t(3) = z0 / sqrt((z1^2 + chi2_2) / 3) with
+// z1 = R sin the pair's second normal and chi2_2 = -2 ln u of the block's third word.
 __device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
                                         uint32_t seed_lo, uint32_t seed_hi, int kind) {
     const U4 w = philox_block(j, worker, t_lo, t_hi, seed_lo, seed_hi);
@@ -149,11 +153,7 @@ __device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_
     const float z0 = r01 * c01;
     if (kind == 1) return z0;
     const float z1 = r01 * s01;
-    float c23, s23;
-    const float r23 = __builtin_sqrtf(radius_sq(w.c));
-    circle_point(w.d, c23, s23);
-    const float z2 = r23 * c23, z3 = r23 * s23;
-    const float q = ((z1 * z1 + z2 * z2) + z3 * z3) / 3.0f;
+    const float q = __builtin_fmaf(z1, z1, radius_sq(w.c)) / 3.0f;
     const float den = __builtin_sqrtf(q);
     return den == 0.0f ? 0.0f : z0 / den;
 }
@@ -726,11 +726,11 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, uint64_t count, u
         p[q] = value;
 }
 
-__global__ __launch_bounds__(256) void k_copy_f4(const float* __restrict__ src, float* __restrict__ dst,
-                                                 uint64_t quads) {
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads;
-         q += (uint64_t)gridDim.x * blockDim.x)
-        reinterpret_cast<float4*>(dst)[q] = reinterpret_cast<const float4*>(src)[q];
+// Plain copy of known size (one quad per thread, single-wave blocks): the yardstick that the
+// hardware byte counters are scaled by.  src may equal dst.
+__global__ __launch_bounds__(64) void k_copy_f4(const float* src, float* dst, uint64_t quads) {
+    const uint64_t q = (uint64_t)blockIdx.x * 64u + threadIdx.x;
+    if (q < quads) reinterpret_cast<float4*>(dst)[q] = reinterpret_cast<const float4*>(src)[q];
 }
 
 }  // namespace ddef

@@ -74,12 +74,11 @@ def test_normal_draw_is_box_muller_of_the_philox_words(oracle_mod):
         want = math.sqrt(-2.0 * math.log(u1)) * math.cos(ang)
         got = oracle_mod.noise_z(seed, t, worker, j, 1)
         assert abs(got - want) <= 5e-6 * max(1.0, abs(want))
+        # Student-t(3): z0 over the root of a chi-square(3)/3 built from the pair's second
+        # normal and the squared radius -2 ln u3 of the block's third word
         z1 = math.sqrt(-2.0 * math.log(u1)) * math.sin(ang)
         u3 = ((int(w[2]) >> 8) + 1) / 2.0 ** 24
-        a3 = 2.0 * math.pi * ((int(w[3]) >> 8) + 0.5) / 2.0 ** 24
-        z2 = math.sqrt(-2.0 * math.log(u3)) * math.cos(a3)
-        z3 = math.sqrt(-2.0 * math.log(u3)) * math.sin(a3)
-        want_t = want / math.sqrt((z1 * z1 + z2 * z2 + z3 * z3) / 3.0)
+        want_t = want / math.sqrt((z1 * z1 - 2.0 * math.log(u3)) / 3.0)
         got_t = oracle_mod.noise_z(seed, t, worker, j, 2)
         assert abs(got_t - want_t) <= 2e-5 * max(1.0, abs(want_t))
     assert oracle_mod.noise_z(seed, t, worker, 5, 0) == 0.0
