@@ -24,14 +24,24 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# one plain (unpacked, unfused) vector instruction per lane and clock: 256 CUs x 64 lanes x 2.4 GHz
+VALU_NOMINAL_TINSTR = 256 * 64 * 2.4e9 / 1e12
+# vector lane-instructions k_grad executes per noise draw, by noise kind: SQ_INSTS_VALU x 64 / draws
+# (profiles/k_grad_C3_valu.txt)
+VALU_PER_DRAW = {2: 214.8}
 
-# algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
-ALGO_BYTES_PER_ELEM = {
-    "k_ef_accumulate": 12.0,   # read e, read g, write p
-    "k_ef_filter": 12.0,       # same pass, with the candidate filter fused in
-    "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
-    "k_digit_hist": 4.0, "k_chunk_count": 4.0, "k_chunk_emit": 4.0,
-}
+def measured_traffic(kernel, workload_name):
+    """HBM bytes per launch from the committed hardware-counter summary (rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, scaled by the copy yardstick), or None when there is none for
+    this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload_name}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -147,9 +157,23 @@ def main():
     algo_bytes = per_elem * elems
     achieved = algo_bytes / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS,
+                "traffic": measured_traffic(dominant, w.name) if args.d is None else None,
                 "algorithmic_bytes_per_launch": algo_bytes,
                 "avg_launch_ms": kernels[dominant]["avg_ms"]}
+
+    # the gradient generator is bound by vector ALU work (Philox + Box-Muller), not by HBM: report
+    # its rate in draws and in vector lane-instructions (count per draw from the hardware counter
+    # SQ_INSTS_VALU, profiles/k_grad_C3_valu.txt) next to the nominal plain-VALU issue rate
+    grad_info = None
+    if "k_grad" in kernels:
+        g_s = kernels["k_grad"]["avg_ms"] * 1e-3
+        grad_info = {"kernel": "k_grad", "bound": "alu", "avg_launch_ms": kernels["k_grad"]["avg_ms"],
+                     "draws_per_s": elems / g_s, "written_GBps": 4.0 * elems / g_s / 1e9}
+        if w.noise_kind in VALU_PER_DRAW:
+            grad_info["valu_lane_instr_per_draw"] = VALU_PER_DRAW[w.noise_kind]
+            grad_info["valu_T_lane_instr_per_s"] = VALU_PER_DRAW[w.noise_kind] * elems / g_s / 1e12
+            grad_info["nominal_valu_T_lane_instr_per_s"] = VALU_NOMINAL_TINSTR
 
     # metric of the path proper (EF + top-k + aggregate + apply), gradient generation aside
     path_ms = phase_ms["ef_compress"] + phase_ms["aggregate"] + phase_ms["apply_delayed"]
@@ -169,6 +193,7 @@ def main():
                    "d": w.d, "n": w.n, "k": w.k(), "tau": w.tau,
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
+        "grad": grad_info,
         "ef_topk_aggregate_apply": path,
         "ms_per_call": phase_ms,
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 5) for k, v in kernels.items()},
