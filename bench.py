@@ -30,6 +30,14 @@ VALU_NOMINAL_TINSTR = 256 * 64 * 2.4e9 / 1e12
 # (profiles/k_grad_C3_valu.txt)
 VALU_PER_DRAW = {2: 214.8}
 
+# algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
+ALGO_BYTES_PER_ELEM = {
+    "k_ef_filter": 12.0,       # read e, read g, write p (the candidate filter rides along)
+    "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
+    "k_digit_hist": 4.0, "k_chunk_count": 4.0, "k_chunk_emit": 4.0,   # whole-row search passes
+}
+
+
 def measured_traffic(kernel, workload_name):
     """HBM bytes per launch from the committed hardware-counter summary (rocprofv3 --pmc
     FETCH_SIZE / WRITE_SIZE, scaled by the copy yardstick), or None when there is none for
