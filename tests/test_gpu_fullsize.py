@@ -1,0 +1,136 @@
+"""GPU parity at the workloads' full sizes, in the launch configuration bench.py times.
+
+C2 and C3 are compared with the oracle element by element for every worker (the oracle needs a
+few seconds per iteration with one thread per worker).  C4 (d = 1.3e9, n*d > 2^32) is too large
+for the oracle to run whole: its selection is checked through properties that hold at any size
+(count, order, threshold dominance, tie rule, EF identity) and its gradients and error-feedback
+values on sampled coordinates that the oracle computes one by one.
+"""
+import numpy as np
+import pytest
+
+from paper_2507_17346_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+
+
+def bits(a):
+    return np.asarray(a, dtype=F32).view(np.uint32)
+
+
+@pytest.fixture(scope="module")
+def ddef():
+    from paper_2507_17346_amd import binding
+    binding.load()
+    return binding
+
+
+def run_pair(ddef, oracle_mod, w, real_steps, delta):
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, w.tau_max)
+    o = oracle_mod.Oracle(w.d, w.n, w.tau_max, threads=w.n)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(w.tau)
+    for t in range(w.tau + real_steps):
+        g.step(delta, w.lr)
+        o.step(delta, w.lr)
+        if t >= w.tau:
+            # indices and thresholds of every worker at every iteration (cheap to fetch)
+            for i in range(w.n):
+                gi, gv = g.get_message(i)
+                oi, ov = o.get_message(i)
+                assert np.array_equal(gi, oi), (w.name, t, i)
+                assert np.array_equal(bits(gv), bits(ov)), (w.name, t, i)
+                assert g.get_threshold(i) == o.get_threshold(i)
+    for i in range(w.n):
+        assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), (w.name, "error buffer", i)
+        assert np.array_equal(bits(g.get_grad(i)), bits(o.get_grad(i))), (w.name, "gradient", i)
+    gu, ou = g.get_update(), o.get_update()
+    gx, ox = g.get_model(), o.get_model()
+    scale = np.abs(ox).max()
+    assert np.abs(gx.astype(np.float64) - ox).max() <= 1e-6 * scale
+    assert np.array_equal(bits(gu), bits(ou)) and np.array_equal(bits(gx), bits(ox))
+    used_filter = w.n * real_steps - g.full_select_count()
+    g.close()
+    o.close()
+    return used_filter
+
+
+def test_c2_full_size(ddef, oracle_mod):
+    w = workloads.get("C2")
+    used = run_pair(ddef, oracle_mod, w, real_steps=6, delta=w.deltas[0])
+    assert used >= 3 * w.n            # the candidate filter carried most selections
+
+
+def test_c3_full_size_bench_configuration(ddef, oracle_mod):
+    w = workloads.get("C3")
+    used = run_pair(ddef, oracle_mod, w, real_steps=4, delta=w.deltas[0])
+    assert used >= w.n                # at least the last iterations ran through the filter
+
+
+def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
+    w = workloads.get("C4")
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, w.tau_max)
+    g.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    g.set_tau(w.tau)
+    # the workload sweeps delta; iterations tau .. 2*tau all take their gradient at x0
+    schedule = {w.tau: 0.001, w.tau + 1: 0.001, w.tau + 2: 0.001, w.tau + 3: 0.1, w.tau + 4: 0.1}
+    rng = np.random.default_rng(17)
+    sample = np.unique(np.concatenate([rng.integers(0, w.d, size=4000),
+                                       [0, 1, w.d - 1, w.d - 2, 2 ** 30, 2 ** 30 + 1]]))
+    watched = (0, w.n - 1)                     # first and last worker: flat offsets beyond 2^32
+    e_prev = {i: np.zeros(len(sample), dtype=F32) for i in watched}
+    for t in range(2 * w.tau + 1):
+        delta = schedule.get(t, 0.001)
+        k = w.k(delta)
+        g.grad()
+        g.ef_compress(delta, w.lr)
+        if t < w.tau:
+            g.aggregate()
+            g.apply_delayed(w.lr)
+            continue
+        for i in watched:
+            idx, val = g.get_message(i)
+            T, r = g.get_threshold(i)
+            e_new = g.get_error(i)
+            assert len(idx) == k
+            assert np.all(np.diff(idx.astype(np.int64)) > 0) and int(idx[-1]) < w.d
+            vkeys = bits(val) & np.uint32(0x7FFFFFFF)
+            assert int(vkeys.min()) == T and int((vkeys == T).sum()) == r
+            assert np.all(bits(e_new[idx]) == 0)             # sent entries leave the buffer
+            ekeys = bits(e_new) & np.uint32(0x7FFFFFFF)
+            assert int(ekeys.max()) <= T                      # nothing larger was left behind
+            left = np.flatnonzero(ekeys == T)
+            if len(left) and r:
+                assert int(left.min()) > int(idx[vkeys == T].max())    # ties: lower indices sent first
+            del ekeys, left
+            # sampled coordinates: gradient and p = e + lr*g recomputed from the oracle's noise
+            gs = g.get_grad(i)[sample]
+            z = np.array([oracle_mod.noise_z(w.seed, t, i, int(j), w.noise_kind) for j in sample], dtype=F32)
+            want_g = lam[sample] * (x0[sample] - xstar[sample]) + F32(w.noise_scale) * z
+            assert np.array_equal(bits(gs), bits(want_g))
+            p = e_prev[i] + F32(w.lr) * gs
+            sent = np.isin(sample, idx)
+            pos = np.searchsorted(idx, sample[sent])
+            assert np.array_equal(bits(val[pos]), bits(p[sent]))
+            assert np.array_equal(bits(e_new[sample][~sent]), bits(p[~sent]))
+            e_prev[i] = e_new[sample]
+            del e_new
+        g.aggregate()
+        U = g.get_update()[sample]
+        acc = np.zeros(len(sample), dtype=F32)
+        for i in range(w.n):
+            idx, val = g.get_message(i)
+            hit = np.isin(sample, idx)
+            acc[hit] = acc[hit] + val[np.searchsorted(idx, sample[hit])]
+        assert np.array_equal(bits(U), bits(acc))
+        x_before = g.get_model()[sample]
+        g.apply_delayed(w.lr)
+        assert np.array_equal(bits(g.get_model()[sample]), bits(x_before - acc / F32(w.n)))
+    # both searches ran at this size: the whole-row one at first and after delta jumped
+    assert 0 < g.full_select_count() < 5 * w.n
+    g.close()
