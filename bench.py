@@ -81,6 +81,35 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note):
                       f"({dt:.1f} s wall, {threads} threads){budget_note}"}
 
 
+def describe(w, sched):
+    noise = {0: "no noise", 1: f"Gaussian noise x{w.noise_scale}", 2: f"Student-t3 noise x{w.noise_scale}"}[w.noise_kind]
+    if w.adaptive_period > 0:
+        pairs = sorted({sched(t) for t in range(0, w.steps, w.adaptive_period)})
+        ratio = f"(tau, delta) re-chosen by DeCo every {w.adaptive_period} iterations from the seeded trace: {pairs}"
+    elif len(w.deltas) > 1:
+        ratio = f"delta swept over {list(w.deltas)} in segments of {w.steps} iterations, tau={w.tau}"
+    else:
+        ratio = f"delta={w.deltas[0]} (k={w.k()}), tau={w.tau}"
+    return f"{w.name}: d={w.d} fp32, n={w.n} workers, {ratio}, lr={w.lr}, {noise}, seed {w.seed}"
+
+
+def make_schedule(w, binding, workloads):
+    """(tau, delta) for iteration t.  Fixed for C1-C3; C4 sweeps its three ratios in segments of
+    `steps` iterations after the empty start-up; C5 re-chooses both from the seeded network trace
+    with DeCo (Algorithm 3) every `adaptive_period` iterations, clamped to the workload's bounds."""
+    if w.adaptive_period > 0:
+        tr = workloads.network_trace(w)
+        pairs = []
+        for a, b in zip(tr.bandwidth_bps, tr.latency_s):
+            tau, delta = binding.deco(tr.v_g_bits, a, b, tr.t_comp_s)
+            pairs.append((int(min(max(tau, tr.tau_bounds[0]), tr.tau_bounds[1])),
+                          float(min(max(delta, tr.delta_bounds[0]), tr.delta_bounds[1]))))
+        return lambda t: pairs[(t // w.adaptive_period) % len(pairs)]
+    if len(w.deltas) > 1:
+        return lambda t: (w.tau, w.deltas[(max(t - w.tau, 0) // w.steps) % len(w.deltas)])
+    return lambda t: (w.tau, w.deltas[0])
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,26 +130,39 @@ def main():
     from paper_2507_17346_amd import binding, workloads
 
     w = workloads.get(args.workload, d=args.d)
-    delta = w.deltas[0]
-    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (k={w.k()}) tau={w.tau} lr={w.lr} "
+    sched = make_schedule(w, binding, workloads)
+    delta = sched(0)[1]
+    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (k={w.k(delta)}) tau={sched(0)[0]} lr={w.lr} "
         f"noise kind {w.noise_kind} scale {w.noise_scale} seed {w.seed}")
     t0 = time.perf_counter()
     lam, xstar, x0 = workloads.make_problem(w)
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
     ctx = binding.Context(w.d, w.n, w.tau_max)
     ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
-    ctx.set_tau(w.tau)
 
-    # warm-up: the tau empty iterations, then W real ones so that the error buffers are
-    # populated and the selection runs in its steady state
-    for _ in range(w.tau + args.warmup):
-        ctx.step(delta, w.lr)
+    state = {"tau": None}
+
+    def begin_iteration():
+        tau, dl = sched(ctx.t)
+        if tau != state["tau"]:
+            ctx.set_tau(tau)
+            state["tau"] = tau
+        return dl
+
+    def whole_step():
+        dl = begin_iteration()
+        ctx.step(dl, w.lr)
+
+    # warm-up: the empty iterations before anything arrives, then W real ones so that the error
+    # buffers are populated and the selection runs in its steady state
+    for _ in range(sched(0)[0] + args.warmup):
+        whole_step()
     ctx.sync()
 
     # ---- timed region: exactly K whole steps ------------------------------------------------
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.step(delta, w.lr)
+        whole_step()
     ctx.sync()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -130,7 +172,10 @@ def main():
     # ---- the same K steps again, once with a wait after each call (time per call), once with
     # HIP events around every kernel launch on the library's stream (time per kernel) -----------
     phase = {"grad": 0.0, "ef_compress": 0.0, "aggregate": 0.0, "apply_delayed": 0.0}
+    floor_bytes_sum = 0.0
     for _ in range(args.steps):
+        delta = begin_iteration()
+        floor_bytes_sum += (12.0 + 24.0 * (w.k(delta) / w.d) + 16.0 / w.n) * w.n * w.d
         for name, call in (("grad", ctx.grad), ("ef_compress", lambda: ctx.ef_compress(delta, w.lr)),
                            ("aggregate", ctx.aggregate), ("apply_delayed", lambda: ctx.apply_delayed(w.lr))):
             ctx.sync()
@@ -142,7 +187,7 @@ def main():
     full0 = ctx.full_select_count()
     ctx.profile_enable(True)
     for _ in range(args.steps):
-        ctx.step(delta, w.lr)
+        whole_step()
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     full_selects = ctx.full_select_count() - full0
@@ -185,7 +230,7 @@ def main():
 
     # metric of the path proper (EF + top-k + aggregate + apply), gradient generation aside
     path_ms = phase_ms["ef_compress"] + phase_ms["aggregate"] + phase_ms["apply_delayed"]
-    floor_bytes = (12.0 + 24.0 * (w.k() / w.d) + 16.0 / w.n) * elems
+    floor_bytes = floor_bytes_sum / args.steps
     path = {"ms": path_ms, "elements_per_s": elems / (path_ms * 1e-3),
             "floor_bytes_per_step": floor_bytes,
             "floor_GBps": floor_bytes / (path_ms * 1e-3) / 1e9,
@@ -196,9 +241,8 @@ def main():
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: d={w.d} fp32, n={w.n} workers, delta={delta} (k={w.k()}), "
-                               f"tau={w.tau}, lr={w.lr}, Student-t3 noise x{w.noise_scale}, seed {w.seed}",
-                   "d": w.d, "n": w.n, "k": w.k(), "tau": w.tau,
+        "config": {"workload": describe(w, sched),
+                   "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,
@@ -209,7 +253,7 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        sample_d = args.cpu_sample_d or w.d
+        sample_d = args.cpu_sample_d or min(w.d, 124_000_000)
         note = ""
         try:
             out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note)

@@ -305,7 +305,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     c->ld = (d + 4095u) & ~(uint64_t)4095u;
     c->nchunks = (uint32_t)(c->ld / 4096u);
     c->nwc = (uint32_t)(c->ld / 256u);          // 256-entry groups of the filter kernel
-    c->nspans = (c->nwc + 8191u) / 8192u;
+    c->nspans = (c->nwc + kSpan - 1u) / kSpan;
     if (hipStreamCreateWithFlags(&c->own_stream, hipStreamNonBlocking) != hipSuccess) return fail(DDEF_EHIP);
     c->stream = c->own_stream;
     const size_t row = (size_t)c->ld * 4u;

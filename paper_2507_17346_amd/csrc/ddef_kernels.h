@@ -8,6 +8,8 @@ namespace ddef {
 
 // A worker's candidate buffer is split into this many parts, each with its own slot counter.
 constexpr uint32_t kSubs = 256;
+// The run table is scanned in spans of this many 256-entry groups (one block each).
+constexpr uint32_t kSpan = 1024;
 
 // Per-worker selection state in device memory.
 struct SelState {

@@ -264,20 +264,15 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
 
 // ---- run table -> coordinate order ------------------------------------------------------
 // tab[w][c].y is the run length of group c.  Three small kernels turn the lengths into
-// exclusive prefixes obase[w][c]: sums over spans of 8192 groups, a scan of the span
-// sums that also decides whether the filter caught enough, and the prefixes inside a span,
-// which drive the copy of the runs into coordinate order.
-constexpr uint32_t kSpan = 8192;
-
-__global__ __launch_bounds__(1024) void k_tab_sum(const uint2* __restrict__ tab, uint32_t nwc,
+// positions in coordinate order: sums over spans of 1024 groups, a scan of the span sums that
+// also decides whether the filter caught enough, and the prefixes inside a span, which drive
+// the copy of the runs into coordinate order.
+__global__ __launch_bounds__(1024) void k_tab_sum(const uint2* __restrict__ tab, uint32_t ngroups,
                                                   uint32_t* __restrict__ span_sum, uint32_t nspans) {
     __shared__ uint32_t red[16];
     const uint32_t w = blockIdx.y, sp = blockIdx.x;
-    const uint2* tw = tab + (uint64_t)w * nwc;
-    const uint32_t c0 = sp * kSpan + threadIdx.x * 8u;
-    uint32_t mine = 0;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) mine += (c0 + q < nwc) ? tw[c0 + q].y : 0u;
+    const uint32_t c = sp * kSpan + threadIdx.x;
+    uint32_t mine = c < ngroups ? tab[(uint64_t)w * ngroups + c].y : 0u;
     mine = wave_sum(mine);
     if (lane_id() == 0) red[threadIdx.x >> 6] = mine;
     __syncthreads();
@@ -349,7 +344,8 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 
 // Prefixes inside a span, and with them the candidates in coordinate order: group c's run
 // cand[first .. first+len) goes to positions [at, at+len) of the ordered arrays (index,
-// value).  A run holds at most 256 entries, so the per-thread copy loops are short.
+// value).  The block copies its span's candidates together: thread q takes the q-th, finds
+// its group by bisection over the span's prefixes in LDS, and the stores are coalesced.
 __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ tab, uint32_t ngroups,
                                                     const uint32_t* __restrict__ span_off,
                                                     uint32_t nspans, const SelState* __restrict__ sel,
@@ -357,31 +353,30 @@ __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ ta
                                                     uint32_t* __restrict__ sorted_idx,
                                                     float* __restrict__ sorted_val) {
     __shared__ uint32_t lds[17];
+    __shared__ uint32_t at_of[kSpan];        // exclusive prefix of the run lengths inside the span
+    __shared__ uint32_t first_of[kSpan];     // first slot of each run
     const uint32_t w = blockIdx.y, sp = blockIdx.x;
     if (sel[w].active) return;
-    const uint2* tw = tab + (uint64_t)w * ngroups;
-    const uint2* cw = cand + (uint64_t)w * cap;
-    uint32_t* oi = sorted_idx + (uint64_t)w * cap;
-    float* ov = sorted_val + (uint64_t)w * cap;
-    const uint32_t c0 = sp * kSpan + threadIdx.x * 8u;
-    uint2 run[8];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        run[q] = (c0 + q < ngroups) ? tw[c0 + q] : make_uint2(0u, 0u);
-        mine += run[q].y;
-    }
+    const uint32_t c = sp * kSpan + threadIdx.x;
+    const uint2 run = c < ngroups ? tab[(uint64_t)w * ngroups + c] : make_uint2(0u, 0u);
     uint32_t total;
-    uint32_t at = span_off[(uint64_t)w * nspans + sp] + block_excl_scan(mine, lds, &total);
-    if (mine == 0u) return;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        for (uint32_t m = 0; m < run[q].y; ++m) {
-            const uint2 item = cw[run[q].x + m];
-            oi[at + m] = item.x;
-            ov[at + m] = __uint_as_float(item.y);
+    const uint32_t at = block_excl_scan(run.y, lds, &total);
+    at_of[threadIdx.x] = at;
+    first_of[threadIdx.x] = run.x;
+    __syncthreads();
+    if (total == 0u) return;
+    const uint2* cw = cand + (uint64_t)w * cap;
+    const uint64_t out0 = (uint64_t)w * cap + span_off[(uint64_t)w * nspans + sp];
+    for (uint32_t q = threadIdx.x; q < total; q += kSpan) {
+        uint32_t lo = 0, hi = kSpan;           // first group in [lo, hi) whose prefix exceeds q
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (at_of[mid] > q) hi = mid; else lo = mid + 1u;
         }
-        at += run[q].y;
+        const uint32_t grp = lo - 1u;           // at_of[0] = 0 <= q, so lo >= 1; empty runs are skipped
+        const uint2 item = cw[first_of[grp] + (q - at_of[grp])];
+        sorted_idx[out0 + q] = item.x;
+        sorted_val[out0 + q] = __uint_as_float(item.y);
     }
 }
 
