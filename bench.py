@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--d", type=int, default=None, help="shrink d (debug only; not a valid bench)")
+    ap.add_argument("--delta", type=float, default=None,
+                    help="fix the compression ratio (study runs only; the default follows the workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -130,6 +132,8 @@ def main():
     from paper_2507_17346_amd import binding, workloads
 
     w = workloads.get(args.workload, d=args.d)
+    if args.delta is not None:
+        w = workloads.replace(w, deltas=(args.delta,), adaptive_period=0, tau=w.tau if w.adaptive_period == 0 else 8)
     sched = make_schedule(w, binding, workloads)
     delta = sched(0)[1]
     log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (k={w.k(delta)}) tau={sched(0)[0]} lr={w.lr} "

@@ -315,7 +315,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
         {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
-        {(void**)&c->filt, (size_t)4 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->filt, (size_t)4 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
     };
     for (const Want& w : wants) {
@@ -373,7 +373,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
     HIP_TRY(c, hipMemset(c->filt, 0, (size_t)4 * c->n * 4));
-    HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * 4));
+    HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
     c->have_bound = false;
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;

@@ -8,6 +8,9 @@ namespace ddef {
 
 // A worker's candidate buffer is split into this many parts, each with its own slot counter.
 constexpr uint32_t kSubs = 256;
+// Each slot counter sits in a cache line of its own (stride in 32-bit words), so that atomics
+// on different counters do not queue up behind one line.
+constexpr uint32_t kSubStride = 32;
 // The run table is scanned in spans of this many 256-entry groups (one block each).
 constexpr uint32_t kSpan = 1024;
 

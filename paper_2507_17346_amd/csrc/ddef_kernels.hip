@@ -246,7 +246,7 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         const uint32_t sub = grp & (kSubs - 1u);
         const uint32_t sub_cap = (uint32_t)(cap / kSubs);
         uint32_t got = 0;
-        if (lane == 0) got = atomicAdd(&cand_count[w * kSubs + sub], total);
+        if (lane == 0) got = atomicAdd(&cand_count[(w * kSubs + sub) * kSubStride], total);
         got = __shfl(got, 0, 64);
         if (got + total > sub_cap) {
             if (lane == 0) overflow[w] = 1u;
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __re
         out_carry += out_total;
     }
     if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, vs.cand_total, overflow);
-    for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[w * kSubs + q] = 0u;
+    for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[(w * kSubs + q) * kSubStride] = 0u;
 }
 
 // Writes the message (ascending coordinate) and sets the sent entries of e to +0.  In a
