@@ -20,13 +20,13 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_SCATTER_ADD,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
     SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_unscatter", "k_scatter_add", "k_apply", "k_copy_f4"};
+    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -190,12 +190,11 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
 }
 
 // Radix select and ordered compaction of every worker through its view (candidates or row).
-void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, bool rows_only) {
+void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
     const uint32_t n = c->n;
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *cand_total = c->filt + 3 * n;
     const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sorted_val, c->sorted_idx, c->cap, cand_total};
     // grids sized for the longest view that can occur (any worker may have to search its row)
-    (void)rows_only;
     const uint64_t span = c->ld;
     const uint32_t gx = blocks_for(c, (span + 1023) / 1024, n, 8);
     for (int level = 0; level < 3; ++level) {
@@ -213,13 +212,20 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, bool rows_only) {
            c->msg_ld, k);
 }
 
-// Puts U back to all-zero by clearing only the coordinates the last aggregate wrote.  Must
-// run before the message buffers are overwritten or reallocated.
+// Puts U back to all-zero.  With sparse messages only the coordinates the last aggregate wrote
+// are cleared (scattered 4-byte stores cost a 64-byte sector each, so this pays while
+// n*k < d/16); otherwise the row is filled.  Must run before the message buffers are
+// overwritten or reallocated.
 void clean_update(ddef_ctx* c) {
     if (!c->u_dirty_k) return;
-    const uint32_t k = (uint32_t)c->u_dirty_k;
-    LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256), c->U,
-           (const uint32_t*)c->msg_idx, c->msg_ld, k, (uint32_t)c->d);
+    const uint64_t k = c->u_dirty_k;
+    if (k * c->n * 16u < c->d) {
+        LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
+               c->U, (const uint32_t*)c->msg_idx, c->msg_ld, (uint32_t)k, (uint32_t)c->d);
+    } else {
+        const uint64_t quads = c->ld / 4u;
+        LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
+    }
     c->u_dirty_k = 0;
 }
 
@@ -463,7 +469,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                (uint32_t)c->d, cand_total, c->hist);
         c->full_selects += n;
     }
-    enqueue_select(c, (uint32_t)k, (uint32_t)kb, !use_filter);
+    enqueue_select(c, (uint32_t)k, (uint32_t)kb);
     c->have_bound = true;
     HIP_TRY(c, hipGetLastError());
     c->k_step = k;

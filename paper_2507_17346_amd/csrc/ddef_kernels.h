@@ -67,7 +67,7 @@ __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* o
 __global__ void k_scatter_add(float* U, const uint32_t* idx, const float* val, uint32_t k, uint32_t d);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
 __global__ void k_unscatter(float* U, const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t d);
-__global__ void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value);
+__global__ void k_fill_f4(float* p, uint64_t quads);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);
 
 }  // namespace ddef

@@ -715,10 +715,10 @@ __global__ __launch_bounds__(256) void k_unscatter(float* __restrict__ U, const 
     }
 }
 
-__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, uint64_t count, uint32_t value) {
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < count;
-         q += (uint64_t)gridDim.x * blockDim.x)
-        p[q] = value;
+// Dense zero fill of a row (one quad per thread, single-wave blocks).
+__global__ __launch_bounds__(64) void k_fill_f4(float* __restrict__ p, uint64_t quads) {
+    const uint64_t q = (uint64_t)blockIdx.x * 64u + threadIdx.x;
+    if (q < quads) reinterpret_cast<float4*>(p)[q] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 // Plain copy of known size (one quad per thread, single-wave blocks): the yardstick that the
