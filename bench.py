@@ -56,9 +56,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note):
+def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None):
     """The oracle, as it stands, on a bounded sample: one non-empty iteration over the first
-    sample_d coordinates of the workload (all n workers, one thread per worker)."""
+    sample_d coordinates of the workload (all n workers, one thread per worker unless capped)."""
     import oracle
     cores = os.cpu_count() or 1
     try:
@@ -69,6 +69,8 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note):
     if env_cap and env_cap.isdigit():
         cores = min(cores, int(env_cap))
     threads = max(1, min(w.n, cores))
+    if max_threads:
+        threads = min(threads, max_threads)
     o = oracle.Oracle(sample_d, w.n, 0, threads=threads)
     o.set_problem(lam[:sample_d], xstar[:sample_d], x0[:sample_d], w.seed, w.noise_kind, w.noise_scale)
     o.set_tau(0)
@@ -202,11 +204,14 @@ def main():
             f"per step {v['ms_per_step']:.4f} ms")
     log("  per call (ms): " + ", ".join(f"{k} {v:.3f}" for k, v in phase_ms.items()))
 
-    if args.copy_probe:
-        for _ in range(args.copy_probe):
-            probe_bytes = ctx.copy_probe()
-        ctx.sync()
-        log(f"  copy yardstick: {args.copy_probe} launches of k_copy_f4, {probe_bytes} bytes read and written each")
+    # what a plain copy reaches on this box (read + write of one row each way), for "% of achievable"
+    ctx.profile_enable(True)
+    for _ in range(max(5, args.copy_probe)):
+        probe_bytes = ctx.copy_probe()
+    copy_cnt, copy_ms = ctx.profile_read()["k_copy_f4"]
+    ctx.profile_enable(False)
+    copy_gbps = 2.0 * probe_bytes / (copy_ms / copy_cnt * 1e-3) / 1e9
+    log(f"  copy yardstick k_copy_f4: {probe_bytes} bytes each way, {copy_ms / copy_cnt:.4f} ms, {copy_gbps:.0f} GB/s")
 
     hot = [k for k in kernels if k != "k_grad"]
     dominant = max(hot, key=lambda k: kernels[k]["ms_per_step"])
@@ -214,7 +219,8 @@ def main():
     algo_bytes = per_elem * elems
     achieved = algo_bytes / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS,
+                "frac": achieved / HBM_PEAK_GBS, "copy_kernel_GBps": copy_gbps,
+                "frac_of_copy_kernel": achieved / copy_gbps,
                 "traffic": measured_traffic(dominant, w.name) if args.d is None else None,
                 "algorithmic_bytes_per_launch": algo_bytes,
                 "avg_launch_ms": kernels[dominant]["avg_ms"]}
@@ -263,6 +269,8 @@ def main():
             out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note)
         except MemoryError:
             out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory")
+        # the same oracle on one thread, on an eighth of the coordinates to keep the run short
+        out["cpu_baseline_single_thread"] = cpu_baseline(w, lam, xstar, x0, max(1, sample_d // 8), "", max_threads=1)
     ctx.close()
     print(json.dumps(out), flush=True)
 
