@@ -124,10 +124,32 @@ int ddef_get_threshold(ddef_ctx* ctx, uint32_t worker, uint32_t* T, uint64_t* r)
 uint64_t ddef_k_from_delta(double delta, uint64_t d);
 /* DeCo (Algorithm 3): scan tau from ceil((b + V_g/a)/T_comp) down to ceil(b/T_comp) with
  * delta = min{(tau T_comp - b) a / V_g, T_comp a / V_g, 1}, skip candidates with
- * delta <= 0, keep the minimal phi = (1-delta) / (delta (1-delta/2)^tau), smallest tau on
- * ties.  v_g_bits, a_bps (bits/s), b_s, t_comp_s > 0.  EINVAL when no candidate exists. */
+ * delta <= 0, keep the minimal phi, smallest tau on ties.  v_g_bits, a_bps (bits/s),
+ * t_comp_s > 0, b_s >= 0.  EINVAL when no candidate exists. */
 int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
               double* delta);
+/* DeCo's objective phi(delta, tau) = (1 - delta) / (delta (1 - delta/2)^tau) (Theorems 1 and 2,
+ * Algorithm 3); NaN outside 0 < delta <= 1, tau >= 0. */
+double ddef_phi(double delta, double tau);
+/* Theorem 3: T_avg ~ max{(T_comp + b + delta V_g / a) / (tau + 1), delta V_g / a, T_comp}. */
+double ddef_t_avg_model(uint32_t tau, double delta, double v_g_bits, double a_bps, double b_s,
+                        double t_comp_s);
+/* The pipeline recurrence the theorem is proved from (Section 4.1 and the proof of Theorem 3:
+ * computation k+1 starts when computation k is done and message k - tau has arrived; a
+ * message takes delta V_g / a on the wire, one at a time, plus the latency b), run for
+ * `iterations` iterations; returns the arrival time of the last message divided by their
+ * number, the quantity the theorem's error bound (b + min{T_comp, delta V_g/a}) / E is for. */
+double ddef_t_avg_simulate(uint32_t tau, double delta, double v_g_bits, double a_bps, double b_s,
+                           double t_comp_s, uint64_t iterations);
+/* Look-up table of Section 4.5: DeCo precomputed at `points` bandwidths spaced evenly over
+ * [a_min, a_max] for a measured latency b.  A query inside the range returns the entry of the
+ * nearest sample point (*from_table = 1); outside it DeCo is evaluated online
+ * (*from_table = 0; from_table may be NULL).  The caller destroys the table. */
+typedef struct ddef_lut ddef_lut;
+int ddef_lut_build(double v_g_bits, double a_min_bps, double a_max_bps, uint32_t points, double b_s,
+                   double t_comp_s, ddef_lut** out);
+int ddef_lut_query(const ddef_lut* lut, double a_bps, uint32_t* tau, double* delta, int* from_table);
+int ddef_lut_destroy(ddef_lut* lut);
 
 /* ---- measurement hooks ------------------------------------------------------------------ */
 /* With profiling on, every kernel launch is bracketed by HIP events on the context's

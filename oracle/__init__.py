@@ -178,6 +178,28 @@ def t_avg_recurrence(tau, delta, v_g, a, b, t_comp, E):
                                                float(b), float(t_comp), int(E)))
 
 
+def lut_build(v_g, a_min, a_max, points, b, t_comp):
+    """Section 4.5, pre-computation: DeCo at `points` bandwidths spaced evenly over [a_min, a_max]
+    for the measured latency b.  Returns a list of (bandwidth, (tau, delta) or None)."""
+    table = []
+    for i in range(points):
+        a = a_min + (a_max - a_min) * i / (points - 1)
+        table.append((a, deco(v_g, a, b, t_comp)))
+    return table
+
+
+def lut_query(table, v_g, b, t_comp, a):
+    """Section 4.5, runtime lookup: inside the recorded range the entry of the nearest sample
+    bandwidth, outside it the online computation.  Returns (tau, delta, from_table) or None."""
+    a_min, a_max = table[0][0], table[-1][0]
+    if a_min <= a <= a_max:
+        nearest = min(range(len(table)), key=lambda i: (abs(table[i][0] - a), -i))
+        if table[nearest][1] is not None:
+            return table[nearest][1] + (True,)
+    online = deco(v_g, a, b, t_comp)
+    return None if online is None else online + (False,)
+
+
 class Oracle:
     """Normative (ring-form) DD-EF-SGD state on the CPU."""
 

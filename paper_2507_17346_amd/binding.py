@@ -43,6 +43,14 @@ SIGNATURES = {
     "ddef_get_threshold": (C.c_int, [_ctx, C.c_uint32, _u32p, _u64p]),
     "ddef_k_from_delta": (C.c_uint64, [C.c_double, C.c_uint64]),
     "ddef_deco": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
+    "ddef_phi": (C.c_double, [C.c_double, C.c_double]),
+    "ddef_t_avg_model": (C.c_double, [C.c_uint32, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double]),
+    "ddef_t_avg_simulate": (C.c_double, [C.c_uint32, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
+                                         C.c_uint64]),
+    "ddef_lut_build": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_uint32, C.c_double, C.c_double,
+                                 C.POINTER(C.c_void_p)]),
+    "ddef_lut_query": (C.c_int, [C.c_void_p, C.c_double, _u32p, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
+    "ddef_lut_destroy": (C.c_int, [C.c_void_p]),
     "ddef_profile_enable": (C.c_int, [_ctx, C.c_int]),
     "ddef_profile_slots": (C.c_int, []),
     "ddef_profile_read": (C.c_int, [_ctx, C.c_int, C.POINTER(C.c_char_p), _u64p, C.POINTER(C.c_double)]),
@@ -99,6 +107,55 @@ def deco(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> Optional
     if rc != OK:
         raise DdefError(rc, "ddef_deco")
     return int(tau.value), float(delta.value)
+
+
+def phi(delta: float, tau: float) -> float:
+    return float(load().ddef_phi(float(delta), float(tau)))
+
+
+def t_avg_model(tau: int, delta: float, v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> float:
+    return float(load().ddef_t_avg_model(int(tau), float(delta), float(v_g_bits), float(a_bps), float(b_s),
+                                         float(t_comp_s)))
+
+
+def t_avg_simulate(tau: int, delta: float, v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float,
+                   iterations: int) -> float:
+    return float(load().ddef_t_avg_simulate(int(tau), float(delta), float(v_g_bits), float(a_bps), float(b_s),
+                                            float(t_comp_s), int(iterations)))
+
+
+class DecoLut:
+    """Look-up table of Section 4.5 (ddef_lut_*)."""
+
+    def __init__(self, v_g_bits, a_min_bps, a_max_bps, points, b_s, t_comp_s):
+        self._lib = load()
+        h = C.c_void_p()
+        rc = self._lib.ddef_lut_build(float(v_g_bits), float(a_min_bps), float(a_max_bps), int(points),
+                                      float(b_s), float(t_comp_s), C.byref(h))
+        if rc != OK:
+            raise DdefError(rc, "ddef_lut_build")
+        self._h = h
+
+    def query(self, a_bps: float):
+        """(tau, delta, from_table) or None when DeCo has no candidate."""
+        tau, delta, hit = C.c_uint32(), C.c_double(), C.c_int()
+        rc = self._lib.ddef_lut_query(self._h, float(a_bps), C.byref(tau), C.byref(delta), C.byref(hit))
+        if rc == EINVAL:
+            return None
+        if rc != OK:
+            raise DdefError(rc, "ddef_lut_query")
+        return int(tau.value), float(delta.value), bool(hit.value)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ddef_lut_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def _f32(a) -> Tuple[np.ndarray, "C._Pointer"]:

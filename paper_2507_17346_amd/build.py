@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libddef.so")
-SOURCES = ["ddef_kernels.hip", "ddef_api.hip"]
+SOURCES = ["ddef_kernels.hip", "ddef_api.hip", "ddef_deco.cpp"]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",

@@ -259,29 +259,6 @@ uint64_t ddef_k_from_delta(double delta, uint64_t d) {
     return (uint64_t)want;
 }
 
-int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau, double* delta) {
-    if (!tau || !delta) return DDEF_EINVAL;
-    if (!(v_g_bits > 0.0) || !(a_bps > 0.0) || !(b_s >= 0.0) || !(t_comp_s > 0.0)) return DDEF_EINVAL;
-    if (!std::isfinite(v_g_bits) || !std::isfinite(a_bps) || !std::isfinite(b_s) || !std::isfinite(t_comp_s))
-        return DDEF_EINVAL;
-    const double per_bit = a_bps / v_g_bits;               // fraction of the gradient sent per second
-    const double first = std::ceil((b_s + 1.0 / per_bit) / t_comp_s);
-    const double last = std::ceil(b_s / t_comp_s);
-    if (first > 4.0e9) return DDEF_EINVAL;
-    bool have = false;
-    double phi_min = INFINITY;
-    for (double cand = first; cand >= last; cand -= 1.0) {
-        double ratio = (cand * t_comp_s - b_s) * per_bit;   // transfer hidden behind tau compute slots
-        const double slot = t_comp_s * per_bit;             // transfer no longer than one compute slot
-        if (slot < ratio) ratio = slot;
-        if (ratio > 1.0) ratio = 1.0;
-        if (!(ratio > 0.0)) continue;
-        const double phi = (1.0 - ratio) / (ratio * std::pow(1.0 - ratio / 2.0, cand));
-        if (phi <= phi_min) { phi_min = phi; *tau = (uint32_t)cand; *delta = ratio; have = true; }
-    }
-    return have ? DDEF_OK : DDEF_EINVAL;
-}
-
 const char* ddef_strerror(int code) {
     switch (code) {
         case DDEF_OK: return "ok";
