@@ -72,6 +72,10 @@ def lib():
         "oracle_queue_run": (None, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_double,
                                     C.c_float, f32p, f32p, f32p, C.c_uint64, C.c_int, C.c_float,
                                     f32p, f32p]),
+        "oracle_randk_indices": (None, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64, u32p]),
+        "oracle_randk_permute": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]),
+        "oracle_murmur_fmix32": (C.c_uint32, [C.c_uint32]),
+        "oracle_set_compressor": (None, [vp, C.c_int]),
         "oracle_phi": (C.c_double, [C.c_double, C.c_double]),
         "oracle_delta_star": (C.c_double, [C.c_double] * 5),
         "oracle_deco": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
@@ -152,6 +156,22 @@ def queue_run(lam, xstar, x0, n, tau, T, delta, lr, seed, noise_kind, noise_scal
     return (xf, traj) if trajectory else xf
 
 
+def randk_indices(seed, t, worker, d, k) -> np.ndarray:
+    """Coordinates the Random-k sparsifier keeps for (seed, t, worker), ascending."""
+    out = np.empty(k, dtype=np.uint32)
+    lib().oracle_randk_indices(int(seed), int(t), int(worker), int(d), int(k),
+                               out.ctypes.data_as(C.POINTER(C.c_uint32)))
+    return out
+
+
+def randk_permute(seed, t, worker, d, m) -> int:
+    return int(lib().oracle_randk_permute(int(seed), int(t), int(worker), int(d), int(m)))
+
+
+def murmur_fmix32(h: int) -> int:
+    return int(lib().oracle_murmur_fmix32(C.c_uint32(h)))
+
+
 def phi(delta, tau):
     return float(lib().oracle_phi(float(delta), float(tau)))
 
@@ -227,6 +247,10 @@ class Oracle:
 
     def set_tau(self, tau):
         lib().oracle_set_tau(self._h, int(tau))
+
+    def set_compressor(self, kind):
+        """0: Top-k (default), 1: Random-k."""
+        lib().oracle_set_compressor(self._h, int(kind))
 
     @property
     def t(self):

@@ -15,6 +15,7 @@
 //   stale iterate     gradient taken at x_{t-tau}             Section 2.2.3
 //   EF accumulate     p = e + gamma*g                         Algorithm 1, worker side
 //   compressor        Top-k of p, k = ceil(delta*d)           Section 5.2 "Baselines"; Top-k lemma
+//   other sparsifier  Random-k: k entries chosen at random    Appendix "Experiment Results with other sparsifiers"
 //   residual          e' = e + gamma*g - Delta                Algorithm 1, worker side
 //   server update     x' = x - (1/n) sum_i Delta_i            Algorithm 1, server side
 //   start-up          Delta_{t-tau} = 0 while t-tau < 0       Section 3.2, boundary convention
@@ -173,6 +174,57 @@ void topk_select(const float* p, uint64_t d, uint64_t k, uint32_t* idx_out,
     if (r_out) *r_out = r;
 }
 
+// ---------------------------------------------------------------------------------
+// Random-k: the k coordinates pi(0), ..., pi(k-1) of a keyed pseudo-random permutation pi
+// of [0, d).  pi is a 4-round Feistel network on 2w bits (w = smallest with 4^w >= d) whose
+// round function is the MurmurHash3 32-bit finaliser of (half XOR round key), cut to w
+// bits, walked until the value falls below d (cycle walking keeps it a bijection of
+// [0, d)).  Round keys: the Philox block with counter (0xFFFFFFFF, worker, t) under the
+// seed -- a counter word no noise draw uses, since coordinates stay below 2^32 - 8192.
+// ---------------------------------------------------------------------------------
+uint32_t murmur_fmix32(uint32_t h) {
+    h ^= h >> 16; h *= 0x85ebca6bu; h ^= h >> 13; h *= 0xc2b2ae35u; h ^= h >> 16;
+    return h;
+}
+
+struct RandkKey { uint32_t round_key[4]; uint32_t w; uint64_t d; };
+
+RandkKey randk_key(uint64_t seed, uint64_t t, uint32_t worker, uint64_t d) {
+    RandkKey key;
+    uint32_t ctr[4] = {0xffffffffu, worker, (uint32_t)t, (uint32_t)(t >> 32)};
+    uint32_t sk[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    philox4x32_10(ctr, sk, key.round_key);
+    key.w = 1;
+    while (((uint64_t)1 << (2 * key.w)) < d) ++key.w;
+    key.d = d;
+    return key;
+}
+
+uint64_t feistel_forward(const RandkKey& key, uint64_t x) {
+    const uint32_t mask = (uint32_t)(((uint64_t)1 << key.w) - 1);
+    uint32_t left = (uint32_t)(x >> key.w), right = (uint32_t)x & mask;
+    for (int r = 0; r < 4; ++r) {
+        uint32_t f = murmur_fmix32(right ^ key.round_key[r]) & mask;
+        uint32_t new_right = left ^ f;
+        left = right;
+        right = new_right;
+    }
+    return ((uint64_t)left << key.w) | right;
+}
+
+uint64_t randk_permute(const RandkKey& key, uint64_t m) {
+    uint64_t y = feistel_forward(key, m);
+    while (y >= key.d) y = feistel_forward(key, y);
+    return y;
+}
+
+// the chosen coordinates in ascending order
+void randk_select(uint64_t seed, uint64_t t, uint32_t worker, uint64_t d, uint64_t k, uint32_t* idx_out) {
+    RandkKey key = randk_key(seed, t, worker, d);
+    for (uint64_t m = 0; m < k; ++m) idx_out[m] = (uint32_t)randk_permute(key, m);
+    std::sort(idx_out, idx_out + k);
+}
+
 uint64_t k_from_delta(double delta, uint64_t d) {
     double kd = std::ceil(delta * (double)d);
     if (kd < 1.0) kd = 1.0;
@@ -191,6 +243,7 @@ struct Oracle {
     int noise_kind = 0;
     float noise_scale = 0.0f;
     int threads = 1;
+    int compressor = 0;                 // 0: Top-k, 1: Random-k
     bool step_is_noop = false;
     std::vector<float> lambda, xstar, U;
     std::vector<std::vector<float>> ring, e, g;
@@ -235,7 +288,12 @@ void compress_worker(Oracle* o, uint32_t i, uint64_t k, float lr) {
     }
     o->msg_idx[i].assign(k, 0u);
     o->msg_val[i].assign(k, 0.0f);
-    topk_select(p.data(), d, k, o->msg_idx[i].data(), &o->thr_T[i], &o->thr_r[i]);
+    if (o->compressor == 1) {
+        randk_select(o->seed, o->t, i, d, k, o->msg_idx[i].data());
+        o->thr_T[i] = 0; o->thr_r[i] = 0;
+    } else {
+        topk_select(p.data(), d, k, o->msg_idx[i].data(), &o->thr_T[i], &o->thr_r[i]);
+    }
     std::vector<float> dense(d, 0.0f);                  // Delta as a dense vector
     for (uint64_t m = 0; m < k; ++m) {
         uint32_t j = o->msg_idx[i][m];
@@ -271,6 +329,15 @@ void oracle_topk(const float* p, uint64_t d, uint64_t k, uint32_t* idx_out, uint
                  uint64_t* r_out) {
     topk_select(p, d, k, idx_out, T_out, r_out);
 }
+
+void oracle_randk_indices(uint64_t seed, uint64_t t, uint32_t worker, uint64_t d, uint64_t k, uint32_t* idx_out) {
+    randk_select(seed, t, worker, d, k, idx_out);
+}
+uint64_t oracle_randk_permute(uint64_t seed, uint64_t t, uint32_t worker, uint64_t d, uint64_t m) {
+    return randk_permute(randk_key(seed, t, worker, d), m);
+}
+uint32_t oracle_murmur_fmix32(uint32_t h) { return murmur_fmix32(h); }
+void oracle_set_compressor(void* h, int kind) { ((Oracle*)h)->compressor = kind; }
 
 void* oracle_create(uint64_t d, uint32_t n, uint32_t tau_max) {
     Oracle* o = new Oracle;
