@@ -33,6 +33,7 @@ VALU_PER_DRAW = {2: 214.8}
 # algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
 ALGO_BYTES_PER_ELEM = {
     "k_ef_filter": 12.0,       # read e, read g, write p (the candidate filter rides along)
+    "k_ef_randk": 12.0,        # same pass for Random-k (+ 1/8 byte of bitmap)
     "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
     "k_digit_hist": 4.0, "k_chunk_count": 4.0, "k_chunk_emit": 4.0,   # whole-row search passes
 }
@@ -56,7 +57,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None):
+def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, compressor=0):
     """The oracle, as it stands, on a bounded sample: one non-empty iteration over the first
     sample_d coordinates of the workload (all n workers, one thread per worker unless capped)."""
     import oracle
@@ -74,6 +75,7 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None):
     o = oracle.Oracle(sample_d, w.n, 0, threads=threads)
     o.set_problem(lam[:sample_d], xstar[:sample_d], x0[:sample_d], w.seed, w.noise_kind, w.noise_scale)
     o.set_tau(0)
+    o.set_compressor(compressor)
     t0 = time.perf_counter()
     o.step(w.deltas[0], w.lr)
     dt = time.perf_counter() - t0
@@ -121,6 +123,8 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="shrink d (debug only; not a valid bench)")
     ap.add_argument("--delta", type=float, default=None,
                     help="fix the compression ratio (study runs only; the default follows the workload)")
+    ap.add_argument("--compressor", choices=["topk", "randk"], default="topk",
+                    help="sparsifier: the paper's default Top-k, or its appendix's Random-k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -145,6 +149,8 @@ def main():
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
     ctx = binding.Context(w.d, w.n, w.tau_max)
     ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK}[args.compressor]
+    ctx.set_compressor(compressor)
 
     state = {"tau": None}
 
@@ -253,6 +259,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
+                   "compressor": args.compressor,
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,
@@ -266,11 +273,13 @@ def main():
         sample_d = args.cpu_sample_d or min(w.d, 124_000_000)
         note = ""
         try:
-            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note)
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note, compressor=compressor)
         except MemoryError:
-            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory")
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory",
+                                               compressor=compressor)
         # the same oracle on one thread, on an eighth of the coordinates to keep the run short
-        out["cpu_baseline_single_thread"] = cpu_baseline(w, lam, xstar, x0, max(1, sample_d // 8), "", max_threads=1)
+        out["cpu_baseline_single_thread"] = cpu_baseline(w, lam, xstar, x0, max(1, sample_d // 8), "",
+                                                         max_threads=1, compressor=compressor)
     ctx.close()
     print(json.dumps(out), flush=True)
 

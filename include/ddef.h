@@ -47,6 +47,10 @@ extern "C" {
 #define DDEF_ENOMEM (-3)     /* device or host allocation failed                          */
 #define DDEF_EHIP (-4)       /* a HIP runtime call failed; sticky for the context         */
 #define DDEF_ENONFINITE (-5) /* reserved: NaN/Inf met where finite input is required      */
+#define DDEF_EINTERNAL (-6)  /* an invariant of the library broke on the device; sticky   */
+
+#define DDEF_COMPRESSOR_TOPK 0  /* keep the k largest magnitudes (default)                  */
+#define DDEF_COMPRESSOR_RANDK 1 /* keep k coordinates drawn at random per worker, iteration */
 
 #define DDEF_NOISE_NONE 0
 #define DDEF_NOISE_GAUSS 1      /* N(0,1) * noise_scale                                    */
@@ -71,6 +75,16 @@ int ddef_set_stream(ddef_ctx* ctx, void* hip_stream);
  * counter-based draw keyed by (seed, t, worker, j): Philox4x32-10, Box-Muller. */
 int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_xstar,
                      const float* host_x0, uint64_t seed, int noise_kind, float noise_scale);
+
+/* The sparsifier C_delta of the following iterations.  Top-k is the paper's default
+ * (Section 5.2); Random-k is its other sparsifier (appendix "Experiment Results with other
+ * sparsifiers": k entries chosen at random).  Random-k keeps the coordinates pi(0..k-1) of a
+ * permutation pi of [0, d) keyed by (seed, t, worker): a 4-round Feistel network over the
+ * smallest even-width bit field holding d, round function MurmurHash3's 32-bit finaliser of
+ * (half XOR round key), cycle-walked into [0, d), round keys from Philox4x32-10 with counter
+ * (0xFFFFFFFF, worker, t).  Messages, error feedback and k = ceil(delta*d) are as for Top-k;
+ * ddef_get_threshold reports (0, 0).  Only between iterations. */
+int ddef_set_compressor(ddef_ctx* ctx, int kind);
 
 /* Staleness for the following iterations, 0..tau_max (Algorithm 2 re-chooses it every E
  * iterations).  Only between iterations, else ESTATE. */

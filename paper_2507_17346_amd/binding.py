@@ -13,7 +13,8 @@ import numpy as np
 
 from . import build as _build
 
-OK, EINVAL, ESTATE, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ESTATE, ENOMEM, EHIP, ENONFINITE, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
+COMPRESSOR_TOPK, COMPRESSOR_RANDK = 0, 1
 NOISE_NONE, NOISE_GAUSS, NOISE_STUDENT_T3 = 0, 1, 2
 OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16 = 1, 2
 
@@ -26,6 +27,7 @@ SIGNATURES = {
     "ddef_set_stream": (C.c_int, [_ctx, C.c_void_p]),
     "ddef_set_problem": (C.c_int, [_ctx, _f32p, _f32p, _f32p, C.c_uint64, C.c_int, C.c_float]),
     "ddef_set_tau": (C.c_int, [_ctx, C.c_uint32]),
+    "ddef_set_compressor": (C.c_int, [_ctx, C.c_int]),
     "ddef_grad": (C.c_int, [_ctx]),
     "ddef_load_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
@@ -213,6 +215,9 @@ class Context:
 
     def set_tau(self, tau: int):
         self._check(self._lib.ddef_set_tau(self._h, int(tau)), "ddef_set_tau")
+
+    def set_compressor(self, kind: int):
+        self._check(self._lib.ddef_set_compressor(self._h, int(kind)), "ddef_set_compressor")
 
     def set_option(self, option: int, value: int):
         self._check(self._lib.ddef_set_option(self._h, int(option), int(value)), "ddef_set_option")

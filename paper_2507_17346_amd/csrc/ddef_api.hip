@@ -19,12 +19,12 @@ namespace {
 enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
-    SL_GRAD = 0, SL_EF_FILTER, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
+    SL_GRAD = 0, SL_EF_FILTER, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
     SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
-    "k_grad", "k_ef_filter", "k_tab_sum", "k_tab_decide", "k_tab_order",
+    "k_grad", "k_ef_filter", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
     "k_unscatter", "k_fill_f4", "k_scatter_add", "k_apply", "k_copy_f4"};
 
@@ -57,6 +57,8 @@ struct ddef_ctx {
     float* sorted_val = nullptr;
     uint64_t cap = 0;
     bool have_bound = false;
+    int compressor = DDEF_COMPRESSOR_TOPK;
+    uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
     // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each)
     uint64_t u_dirty_k = 0;
     Phase phase = PH_IDLE;
@@ -167,13 +169,15 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
         HIP_TRY(c, hipMemset(c->msg_val, 0, (size_t)c->n * len * 4u));
         c->msg_ld = len;
     }
-    // room for the candidates: three times the target while messages are sparse, twice otherwise
+    // room for the candidates: three times the target while messages are sparse, twice otherwise,
+    // at least 32 slots in each of the kSubs parts of the buffer, plus one whole 256-entry group
+    // per part (a part fills unevenly when d is small or the selection is dense); never more than
+    // every coordinate can need
     const bool sparse = k * 32u <= c->d;
-    // and at least 32 slots in each of the kSubs parts of the buffer
     uint64_t want = (sparse ? 3u : 2u) * kb;
     if (want < 32u * kSubs) want = 32u * kSubs;
-    want = (want + 4095u) & ~(uint64_t)4095u;
     if (want > c->ld) want = c->ld;
+    want = ((want + 4095u) & ~(uint64_t)4095u) + 256u * kSubs;
     if (want > c->cap) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         if (c->cand) (void)hipFree(c->cand);
@@ -236,6 +240,17 @@ int check_ctx(ddef_ctx* c) {
     return DDEF_OK;
 }
 
+// After a Random-k selection the device flags a worker whose runs did not hold exactly k
+// entries (slot overflow).  Called with the stream idle.
+int check_selection(ddef_ctx* c) {
+    if (c->compressor != DDEF_COMPRESSOR_RANDK || c->k_step == 0) return DDEF_OK;
+    std::vector<SelState> st(c->n);
+    HIP_TRY(c, hipMemcpy(st.data(), c->sel, sizeof(SelState) * c->n, hipMemcpyDeviceToHost));
+    for (const SelState& s : st)
+        if (s.active == 2u) { c->sticky = DDEF_EINTERNAL; return DDEF_EINTERNAL; }
+    return DDEF_OK;
+}
+
 int copy_row_out(ddef_ctx* c, const float* dev_row, float* host) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(host, dev_row, (size_t)c->d * 4u, hipMemcpyDeviceToHost));
@@ -268,6 +283,7 @@ const char* ddef_strerror(int code) {
         case DDEF_ENOMEM: return "out of memory";
         case DDEF_EHIP: return "HIP runtime error";
         case DDEF_ENONFINITE: return "non-finite value";
+        case DDEF_EINTERNAL: return "internal invariant violated";
         default: return "unknown error";
     }
 }
@@ -319,7 +335,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->bitmap, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -361,6 +377,15 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
     c->u_dirty_k = 0;
+    return DDEF_OK;
+}
+
+int ddef_set_compressor(ddef_ctx* c, int kind) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    c->compressor = kind;
     return DDEF_OK;
 }
 
@@ -426,11 +451,35 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     if (rc) return rc;
     const uint32_t n = c->n;
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
+    uint32_t* cand_total = c->filt + 3 * n;
+    if (c->compressor == DDEF_COMPRESSOR_RANDK) {
+        const uint64_t bitmap_ld = c->ld / 32u;
+        if (!c->bitmap) {
+            HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
+            HIP_TRY(c, hipMemsetAsync(c->bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream));
+        }
+        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
+               c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+        LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
+               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
+        LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               c->span_sum, c->nspans);
+        LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_randk, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
+               (uint32_t)k, c->sel, cand_total, cand_count);
+        LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
+               c->msg_idx, c->msg_val, c->msg_ld);
+        HIP_TRY(c, hipGetLastError());
+        c->have_bound = false;          // a Top-k bound from before no longer describes e
+        c->k_step = k;
+        c->phase = PH_COMPRESSED;
+        return DDEF_OK;
+    }
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
     LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
            (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
-    uint32_t* cand_total = c->filt + 3 * n;
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
@@ -439,7 +488,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                stat_full, c->hist);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
-               c->sorted_idx, c->sorted_val);
+               c->sorted_idx, c->sorted_val, c->cap);
     } else {
         LAUNCH(c, SL_SEL_BEGIN_ROWS, k_sel_begin_rows, dim3(n), dim3(256), c->sel, n, (uint32_t)k, (uint32_t)kb,
                (uint32_t)c->d, cand_total, c->hist);
@@ -492,7 +541,7 @@ int ddef_sync(ddef_ctx* c) {
     if (rc) return rc;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return DDEF_OK;
+    return check_selection(c);
 }
 
 int ddef_step_index(ddef_ctx* c, uint64_t* t) {
@@ -560,6 +609,8 @@ int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* ho
     if (!host_idx || !host_val || c->k_step == 0) return DDEF_OK;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    rc = check_selection(c);
+    if (rc) return rc;
     HIP_TRY(c, hipMemcpy(host_idx, c->msg_idx + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
                          hipMemcpyDeviceToHost));
     HIP_TRY(c, hipMemcpy(host_val, c->msg_val + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,

@@ -16,7 +16,7 @@ constexpr uint32_t kSpan = 1024;
 
 // Per-worker selection state in device memory.
 struct SelState {
-    uint32_t active;      // 1: search the whole row; 0: search the filtered candidates
+    uint32_t active;      // 1: search the whole row; 0: search the filtered candidates; 2: invariant broken
     uint32_t prefix[2];   // magnitude pattern built so far for rank 0 (k) and rank 1 (filter)
     uint32_t krem[2];     // rank still to find inside the current prefix group (1-based)
     uint32_t T, r;        // threshold pattern and how many entries equal to T are sent
@@ -53,7 +53,14 @@ __global__ void k_sel_begin_rows(SelState* sel, uint32_t n, uint32_t k, uint32_t
                                  uint32_t* cand_total, uint32_t* hist);
 __global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* span_off, uint32_t nspans,
                             const SelState* sel, const uint2* cand, uint64_t cap, uint32_t* sorted_idx,
-                            float* sorted_val);
+                            float* sorted_val, uint64_t out_ld);
+__global__ void k_randk_mark(uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d, uint32_t k, uint32_t seed_lo,
+                             uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
+__global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, uint32_t* bitmap,
+                           uint64_t bitmap_ld, uint2* cand, uint64_t cap, uint32_t* cand_count,
+                           uint32_t* overflow, uint2* tab, uint32_t ngroups);
+__global__ void k_tab_decide_randk(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k,
+                                   SelState* sel, uint32_t* cand_total, uint32_t* cand_count);
 __global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);
 __global__ void k_digit_pick(SelState* sel, const uint32_t* hist, int level);
 __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,

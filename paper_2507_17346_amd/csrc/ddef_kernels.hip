@@ -262,6 +262,136 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
     if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
 }
 
+// ------------------------------------------------------------------------------------
+// Random-k sparsifier (the paper's appendix on other sparsifiers): worker w keeps the k
+// coordinates pi(0..k-1) of a keyed permutation pi of [0, d), drawn afresh for every
+// (worker, iteration).  pi: 4-round Feistel network on 2w bits, round function = MurmurHash3's
+// 32-bit finaliser of (half ^ round key) cut to w bits, cycle-walked into [0, d); round keys =
+// the Philox block of counter (0xFFFFFFFF, worker, t), which no noise draw uses.
+// k_randk_mark sets the chosen coordinates' bits in a bitmap; k_ef_randk is the accumulate
+// pass that reads its 256 bits per group, sends the marked entries (same run mechanism as the
+// Top-k candidates, but here the runs *are* the message) and writes the residual in one go.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t fmix32(uint32_t h) {
+    h ^= h >> 16; h *= 0x85ebca6bu; h ^= h >> 13; h *= 0xc2b2ae35u; h ^= h >> 16;
+    return h;
+}
+
+__global__ __launch_bounds__(256) void k_randk_mark(uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
+                                                    uint32_t d, uint32_t k, uint32_t seed_lo,
+                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
+    const uint32_t w = blockIdx.y;
+    const U4 rk = philox_block(0xffffffffu, w, t_lo, t_hi, seed_lo, seed_hi);
+    const uint32_t key[4] = {rk.a, rk.b, rk.c, rk.d};
+    uint32_t half = 1;
+    while (((uint64_t)1 << (2u * half)) < (uint64_t)d) ++half;
+    const uint32_t mask = (uint32_t)(((uint64_t)1 << half) - 1u);
+    uint32_t* row = bitmap + (uint64_t)w * bitmap_ld;
+    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
+        uint64_t y = m;
+        do {                                   // walk until the image falls inside [0, d)
+            uint32_t left = (uint32_t)(y >> half), right = (uint32_t)y & mask;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t nr = left ^ (fmix32(right ^ key[r]) & mask);
+                left = right;
+                right = nr;
+            }
+            y = ((uint64_t)left << half) | right;
+        } while (y >= (uint64_t)d);
+        atomicOr(&row[(uint32_t)y >> 5], 1u << ((uint32_t)y & 31u));
+    }
+}
+
+// grid (ld/256, n), one wave per block, as k_ef_filter.  Eight lanes share one bitmap word;
+// the first of them clears it after the group has read it, so the bitmap is all-zero again
+// when the pass is over.
+__global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const float* __restrict__ g,
+                                                 uint64_t ld, uint32_t d, float lr,
+                                                 uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
+                                                 uint2* __restrict__ cand, uint64_t cap,
+                                                 uint32_t* __restrict__ cand_count,
+                                                 uint32_t* __restrict__ overflow,
+                                                 uint2* __restrict__ tab, uint32_t ngroups) {
+    const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
+    const uint32_t j = grp * 256u + lane * 4u;
+    uint32_t* word = bitmap + (uint64_t)w * bitmap_ld + (j >> 5);
+    const uint32_t bitsel = (*word >> (j & 31u)) & 0xfu;     // this lane's four coordinates
+    float pv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j < d) {
+        float* ep = e + (uint64_t)w * ld + j;
+        const float4 ev = load_stream4(ep);
+        const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
+        pv[0] = ev.x + lr * gv.x;
+        pv[1] = ev.y + lr * gv.y;
+        pv[2] = ev.z + lr * gv.z;
+        pv[3] = ev.w + lr * gv.w;
+        float res[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) res[c] = ((bitsel >> c) & 1u) ? 0.0f : pv[c];
+        store_stream4(ep, res);
+    }
+    const bool any = bitsel != 0u;
+    uint32_t first = 0, total = 0;
+    if (__ballot(any)) {
+        if ((lane & 7u) == 0u) *word = 0u;                   // every lane of the group has read it
+        uint32_t below = 0;
+        bool f[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            f[c] = (bitsel >> c) & 1u;
+            const uint64_t m = __ballot(f[c]);
+            below += mask_rank(m);
+            total += (uint32_t)__popcll(m);
+        }
+        const uint32_t sub = grp & (kSubs - 1u);
+        const uint32_t sub_cap = (uint32_t)(cap / kSubs);
+        uint32_t got = 0;
+        if (lane == 0) got = atomicAdd(&cand_count[(w * kSubs + sub) * kSubStride], total);
+        got = __shfl(got, 0, 64);
+        if (got + total > sub_cap) {
+            if (lane == 0) overflow[w] = 1u;
+        } else {
+            first = sub * sub_cap + got;
+            uint2* cw = cand + (uint64_t)w * cap;
+            uint32_t pos = first + below;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
+        }
+    }
+    if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
+}
+
+// One block per worker: span sums -> span offsets; the runs must hold exactly k entries.
+// sel[w].active = 0 lets k_tab_order copy the runs; 2 flags a broken invariant (slot overflow).
+__global__ __launch_bounds__(256) void k_tab_decide_randk(uint32_t* __restrict__ span_sum, uint32_t nspans,
+                                                          uint32_t* __restrict__ overflow, uint32_t k,
+                                                          SelState* __restrict__ sel,
+                                                          uint32_t* __restrict__ cand_total,
+                                                          uint32_t* __restrict__ cand_count) {
+    __shared__ uint32_t lds[5];
+    const uint32_t w = blockIdx.x;
+    uint32_t* sw = span_sum + (uint64_t)w * nspans;
+    uint32_t carry = 0;
+    for (uint32_t first = 0; first < nspans; first += 256u) {
+        const uint32_t sp = first + threadIdx.x;
+        const uint32_t v = sp < nspans ? sw[sp] : 0u;
+        uint32_t total;
+        const uint32_t at = carry + block_excl_scan(v, lds, &total);
+        if (sp < nspans) sw[sp] = at;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        const bool fine = overflow[w] == 0u && carry == k;
+        cand_total[w] = carry;
+        sel[w].active = fine ? 0u : 2u;
+        sel[w].T = 0u; sel[w].r = 0u; sel[w].seen = carry;
+        overflow[w] = 0u;
+    }
+    for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[(w * kSubs + q) * kSubStride] = 0u;
+}
+
 // ---- run table -> coordinate order ------------------------------------------------------
 // tab[w][c].y is the run length of group c.  Three small kernels turn the lengths into
 // positions in coordinate order: sums over spans of 1024 groups, a scan of the span sums that
@@ -344,14 +474,14 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 
 // Prefixes inside a span, and with them the candidates in coordinate order: group c's run
 // cand[first .. first+len) goes to positions [at, at+len) of the ordered arrays (index,
-// value).  The block copies its span's candidates together: thread q takes the q-th, finds
+// value; rows of out_ld entries).  The block copies its span's candidates together: thread q takes the q-th, finds
 // its group by bisection over the span's prefixes in LDS, and the stores are coalesced.
 __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ tab, uint32_t ngroups,
                                                     const uint32_t* __restrict__ span_off,
                                                     uint32_t nspans, const SelState* __restrict__ sel,
                                                     const uint2* __restrict__ cand, uint64_t cap,
                                                     uint32_t* __restrict__ sorted_idx,
-                                                    float* __restrict__ sorted_val) {
+                                                    float* __restrict__ sorted_val, uint64_t out_ld) {
     __shared__ uint32_t lds[17];
     __shared__ uint32_t at_of[kSpan];        // exclusive prefix of the run lengths inside the span
     __shared__ uint32_t first_of[kSpan];     // first slot of each run
@@ -366,7 +496,7 @@ __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ ta
     __syncthreads();
     if (total == 0u) return;
     const uint2* cw = cand + (uint64_t)w * cap;
-    const uint64_t out0 = (uint64_t)w * cap + span_off[(uint64_t)w * nspans + sp];
+    const uint64_t out0 = (uint64_t)w * out_ld + span_off[(uint64_t)w * nspans + sp];
     for (uint32_t q = threadIdx.x; q < total; q += kSpan) {
         uint32_t lo = 0, hi = kSpan;           // first group in [lo, hi) whose prefix exceeds q
         while (lo < hi) {
