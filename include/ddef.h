@@ -46,7 +46,7 @@ extern "C" {
 #define DDEF_ESTATE (-2)     /* call order violated                                       */
 #define DDEF_ENOMEM (-3)     /* device or host allocation failed                          */
 #define DDEF_EHIP (-4)       /* a HIP runtime call failed; sticky for the context         */
-#define DDEF_ENONFINITE (-5) /* reserved: NaN/Inf met where finite input is required      */
+#define DDEF_ENONFINITE (-5) /* NaN/Inf appeared in e + lr*g; sticky until ddef_set_problem  */
 #define DDEF_EINTERNAL (-6)  /* an invariant of the library broke on the device; sticky   */
 
 #define DDEF_COMPRESSOR_TOPK 0  /* keep the k largest magnitudes (default)                  */
@@ -114,7 +114,10 @@ int ddef_aggregate(ddef_ctx* ctx);
  * feedback, as in Algorithm 1; it is checked, not applied a second time), else EINVAL. */
 int ddef_apply_delayed(ddef_ctx* ctx, float lr);
 
-/* Wait for the context's stream. */
+/* Wait for the context's stream.  Also reports what the kernels flagged meanwhile:
+ * DDEF_ENONFINITE when some e + lr*g was Inf or NaN (the method needs finite values; the
+ * context then refuses further work until ddef_set_problem), DDEF_EINTERNAL when a device-side
+ * invariant broke.  ddef_get_message reports the same. */
 int ddef_sync(ddef_ctx* ctx);
 
 /* ---- inspection / checkpoint hooks (each waits for the stream) ------------------------ */

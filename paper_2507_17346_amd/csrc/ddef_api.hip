@@ -44,7 +44,7 @@ struct ddef_ctx {
     uint64_t msg_ld = 0;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
-    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total], slot
+    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite], slot
     // counters [n][kSubs], the run table per 256-entry group with its prefixes, and the
     // candidate buffers of `cap` entries per worker
     uint32_t* filt = nullptr;
@@ -240,9 +240,14 @@ int check_ctx(ddef_ctx* c) {
     return DDEF_OK;
 }
 
-// After a Random-k selection the device flags a worker whose runs did not hold exactly k
-// entries (slot overflow).  Called with the stream idle.
-int check_selection(ddef_ctx* c) {
+// Flags the kernels raise on the device, read with the stream idle: a non-finite entry of
+// e + lr*g (finite input is required; the selection order is undefined for NaN), and, after a
+// Random-k selection, a worker whose runs did not hold exactly k entries (slot overflow).
+int check_device_flags(ddef_ctx* c) {
+    std::vector<uint32_t> bad(c->n, 0u);
+    HIP_TRY(c, hipMemcpy(bad.data(), c->filt + 4 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
+    for (uint32_t v : bad)
+        if (v) { c->sticky = DDEF_ENONFINITE; return DDEF_ENONFINITE; }
     if (c->compressor != DDEF_COMPRESSOR_RANDK || c->k_step == 0) return DDEF_OK;
     std::vector<SelState> st(c->n);
     HIP_TRY(c, hipMemcpy(st.data(), c->sel, sizeof(SelState) * c->n, hipMemcpyDeviceToHost));
@@ -314,7 +319,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
         {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
-        {(void**)&c->filt, (size_t)4 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
     };
     for (const Want& w : wants) {
@@ -355,6 +360,7 @@ int ddef_set_stream(ddef_ctx* c, void* hip_stream) {
 
 int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xstar, const float* host_x0,
                      uint64_t seed, int noise_kind, float noise_scale) {
+    if (c && c->sticky == DDEF_ENONFINITE) c->sticky = DDEF_OK;      // a fresh problem starts clean
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!host_lambda || !host_xstar || !host_x0) return DDEF_EINVAL;
@@ -370,7 +376,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
-    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)4 * c->n * 4));
+    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)5 * c->n * 4));
     HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
     c->have_bound = false;
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
@@ -462,7 +468,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
                (uint32_t)c->t, (uint32_t)(c->t >> 32));
         LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
-               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
+               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_randk, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
@@ -479,7 +485,8 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
     LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
-           (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc);
+           (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc,
+           c->filt + 4 * n);
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
@@ -541,7 +548,7 @@ int ddef_sync(ddef_ctx* c) {
     if (rc) return rc;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return check_selection(c);
+    return check_device_flags(c);
 }
 
 int ddef_step_index(ddef_ctx* c, uint64_t* t) {
@@ -609,7 +616,7 @@ int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* ho
     if (!host_idx || !host_val || c->k_step == 0) return DDEF_OK;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    rc = check_selection(c);
+    rc = check_device_flags(c);
     if (rc) return rc;
     HIP_TRY(c, hipMemcpy(host_idx, c->msg_idx + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
                          hipMemcpyDeviceToHost));

@@ -44,7 +44,8 @@ __global__ void k_grad(const float* lambda, const float* xstar, const float* xs,
                        uint32_t t_lo, uint32_t t_hi, int kind, float scale);
 __global__ void k_ef_filter(float* e, const float* g, uint64_t ld, uint32_t d, float lr,
                             const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
-                            uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups);
+                            uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups,
+                            uint32_t* nonfinite);
 __global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
 __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
                              uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,
@@ -58,7 +59,7 @@ __global__ void k_randk_mark(uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d, u
                              uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
 __global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, uint32_t* bitmap,
                            uint64_t bitmap_ld, uint2* cand, uint64_t cap, uint32_t* cand_count,
-                           uint32_t* overflow, uint2* tab, uint32_t ngroups);
+                           uint32_t* overflow, uint2* tab, uint32_t ngroups, uint32_t* nonfinite);
 __global__ void k_tab_decide_randk(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k,
                                    SelState* sel, uint32_t* cand_total, uint32_t* cand_count);
 __global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);

@@ -74,6 +74,15 @@ __device__ __forceinline__ void store_stream4(float* p, const float (&v)[4]) {
 
 __device__ __forceinline__ uint32_t mag_key(float v) { return __float_as_uint(v) & 0x7fffffffu; }
 
+// True for the whole wave when any lane holds an Inf or NaN among its four values (entries of
+// the row padding are zero and never trigger).
+__device__ __forceinline__ bool note_nonfinite(const float (&v)[4]) {
+    bool bad = false;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) bad |= mag_key(v[c]) >= 0x7f800000u;
+    return __ballot(bad) != 0ull;
+}
+
 // ------------------------------------------------------------------------------------
 // gradient noise: Philox4x32-10 (Salmon et al., SC'11) + Box-Muller out of +,-,*,/,sqrt and
 // explicit fused multiply-adds.  Every fp32 operation is written out (the file is compiled
@@ -214,7 +223,8 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
                                                   uint2* __restrict__ cand, uint64_t cap,
                                                   uint32_t* __restrict__ cand_count,
                                                   uint32_t* __restrict__ overflow,
-                                                  uint2* __restrict__ tab, uint32_t ngroups) {
+                                                  uint2* __restrict__ tab, uint32_t ngroups,
+                                                  uint32_t* __restrict__ nonfinite) {
     const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
     const uint32_t j = grp * 256u + lane * 4u;
     float pv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -228,6 +238,7 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         pv[3] = ev.w + lr * gv.w;
         store_stream4(ep, pv);
     }
+    if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
     if (!use_filter) return;
     const uint32_t L = bound[w];
     bool f[4];
@@ -312,7 +323,8 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
                                                  uint2* __restrict__ cand, uint64_t cap,
                                                  uint32_t* __restrict__ cand_count,
                                                  uint32_t* __restrict__ overflow,
-                                                 uint2* __restrict__ tab, uint32_t ngroups) {
+                                                 uint2* __restrict__ tab, uint32_t ngroups,
+                                                 uint32_t* __restrict__ nonfinite) {
     const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
     const uint32_t j = grp * 256u + lane * 4u;
     uint32_t* word = bitmap + (uint64_t)w * bitmap_ld + (j >> 5);
@@ -331,6 +343,7 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
         for (int c = 0; c < 4; ++c) res[c] = ((bitsel >> c) & 1u) ? 0.0f : pv[c];
         store_stream4(ep, res);
     }
+    if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
     const bool any = bitsel != 0u;
     uint32_t first = 0, total = 0;
     if (__ballot(any)) {

@@ -348,3 +348,23 @@ def test_filter_with_ties_at_the_threshold(ddef, oracle_mod):
         g.aggregate(); o.aggregate(); g.apply_delayed(1.0); o.apply_delayed()
     assert g.full_select_count() < 6
     g.close()
+
+
+def test_non_finite_values_are_reported(ddef):
+    d = 10_000
+    c = ddef.Context(d, 2, 0)
+    one = np.ones(d, dtype=F32)
+    c.set_problem(one, one, one, 0, 0, 0.0)
+    c.step(0.1, 0.05)
+    assert c.raw("sync") == ddef.OK
+    g = np.zeros(d, dtype=F32)
+    g[1234] = np.inf
+    c.load_grad(0, np.zeros(d, dtype=F32))
+    c.load_grad(1, g)
+    c.ef_compress(0.1, 0.05)
+    assert c.raw("sync") == ddef.ENONFINITE
+    assert c.raw("aggregate") == ddef.ENONFINITE          # refused until a fresh problem is set
+    c.set_problem(one, one, one, 0, 0, 0.0)
+    c.step(0.1, 0.05)
+    assert c.raw("sync") == ddef.OK
+    c.close()
