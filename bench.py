@@ -125,6 +125,8 @@ def main():
                     help="fix the compression ratio (study runs only; the default follows the workload)")
     ap.add_argument("--compressor", choices=["topk", "randk"], default="topk",
                     help="sparsifier: the paper's default Top-k, or its appendix's Random-k")
+    ap.add_argument("--prefetch", type=int, default=0,
+                    help="1: generate the next iteration's gradient on a second stream meanwhile")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -151,6 +153,7 @@ def main():
     ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
     compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK}[args.compressor]
     ctx.set_compressor(compressor)
+    ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
 
     state = {"tau": None}
 
@@ -259,7 +262,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor,
+                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,

@@ -193,6 +193,14 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
 /* Tuning / test knobs; see DDEF_OPT_*.  Only between iterations. */
 #define DDEF_OPT_FORCE_FULL_SELECT 1 /* 1: never use the candidate filter                 */
 #define DDEF_OPT_CANDIDATE_SLACK_X16 2 /* candidate target = k * value / 16 (default 40)  */
+#define DDEF_OPT_PREFETCH_GRAD 3 /* 1: ddef_grad also starts the gradient of the NEXT iteration
+                                  * on a second stream (it only needs x_{t+1-tau}, tau >= 1), so
+                                  * that its arithmetic overlaps the memory-bound rest of the
+                                  * iteration; results are unchanged.  Costs a second gradient
+                                  * buffer of n*d floats.  Default 0: measured on MI355X the two
+                                  * kernels share the chip poorly (the whole step gains about
+                                  * 10 %, the streaming pass loses most of its bandwidth while
+                                  * they overlap).                                              */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 
 const char* ddef_strerror(int code);

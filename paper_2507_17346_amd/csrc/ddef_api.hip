@@ -58,6 +58,16 @@ struct ddef_ctx {
     uint64_t cap = 0;
     bool have_bound = false;
     int compressor = DDEF_COMPRESSOR_TOPK;
+    // gradient prefetch: the gradient of iteration t+1 only needs x_{t+1-tau}, which exists as soon
+    // as iteration t starts (tau >= 1), so it is generated on a second stream into a second buffer
+    // while the memory-bound rest of iteration t runs
+    int64_t opt_prefetch = 0;
+    float* g_next = nullptr;
+    hipStream_t side = nullptr;
+    hipEvent_t ev_applied = nullptr, ev_prefetched = nullptr;
+    bool pf_valid = false;
+    uint64_t pf_t = 0;
+    uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
     // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each)
     uint64_t u_dirty_k = 0;
@@ -114,27 +124,31 @@ hipEvent_t take_event(ddef_ctx* c) {
 
 struct LaunchScope {
     ddef_ctx* c;
+    hipStream_t stream;
     hipEvent_t stop = nullptr;
     int slot;
-    LaunchScope(ddef_ctx* ctx, int s) : c(ctx), slot(s) {
+    LaunchScope(ddef_ctx* ctx, hipStream_t st, int s) : c(ctx), stream(st), slot(s) {
         if (!c->profiling) return;
         hipEvent_t start = take_event(c);
         stop = take_event(c);
         if (!start || !stop) { stop = nullptr; return; }
-        (void)hipEventRecord(start, c->stream);
+        (void)hipEventRecord(start, stream);
         c->pending.push_back(ProfRecord{slot, start, stop});
     }
-    ~LaunchScope() { if (stop) (void)hipEventRecord(stop, c->stream); }
+    ~LaunchScope() { if (stop) (void)hipEventRecord(stop, stream); }
 };
 
-#define LAUNCH(ctx, slot, kernel, grid, block, ...)                                 \
-    do {                                                                            \
-        LaunchScope scope__((ctx), (slot));                                         \
-        hipLaunchKernelGGL(kernel, (grid), (block), 0, (ctx)->stream, __VA_ARGS__); \
+#define LAUNCH_ON(ctx, stream_, slot, kernel, grid, block, ...)                  \
+    do {                                                                         \
+        LaunchScope scope__((ctx), (stream_), (slot));                           \
+        hipLaunchKernelGGL(kernel, (grid), (block), 0, (stream_), __VA_ARGS__);  \
     } while (0)
+#define LAUNCH(ctx, slot, kernel, grid, block, ...) \
+    LAUNCH_ON(ctx, (ctx)->stream, slot, kernel, grid, block, __VA_ARGS__)
 
 int resolve_profile(ddef_ctx* c) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
     for (const ProfRecord& r : c->pending) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
@@ -232,6 +246,44 @@ void clean_update(ddef_ctx* c) {
         LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
     }
     c->u_dirty_k = 0;
+}
+
+void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t t, uint32_t tau, uint32_t blocks_per_cu) {
+    const uint64_t quads = (c->d + 3) / 4;
+    const uint32_t gx = blocks_for(c, (quads + 255) / 256, 1, blocks_per_cu);
+    LAUNCH_ON(c, stream, SL_GRAD, k_grad, dim3(gx), dim3(256), c->lambda, c->xstar, c->slot(t - tau), dest, c->ld,
+              (uint32_t)c->d, c->n, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)t, (uint32_t)(t >> 32),
+              c->noise_kind, c->noise_scale);
+}
+
+// Forget a prefetched gradient (its inputs are about to change); waits for the second stream so
+// that nothing of it is still reading them.
+int drop_prefetch(ddef_ctx* c) {
+    c->pf_valid = false;
+    if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
+    return DDEF_OK;
+}
+
+// After the gradient of iteration t is in place: start the one of iteration t+1 on the second
+// stream.  It reads snapshot x_{t+1-tau} (complete once iteration t-1 was applied, and a
+// different ring slot from the one iteration t writes, as 1 <= tau <= tau_max) and writes the
+// buffer the accumulate pass of iteration t-1 has finished reading.
+int start_prefetch(ddef_ctx* c) {
+    if (!c->opt_prefetch || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
+    if (!c->side) {
+        HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_applied, hipEventDisableTiming));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_prefetched, hipEventDisableTiming));
+        HIP_TRY(c, hipMalloc((void**)&c->g_next, (size_t)c->ld * 4u * c->n));
+        HIP_TRY(c, hipMemsetAsync(c->g_next, 0, (size_t)c->ld * 4u * c->n, c->side));
+    }
+    HIP_TRY(c, hipEventRecord(c->ev_applied, c->stream));        // everything up to here on the main stream
+    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_applied, 0));
+    // fewer resident blocks than the stand-alone launch: the two kernels share the CUs' wave slots
+    enqueue_grad(c, c->side, c->g_next, c->t + 1, c->tau, 16u);
+    HIP_TRY(c, hipEventRecord(c->ev_prefetched, c->side));
+    c->pf_valid = true; c->pf_t = c->t + 1; c->pf_tau = c->tau;
+    return DDEF_OK;
 }
 
 int check_ctx(ddef_ctx* c) {
@@ -337,10 +389,13 @@ int ddef_destroy(ddef_ctx* c) {
     if (!c) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     if (c->stream) (void)hipStreamSynchronize(c->stream);
+    if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+    if (c->ev_applied) (void)hipEventDestroy(c->ev_applied);
+    if (c->ev_prefetched) (void)hipEventDestroy(c->ev_prefetched);
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->bitmap, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->bitmap, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -354,6 +409,8 @@ int ddef_set_stream(ddef_ctx* c, void* hip_stream) {
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    rc = drop_prefetch(c);
+    if (rc) return rc;
     c->stream = hip_stream ? (hipStream_t)hip_stream : c->own_stream;
     return DDEF_OK;
 }
@@ -368,6 +425,8 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     if (!std::isfinite(noise_scale)) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    rc = drop_prefetch(c);
+    if (rc) return rc;
     const size_t bytes = (size_t)c->d * 4u;
     HIP_TRY(c, hipMemcpy(c->lambda, host_lambda, bytes, hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->xstar, host_xstar, bytes, hipMemcpyHostToDevice));
@@ -400,6 +459,7 @@ int ddef_set_tau(ddef_ctx* c, uint32_t tau) {
     if (rc) return rc;
     if (tau > c->tau_max) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    if (tau != c->tau) c->pf_valid = false;
     c->tau = tau;
     return DDEF_OK;
 }
@@ -411,12 +471,18 @@ int ddef_grad(ddef_ctx* c) {
     DeviceGuard guard(c->device);
     c->step_empty = c->t < c->tau;
     if (!c->step_empty) {
-        const uint64_t quads = (c->d + 3) / 4;
-        const uint32_t gx = blocks_for(c, (quads + 255) / 256, 1, 64);
-        LAUNCH(c, SL_GRAD, k_grad, dim3(gx), dim3(256), c->lambda, c->xstar, c->slot(c->t - c->tau), c->g,
-               c->ld, (uint32_t)c->d, c->n, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)c->t,
-               (uint32_t)(c->t >> 32), c->noise_kind, c->noise_scale);
+        if (c->pf_valid && c->pf_t == c->t && c->pf_tau == c->tau) {
+            HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_prefetched, 0));
+            float* ready = c->g_next;
+            c->g_next = c->g;
+            c->g = ready;
+            c->pf_valid = false;
+        } else {
+            enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+        }
         HIP_TRY(c, hipGetLastError());
+        rc = start_prefetch(c);
+        if (rc) return rc;
     }
     c->phase = PH_GRAD;
     return DDEF_OK;
@@ -548,6 +614,7 @@ int ddef_sync(ddef_ctx* c) {
     if (rc) return rc;
     DeviceGuard guard(c->device);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->side) HIP_TRY(c, hipStreamSynchronize(c->side));
     return check_device_flags(c);
 }
 
@@ -571,6 +638,8 @@ int ddef_set_model(ddef_ctx* c, const float* host_x) {
     if (!host_x) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
+    rc = drop_prefetch(c);                 // a prefetched gradient may have been taken at this snapshot
+    if (rc) return rc;
     return copy_row_in(c, c->slot(c->t), host_x);
 }
 
@@ -715,6 +784,10 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     switch (option) {
         case DDEF_OPT_FORCE_FULL_SELECT: c->opt_force_full = value != 0; return DDEF_OK;
+        case DDEF_OPT_PREFETCH_GRAD:
+            c->opt_prefetch = value != 0;
+            if (!c->opt_prefetch) return drop_prefetch(c);
+            return DDEF_OK;
         case DDEF_OPT_CANDIDATE_SLACK_X16:
             if (value < 16 || value > 1024) return DDEF_EINVAL;
             c->opt_slack_x16 = value;

@@ -368,3 +368,35 @@ def test_non_finite_values_are_reported(ddef):
     c.step(0.1, 0.05)
     assert c.raw("sync") == ddef.OK
     c.close()
+
+
+# ---- gradient prefetch on a second stream: same results ------------------------------------------
+@pytest.mark.parametrize("tau", [0, 1, 3])
+def test_prefetched_gradient_gives_identical_trajectories(ddef, oracle_mod, tau):
+    w = workloads.get("C3", d=300_000, n=4)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, 4)
+    g.set_option(ddef.OPT_PREFETCH_GRAD, 1)
+    o = oracle_mod.Oracle(w.d, w.n, 4, threads=4)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(tau)
+    rng = np.random.default_rng(8)
+    for t in range(14):
+        if t == 6:                                  # staleness changes: a prefetched gradient is stale
+            g.set_tau(min(tau + 1, 4)); o.set_tau(min(tau + 1, 4))
+        if t == 9:                                  # so it is after the model was overwritten
+            x = rng.standard_normal(w.d, dtype=F32)
+            g.set_model(x); o.set_model(x)
+        if t == 11:
+            g.set_option(ddef.OPT_PREFETCH_GRAD, 0)
+        g.grad(); o.grad()
+        if t == 4:                                  # test hook on top of a prefetched gradient
+            v = rng.standard_normal(w.d, dtype=F32)
+            g.load_grad(1, v); o.load_grad(1, v)
+        g.ef_compress(0.004, w.lr); o.ef_compress(0.004, w.lr)
+        assert_step_state_equal(g, o, w.n, check_grad=(t >= 4), what=("prefetch", tau, t))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert_model_equal(g, o, what=("prefetch", tau, t))
+    g.close()
