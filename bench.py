@@ -33,6 +33,7 @@ VALU_PER_DRAW = {2: 214.8}
 # algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
 ALGO_BYTES_PER_ELEM = {
     "k_ef_filter": 12.0,       # read e, read g, write p (the candidate filter rides along)
+    "k_ef_filter_fused": 8.0,  # read e, write p; the gradient is generated in registers
     "k_ef_randk": 12.0,        # same pass for Random-k (+ 1/8 byte of bitmap)
     "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
     "k_digit_hist": 4.0, "k_chunk_count": 4.0, "k_chunk_emit": 4.0,   # whole-row search passes
@@ -127,6 +128,8 @@ def main():
                     help="sparsifier: the paper's default Top-k, or its appendix's Random-k")
     ap.add_argument("--prefetch", type=int, default=0,
                     help="1: generate the next iteration's gradient on a second stream meanwhile")
+    ap.add_argument("--fuse-grad", type=int, default=0,
+                    help="1: generate the gradient inside the accumulate pass (never stored)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -154,6 +157,7 @@ def main():
     compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK}[args.compressor]
     ctx.set_compressor(compressor)
     ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
+    ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
 
     state = {"tau": None}
 
@@ -262,7 +266,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch),
+                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,

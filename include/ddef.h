@@ -201,6 +201,12 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                                   * kernels share the chip poorly (the whole step gains about
                                   * 10 %, the streaming pass loses most of its bandwidth while
                                   * they overlap).                                              */
+#define DDEF_OPT_FUSE_GRAD 4 /* 1: ddef_grad launches nothing; ddef_ef_compress generates the gradient
+                              * inside the accumulate pass, so it never touches HBM (8 bytes less per
+                              * worker and element).  Results are unchanged.  ddef_get_grad then works
+                              * only between ddef_grad and ddef_apply_delayed (it regenerates the
+                              * values); ddef_load_grad and Random-k fall back to a stored gradient.
+                              * Default 0: the pass becomes bound by the generator's arithmetic.      */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 
 const char* ddef_strerror(int code);

@@ -19,12 +19,12 @@ namespace {
 enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
-    SL_GRAD = 0, SL_EF_FILTER, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
+    SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
     SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
-    "k_grad", "k_ef_filter", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
+    "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
     "k_unscatter", "k_fill_f4", "k_scatter_add", "k_apply", "k_copy_f4"};
 
@@ -62,6 +62,10 @@ struct ddef_ctx {
     // as iteration t starts (tau >= 1), so it is generated on a second stream into a second buffer
     // while the memory-bound rest of iteration t runs
     int64_t opt_prefetch = 0;
+    // fused gradient: ddef_grad launches nothing, the accumulate pass generates the gradient in
+    // registers; grad_pending is true from ddef_grad until something needs g in memory
+    int64_t opt_fuse = 0;
+    bool grad_pending = false, grad_live = false, grad_stored = false;
     float* g_next = nullptr;
     hipStream_t side = nullptr;
     hipEvent_t ev_applied = nullptr, ev_prefetched = nullptr;
@@ -248,12 +252,25 @@ void clean_update(ddef_ctx* c) {
     c->u_dirty_k = 0;
 }
 
+GradSource grad_source(const ddef_ctx* c, uint64_t t, uint32_t tau) {
+    return GradSource{c->lambda, c->xstar, c->slot(t - tau), (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+                      (uint32_t)t, (uint32_t)(t >> 32), c->noise_kind, c->noise_scale};
+}
+
 void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t t, uint32_t tau, uint32_t blocks_per_cu) {
     const uint64_t quads = (c->d + 3) / 4;
     const uint32_t gx = blocks_for(c, (quads + 255) / 256, 1, blocks_per_cu);
-    LAUNCH_ON(c, stream, SL_GRAD, k_grad, dim3(gx), dim3(256), c->lambda, c->xstar, c->slot(t - tau), dest, c->ld,
-              (uint32_t)c->d, c->n, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)t, (uint32_t)(t >> 32),
-              c->noise_kind, c->noise_scale);
+    LAUNCH_ON(c, stream, SL_GRAD, k_grad, dim3(gx), dim3(256), grad_source(c, t, tau), dest, c->ld,
+              (uint32_t)c->d, c->n);
+}
+
+// Fused mode: write this iteration's gradient to memory after all (a getter, the test hook or a
+// kernel that reads g needs it).  Valid until the iteration is applied.
+void materialize_grad(ddef_ctx* c) {
+    if (!c->grad_pending) return;
+    if (!c->grad_stored) enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+    c->grad_stored = true;
+    c->grad_pending = false;
 }
 
 // Forget a prefetched gradient (its inputs are about to change); waits for the second stream so
@@ -269,7 +286,7 @@ int drop_prefetch(ddef_ctx* c) {
 // different ring slot from the one iteration t writes, as 1 <= tau <= tau_max) and writes the
 // buffer the accumulate pass of iteration t-1 has finished reading.
 int start_prefetch(ddef_ctx* c) {
-    if (!c->opt_prefetch || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
+    if (!c->opt_prefetch || c->opt_fuse || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
     if (!c->side) {
         HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
         HIP_TRY(c, hipEventCreateWithFlags(&c->ev_applied, hipEventDisableTiming));
@@ -470,7 +487,12 @@ int ddef_grad(ddef_ctx* c) {
     if (!c->problem_set || c->phase != PH_IDLE) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
     c->step_empty = c->t < c->tau;
-    if (!c->step_empty) {
+    c->grad_pending = false;
+    c->grad_stored = false;
+    c->grad_live = !c->step_empty;
+    if (!c->step_empty && c->opt_fuse) {
+        c->grad_pending = true;            // generated inside the accumulate pass
+    } else if (!c->step_empty) {
         if (c->pf_valid && c->pf_t == c->t && c->pf_tau == c->tau) {
             HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_prefetched, 0));
             float* ready = c->g_next;
@@ -494,9 +516,11 @@ int ddef_load_grad(ddef_ctx* c, uint32_t worker, const float* host_g) {
     if (!host_g || worker >= c->n) return DDEF_EINVAL;
     if (!c->problem_set || (c->phase != PH_IDLE && c->phase != PH_GRAD)) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
+    materialize_grad(c);
     rc = copy_row_in(c, c->g + (uint64_t)worker * c->ld, host_g);
     if (rc) return rc;
     c->step_empty = false;
+    c->grad_live = true;
     c->phase = PH_GRAD;
     return DDEF_OK;
 }
@@ -525,6 +549,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     uint32_t* cand_total = c->filt + 3 * n;
     if (c->compressor == DDEF_COMPRESSOR_RANDK) {
+        materialize_grad(c);
         const uint64_t bitmap_ld = c->ld / 32u;
         if (!c->bitmap) {
             HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
@@ -550,9 +575,16 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
-    LAUNCH(c, SL_EF_FILTER, k_ef_filter, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
-           (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc,
-           c->filt + 4 * n);
+    const GradSource src = grad_source(c, c->t, c->tau);
+    if (c->grad_pending) {
+        LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
+               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count,
+               overflow, c->tab, c->nwc, c->filt + 4 * n);
+    } else {
+        LAUNCH(c, SL_EF_FILTER, k_ef_filter<false>, dim3(c->nwc, n), dim3(64), c->e, (const float*)c->g, src, n,
+               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count,
+               overflow, c->tab, c->nwc, c->filt + 4 * n);
+    }
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
@@ -606,6 +638,7 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
     HIP_TRY(c, hipGetLastError());
     c->t += 1;
     c->phase = PH_IDLE;
+    if (c->opt_fuse) c->grad_live = false;
     return DDEF_OK;
 }
 
@@ -664,7 +697,13 @@ int ddef_get_grad(ddef_ctx* c, uint32_t worker, float* host_g) {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!host_g || worker >= c->n) return DDEF_EINVAL;
+    if (c->opt_fuse && !c->grad_live) return DDEF_ESTATE;   // fused: the gradient was never stored
     DeviceGuard guard(c->device);
+    if (c->opt_fuse && !c->grad_stored && c->phase != PH_IDLE) {
+        // generate it from the same inputs (the snapshot is intact until the iteration is applied)
+        enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+        c->grad_stored = true;
+    }
     return copy_row_out(c, c->g + (uint64_t)worker * c->ld, host_g);
 }
 
@@ -787,6 +826,10 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
         case DDEF_OPT_PREFETCH_GRAD:
             c->opt_prefetch = value != 0;
             if (!c->opt_prefetch) return drop_prefetch(c);
+            return DDEF_OK;
+        case DDEF_OPT_FUSE_GRAD:
+            c->opt_fuse = value != 0;
+            if (c->opt_fuse) return drop_prefetch(c);
             return DDEF_OK;
         case DDEF_OPT_CANDIDATE_SLACK_X16:
             if (value < 16 || value > 1024) return DDEF_EINVAL;

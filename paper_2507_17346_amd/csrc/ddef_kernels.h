@@ -39,11 +39,20 @@ struct SelViews {
     const uint32_t* cand_total;
 };
 
-__global__ void k_grad(const float* lambda, const float* xstar, const float* xs, float* g,
-                       uint64_t ld, uint32_t d, uint32_t n, uint32_t seed_lo, uint32_t seed_hi,
-                       uint32_t t_lo, uint32_t t_hi, int kind, float scale);
-__global__ void k_ef_filter(float* e, const float* g, uint64_t ld, uint32_t d, float lr,
-                            const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
+// Everything the synthetic gradient of one iteration is made from.
+struct GradSource {
+    const float* lambda;
+    const float* xstar;
+    const float* xs;             // snapshot x_{t-tau}
+    uint32_t seed_lo, seed_hi, t_lo, t_hi;
+    int kind;
+    float scale;
+};
+
+__global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);
+template <bool kFusedGrad>
+__global__ void k_ef_filter(float* e, const float* g, GradSource src, uint32_t n, uint64_t ld, uint32_t d,
+                            float lr, const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
                             uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups,
                             uint32_t* nonfinite);
 __global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);

@@ -169,34 +169,41 @@ __device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_
 
 // ------------------------------------------------------------------------------------
 // S0  g_i = lambda * (x_{t-tau} - x*) + scale * z      (Assumption 2; stale iterate)
-// One thread owns four consecutive coordinates and loops over the workers, so lambda,
-// x* and the snapshot are read once for all n workers.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_grad(const float* __restrict__ lambda,
-                                              const float* __restrict__ xstar,
-                                              const float* __restrict__ xs, float* __restrict__ g,
-                                              uint64_t ld, uint32_t d, uint32_t n, uint32_t seed_lo,
-                                              uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi,
-                                              int kind, float scale) {
+// deterministic part of four consecutive coordinates, shared by all workers
+__device__ __forceinline__ void grad_mean4(const GradSource& s, uint32_t j, float (&mean)[4]) {
+    const float4 lam = *reinterpret_cast<const float4*>(s.lambda + j);
+    const float4 xo = *reinterpret_cast<const float4*>(s.xstar + j);
+    const float4 xv = *reinterpret_cast<const float4*>(s.xs + j);
+    mean[0] = lam.x * (xv.x - xo.x);
+    mean[1] = lam.y * (xv.y - xo.y);
+    mean[2] = lam.z * (xv.z - xo.z);
+    mean[3] = lam.w * (xv.w - xo.w);
+}
+
+// worker's gradient at coordinates j..j+3 (zero past d, which keeps the row padding at zero)
+__device__ __forceinline__ void grad_quad(const GradSource& s, const float (&mean)[4], uint32_t worker,
+                                          uint32_t j, uint32_t d, float (&out)[4]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float xi = 0.0f;
+        if (s.kind != 0) xi = s.scale * draw_z(j + c, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi, s.kind);
+        out[c] = (j + c < d) ? mean[c] + xi : 0.0f;
+    }
+}
+
+// One thread owns four consecutive coordinates and loops over the workers, so lambda, x* and
+// the snapshot are read once for all n workers.
+__global__ __launch_bounds__(256) void k_grad(GradSource s, float* __restrict__ g, uint64_t ld, uint32_t d,
+                                              uint32_t n) {
     const uint32_t quads = (d + 3u) >> 2;
     for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
         const uint32_t j = q << 2;
-        const float4 lam = *reinterpret_cast<const float4*>(lambda + j);
-        const float4 xo = *reinterpret_cast<const float4*>(xstar + j);
-        const float4 xv = *reinterpret_cast<const float4*>(xs + j);
         float mean[4];
-        mean[0] = lam.x * (xv.x - xo.x);
-        mean[1] = lam.y * (xv.y - xo.y);
-        mean[2] = lam.z * (xv.z - xo.z);
-        mean[3] = lam.w * (xv.w - xo.w);
+        grad_mean4(s, j, mean);
         for (uint32_t i = 0; i < n; ++i) {
             float out[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                float xi = 0.0f;
-                if (kind != 0) xi = scale * draw_z(j + c, i, t_lo, t_hi, seed_lo, seed_hi, kind);
-                out[c] = (j + c < d) ? mean[c] + xi : 0.0f;      // keep the row padding at zero
-            }
+            grad_quad(s, mean, i, j, d, out);
             *reinterpret_cast<float4*>(g + (uint64_t)i * ld + j) = make_float4(out[0], out[1], out[2], out[3]);
         }
     }
@@ -215,9 +222,12 @@ __global__ __launch_bounds__(256) void k_grad(const float* __restrict__ lambda,
 // order although slots are handed out in arbitrary order.  To keep the atomics from
 // serialising on one address, a worker's candidate buffer is split into kSubs equal parts
 // with a counter each, and group number mod kSubs picks the part.
-// With use_filter == 0 this is the plain accumulate pass.
+// With use_filter == 0 this is the plain accumulate pass.  With kFusedGrad the gradient is not
+// read from g but generated in place (same arithmetic as k_grad), so it never touches HBM.
 // ------------------------------------------------------------------------------------
+template <bool kFusedGrad>
 __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
+                                                  GradSource src, uint32_t n,
                                                   uint64_t ld, uint32_t d, float lr,
                                                   const uint32_t* __restrict__ bound, int use_filter,
                                                   uint2* __restrict__ cand, uint64_t cap,
@@ -225,17 +235,29 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
                                                   uint32_t* __restrict__ overflow,
                                                   uint2* __restrict__ tab, uint32_t ngroups,
                                                   uint32_t* __restrict__ nonfinite) {
-    const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
+    // plain: grid (groups, n).  fused: 1-D grid with the worker index fastest, so that the blocks
+    // that need the same lambda / x* / snapshot lines run at about the same time
+    const uint32_t w = kFusedGrad ? blockIdx.x % n : blockIdx.y;
+    const uint32_t grp = kFusedGrad ? blockIdx.x / n : blockIdx.x;
+    const uint32_t lane = threadIdx.x;
     const uint32_t j = grp * 256u + lane * 4u;
     float pv[4] = {0.f, 0.f, 0.f, 0.f};
     if (j < d) {
         float* ep = e + (uint64_t)w * ld + j;
         const float4 ev = load_stream4(ep);
-        const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
-        pv[0] = ev.x + lr * gv.x;
-        pv[1] = ev.y + lr * gv.y;
-        pv[2] = ev.z + lr * gv.z;
-        pv[3] = ev.w + lr * gv.w;
+        float gq[4];
+        if (kFusedGrad) {
+            float mean[4];
+            grad_mean4(src, j, mean);
+            grad_quad(src, mean, w, j, d, gq);
+        } else {
+            const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
+            gq[0] = gv.x; gq[1] = gv.y; gq[2] = gv.z; gq[3] = gv.w;
+        }
+        pv[0] = ev.x + lr * gq[0];
+        pv[1] = ev.y + lr * gq[1];
+        pv[2] = ev.z + lr * gq[2];
+        pv[3] = ev.w + lr * gq[3];
         store_stream4(ep, pv);
     }
     if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
@@ -272,6 +294,13 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
     }
     if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
 }
+
+template __global__ void k_ef_filter<false>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
+                                            const uint32_t*, int, uint2*, uint64_t, uint32_t*, uint32_t*, uint2*,
+                                            uint32_t, uint32_t*);
+template __global__ void k_ef_filter<true>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
+                                           const uint32_t*, int, uint2*, uint64_t, uint32_t*, uint32_t*, uint2*,
+                                           uint32_t, uint32_t*);
 
 // ------------------------------------------------------------------------------------
 // Random-k sparsifier (the paper's appendix on other sparsifiers): worker w keeps the k

@@ -400,3 +400,37 @@ def test_prefetched_gradient_gives_identical_trajectories(ddef, oracle_mod, tau)
         g.apply_delayed(w.lr); o.apply_delayed()
         assert_model_equal(g, o, what=("prefetch", tau, t))
     g.close()
+
+
+# ---- gradient generated inside the accumulate pass: same results --------------------------------
+@pytest.mark.parametrize("name,d,n,tau,delta", [("C3", 200_001, 4, 2, 0.002), ("C1", 50_000, 3, 0, 0.01),
+                                                ("C2", 150_000, 8, 1, 0.01)])
+def test_fused_gradient_gives_identical_trajectories(ddef, oracle_mod, name, d, n, tau, delta):
+    w = workloads.get(name, d=d, n=n)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, max(tau, 1))
+    g.set_option(ddef.OPT_FUSE_GRAD, 1)
+    o = oracle_mod.Oracle(w.d, w.n, max(tau, 1), threads=4)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(tau)
+    rng = np.random.default_rng(9)
+    for t in range(tau + 9):
+        if t == tau + 5:                               # Random-k reads a stored gradient: falls back
+            g.set_compressor(1); o.set_compressor(1)
+        if t == tau + 6:
+            g.set_compressor(0); o.set_compressor(0)
+        g.grad(); o.grad()
+        if t == tau + 3:                               # the test hook needs the gradient in memory
+            v = rng.standard_normal(w.d, dtype=F32)
+            g.load_grad(0, v); o.load_grad(0, v)
+        g.ef_compress(delta, w.lr); o.ef_compress(delta, w.lr)
+        # in this mode the gradient can be fetched until the iteration is applied
+        assert_step_state_equal(g, o, w.n, check_grad=(t >= tau), what=("fused", name, t))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert_model_equal(g, o, what=("fused", name, t))
+    import ctypes as C
+    buf = np.empty(w.d, dtype=F32)
+    assert g.raw("get_grad", 0, buf.ctypes.data_as(C.POINTER(C.c_float))) == ddef.ESTATE
+    g.close()
