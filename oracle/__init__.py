@@ -76,6 +76,9 @@ def lib():
         "oracle_randk_permute": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]),
         "oracle_murmur_fmix32": (C.c_uint32, [C.c_uint32]),
         "oracle_set_compressor": (None, [vp, C.c_int]),
+        "oracle_set_heterogeneity": (None, [vp, C.c_float]),
+        "oracle_phi_prime": (C.c_double, [C.c_double, C.c_double]),
+        "oracle_deco_noniid": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
         "oracle_phi": (C.c_double, [C.c_double, C.c_double]),
         "oracle_delta_star": (C.c_double, [C.c_double] * 5),
         "oracle_deco": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
@@ -176,6 +179,21 @@ def phi(delta, tau):
     return float(lib().oracle_phi(float(delta), float(tau)))
 
 
+def phi_prime(delta, tau):
+    return float(lib().oracle_phi_prime(float(delta), float(tau)))
+
+
+def deco_noniid(v_g, a, b, t_comp):
+    tau, delta = C.c_uint32(), C.c_double()
+    rc = lib().oracle_deco_noniid(float(v_g), float(a), float(b), float(t_comp), C.byref(tau), C.byref(delta))
+    if rc != 0:
+        return None
+    return int(tau.value), float(delta.value)
+
+
+HETEROGENEITY_KEY = 0xFFFFFFFFFFFFFFFE     # the step key the per-worker optimum shifts are drawn under
+
+
 def delta_star(tau, v_g, a, b, t_comp):
     return float(lib().oracle_delta_star(float(tau), float(v_g), float(a), float(b), float(t_comp)))
 
@@ -247,6 +265,10 @@ class Oracle:
 
     def set_tau(self, tau):
         lib().oracle_set_tau(self._h, int(tau))
+
+    def set_heterogeneity(self, zeta):
+        """Non-IID workers: worker i's optimum is x* + zeta * u_i, u_i a fixed standard normal vector."""
+        lib().oracle_set_heterogeneity(self._h, float(zeta))
 
     def set_compressor(self, kind):
         """0: Top-k (default), 1: Random-k."""

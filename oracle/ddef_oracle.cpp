@@ -244,6 +244,7 @@ struct Oracle {
     float noise_scale = 0.0f;
     int threads = 1;
     int compressor = 0;                 // 0: Top-k, 1: Random-k
+    float zeta = 0.0f;                  // non-IID: worker i's optimum is x* + zeta * u_i
     bool step_is_noop = false;
     std::vector<float> lambda, xstar, U;
     std::vector<std::vector<float>> ring, e, g;
@@ -268,11 +269,17 @@ void for_each_worker(Oracle* o, F fn) {
     for (auto& th : pool) th.join();
 }
 
+constexpr uint64_t kHeterogeneityKey = 0xfffffffffffffffeull;
+
 void grad_worker(Oracle* o, uint32_t i) {
     const std::vector<float>& xs = o->slot(o->t - o->tau);
     std::vector<float>& g = o->g[i];
     for (uint64_t j = 0; j < o->d; ++j) {
-        float diff = xs[j] - o->xstar[j];
+        // heterogeneous local objectives (Assumption 3): f_i has its own optimum, shifted from x*
+        // by zeta times a fixed standard normal vector u_i (drawn under a step key no iteration uses)
+        float optimum = o->xstar[j];
+        if (o->zeta != 0.0f) optimum = o->xstar[j] + o->zeta * noise_z(o->seed, kHeterogeneityKey, i, (uint32_t)j, 1);
+        float diff = xs[j] - optimum;
         float mean = o->lambda[j] * diff;
         float xi = o->noise_scale * noise_z(o->seed, o->t, i, (uint32_t)j, o->noise_kind);
         g[j] = mean + xi;
@@ -338,6 +345,7 @@ uint64_t oracle_randk_permute(uint64_t seed, uint64_t t, uint32_t worker, uint64
 }
 uint32_t oracle_murmur_fmix32(uint32_t h) { return murmur_fmix32(h); }
 void oracle_set_compressor(void* h, int kind) { ((Oracle*)h)->compressor = kind; }
+void oracle_set_heterogeneity(void* h, float zeta) { ((Oracle*)h)->zeta = zeta; }
 
 void* oracle_create(uint64_t d, uint32_t n, uint32_t tau_max) {
     Oracle* o = new Oracle;
@@ -507,6 +515,11 @@ void oracle_queue_run(uint64_t d, uint32_t n, uint32_t tau, uint64_t T, double d
 // ---- DeCo (Algorithm 3) and the timing model (Section 4, Theorem 3) ----------------
 double oracle_phi(double delta, double tau) { return phi_value(delta, tau); }
 
+// Key factor of the non-IID analysis (Remark on phi): phi' = (1-delta) / (delta^2 (1-delta/2)^tau).
+double oracle_phi_prime(double delta, double tau) {
+    return (1.0 - delta) / (delta * delta * std::pow(1.0 - 0.5 * delta, tau));
+}
+
 // delta*(tau) of the Remark following Theorem 3.
 double oracle_delta_star(double tau, double v_g, double a, double b, double t_comp) {
     double first = std::max(0.0, (tau * t_comp - b) * a / v_g);
@@ -526,6 +539,21 @@ int oracle_deco(double v_g, double a, double b, double t_comp, uint32_t* tau_out
         if (!(delta > 0.0)) continue;
         double phi = phi_value(delta, (double)tau);
         if (phi <= best) { best = phi; *tau_out = (uint32_t)tau; *delta_out = delta; found = 0; }
+    }
+    return found;
+}
+
+// The same scan with phi' as the objective (Section 5.6: "In non-IID scenarios, we replace phi").
+int oracle_deco_noniid(double v_g, double a, double b, double t_comp, uint32_t* tau_out, double* delta_out) {
+    long hi = (long)std::ceil((b + v_g / a) / t_comp);
+    long lo = (long)std::ceil(b / t_comp);
+    double best = std::numeric_limits<double>::infinity();
+    int found = -1;
+    for (long tau = hi; tau >= lo; --tau) {
+        double delta = std::min(std::min((tau * t_comp - b) * a / v_g, t_comp * a / v_g), 1.0);
+        if (!(delta > 0.0)) continue;
+        double obj = oracle_phi_prime(delta, (double)tau);
+        if (obj <= best) { best = obj; *tau_out = (uint32_t)tau; *delta_out = delta; found = 0; }
     }
     return found;
 }
