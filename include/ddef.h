@@ -86,6 +86,12 @@ int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_
  * ddef_get_threshold reports (0, 0).  Only between iterations. */
 int ddef_set_compressor(ddef_ctx* ctx, int kind);
 
+/* Heterogeneous local objectives (Assumption 3; the paper's non-IID experiments): worker i's
+ * quadratic has the optimum xstar + zeta * u_i instead of xstar, u_i a standard normal vector
+ * fixed by (seed, i) -- the same counter-based draw as the gradient noise, under the step key
+ * 2^64 - 2 that no iteration reaches.  zeta = 0 (default) is the IID case.  Between iterations. */
+int ddef_set_heterogeneity(ddef_ctx* ctx, float zeta);
+
 /* Staleness for the following iterations, 0..tau_max (Algorithm 2 re-chooses it every E
  * iterations).  Only between iterations, else ESTATE. */
 int ddef_set_tau(ddef_ctx* ctx, uint32_t tau);
@@ -145,6 +151,11 @@ uint64_t ddef_k_from_delta(double delta, uint64_t d);
  * t_comp_s > 0, b_s >= 0.  EINVAL when no candidate exists. */
 int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
               double* delta);
+/* The same scan minimising phi' = phi / delta, the key factor when data is non-IID (Remark on
+ * phi; Section 5.6 replaces phi by it). */
+int ddef_deco_noniid(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
+                     double* delta);
+double ddef_phi_prime(double delta, double tau);
 /* DeCo's objective phi(delta, tau) = (1 - delta) / (delta (1 - delta/2)^tau) (Theorems 1 and 2,
  * Algorithm 3); NaN outside 0 < delta <= 1, tau >= 0. */
 double ddef_phi(double delta, double tau);

@@ -28,6 +28,9 @@ SIGNATURES = {
     "ddef_set_problem": (C.c_int, [_ctx, _f32p, _f32p, _f32p, C.c_uint64, C.c_int, C.c_float]),
     "ddef_set_tau": (C.c_int, [_ctx, C.c_uint32]),
     "ddef_set_compressor": (C.c_int, [_ctx, C.c_int]),
+    "ddef_set_heterogeneity": (C.c_int, [_ctx, C.c_float]),
+    "ddef_deco_noniid": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
+    "ddef_phi_prime": (C.c_double, [C.c_double, C.c_double]),
     "ddef_grad": (C.c_int, [_ctx]),
     "ddef_load_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
@@ -109,6 +112,21 @@ def deco(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> Optional
     if rc != OK:
         raise DdefError(rc, "ddef_deco")
     return int(tau.value), float(delta.value)
+
+
+def deco_noniid(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> Optional[Tuple[int, float]]:
+    tau, delta = C.c_uint32(), C.c_double()
+    rc = load().ddef_deco_noniid(float(v_g_bits), float(a_bps), float(b_s), float(t_comp_s),
+                                 C.byref(tau), C.byref(delta))
+    if rc == EINVAL:
+        return None
+    if rc != OK:
+        raise DdefError(rc, "ddef_deco_noniid")
+    return int(tau.value), float(delta.value)
+
+
+def phi_prime(delta: float, tau: float) -> float:
+    return float(load().ddef_phi_prime(float(delta), float(tau)))
 
 
 def phi(delta: float, tau: float) -> float:
@@ -215,6 +233,9 @@ class Context:
 
     def set_tau(self, tau: int):
         self._check(self._lib.ddef_set_tau(self._h, int(tau)), "ddef_set_tau")
+
+    def set_heterogeneity(self, zeta: float):
+        self._check(self._lib.ddef_set_heterogeneity(self._h, float(zeta)), "ddef_set_heterogeneity")
 
     def set_compressor(self, kind: int):
         self._check(self._lib.ddef_set_compressor(self._h, int(kind)), "ddef_set_compressor")

@@ -82,6 +82,7 @@ struct ddef_ctx {
     uint64_t seed = 0;
     int noise_kind = 0;
     float noise_scale = 0.0f;
+    float zeta = 0.0f;
     int sticky = DDEF_OK;
     uint64_t full_selects = 0;
     int64_t opt_force_full = 0, opt_slack_x16 = 40;
@@ -254,7 +255,7 @@ void clean_update(ddef_ctx* c) {
 
 GradSource grad_source(const ddef_ctx* c, uint64_t t, uint32_t tau) {
     return GradSource{c->lambda, c->xstar, c->slot(t - tau), (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-                      (uint32_t)t, (uint32_t)(t >> 32), c->noise_kind, c->noise_scale};
+                      (uint32_t)t, (uint32_t)(t >> 32), c->noise_kind, c->noise_scale, c->zeta};
 }
 
 void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t t, uint32_t tau, uint32_t blocks_per_cu) {
@@ -468,6 +469,18 @@ int ddef_set_compressor(ddef_ctx* c, int kind) {
     if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     c->compressor = kind;
+    return DDEF_OK;
+}
+
+int ddef_set_heterogeneity(ddef_ctx* c, float zeta) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!std::isfinite(zeta)) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    rc = drop_prefetch(c);
+    if (rc) return rc;
+    c->zeta = zeta;
     return DDEF_OK;
 }
 

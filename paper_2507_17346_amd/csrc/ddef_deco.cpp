@@ -38,7 +38,13 @@ double ddef_phi(double delta, double tau) {
     return (1.0 - delta) / (delta * std::pow(1.0 - delta / 2.0, tau));
 }
 
-int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau, double* delta) {
+double ddef_phi_prime(double delta, double tau) {
+    const double phi = ddef_phi(delta, tau);
+    return phi / delta;                                   // NaN stays NaN outside the domain
+}
+
+static int deco_scan(bool non_iid, double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
+                     double* delta) {
     if (!tau || !delta) return DDEF_EINVAL;
     if (!positive_finite(v_g_bits) || !positive_finite(a_bps) || !positive_finite(t_comp_s)) return DDEF_EINVAL;
     if (!std::isfinite(b_s) || b_s < 0.0) return DDEF_EINVAL;
@@ -51,10 +57,18 @@ int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32
     for (double cand = first; cand >= last; cand -= 1.0) {
         const double ratio = hidden_ratio(cand, sent_per_second, b_s, t_comp_s);
         if (!(ratio > 0.0)) continue;                     // nothing can be sent in time: no phi
-        const double phi = ddef_phi(ratio, cand);
+        const double phi = non_iid ? ddef_phi_prime(ratio, cand) : ddef_phi(ratio, cand);
         if (phi <= phi_min) { phi_min = phi; *tau = (uint32_t)cand; *delta = ratio; have = true; }
     }
     return have ? DDEF_OK : DDEF_EINVAL;
+}
+
+int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau, double* delta) {
+    return deco_scan(false, v_g_bits, a_bps, b_s, t_comp_s, tau, delta);
+}
+
+int ddef_deco_noniid(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau, double* delta) {
+    return deco_scan(true, v_g_bits, a_bps, b_s, t_comp_s, tau, delta);
 }
 
 double ddef_t_avg_model(uint32_t tau, double delta, double v_g_bits, double a_bps, double b_s, double t_comp_s) {

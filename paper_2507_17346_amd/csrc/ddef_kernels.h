@@ -47,6 +47,7 @@ struct GradSource {
     uint32_t seed_lo, seed_hi, t_lo, t_hi;
     int kind;
     float scale;
+    float zeta;                  // 0: all workers share the optimum xstar
 };
 
 __global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);

@@ -70,3 +70,19 @@ def test_lut_matches_oracle_and_section_4_5(oracle_mod):
     assert lib.ddef_lut_build(V_G, 2e8, 1e8, 20, b, t_comp, C.byref(h)) == binding.EINVAL
     assert lib.ddef_lut_build(V_G, 1e8, 2e8, 1, b, t_comp, C.byref(h)) == binding.EINVAL
     assert lib.ddef_lut_destroy(None) == binding.EINVAL
+
+
+def test_non_iid_objective_matches_oracle(oracle_mod):
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        v_g = 32 * 10 ** rng.uniform(6, 9)
+        a = 10 ** rng.uniform(8, 10)
+        b = rng.uniform(0.01, 0.3)
+        t_comp = 10 ** rng.uniform(-2, 0)
+        got, want = binding.deco_noniid(v_g, a, b, t_comp), oracle_mod.deco_noniid(v_g, a, b, t_comp)
+        assert (got is None) == (want is None)
+        if got:
+            assert got[0] == want[0] and got[1] == pytest.approx(want[1], rel=1e-12)
+        delta, tau = float(10 ** rng.uniform(-4, 0)), int(rng.integers(0, 17))
+        assert binding.phi_prime(delta, tau) == pytest.approx(oracle_mod.phi_prime(delta, tau), rel=1e-13)
+    assert binding.phi_prime(1.0, 3) == 0.0 and math.isnan(binding.phi_prime(0.0, 3))

@@ -434,3 +434,27 @@ def test_fused_gradient_gives_identical_trajectories(ddef, oracle_mod, name, d, 
     buf = np.empty(w.d, dtype=F32)
     assert g.raw("get_grad", 0, buf.ctypes.data_as(C.POINTER(C.c_float))) == ddef.ESTATE
     g.close()
+
+
+# ---- non-IID workers: per-worker optima --------------------------------------------------------
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_heterogeneous_objectives(ddef, oracle_mod, fuse):
+    w = workloads.get("C1", d=120_001, n=4)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, 2)
+    g.set_option(ddef.OPT_FUSE_GRAD, fuse)
+    o = oracle_mod.Oracle(w.d, w.n, 2, threads=4)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(1)
+        h.set_heterogeneity(0.4)
+    for t in range(8):
+        if t == 5:
+            g.set_heterogeneity(0.0); o.set_heterogeneity(0.0)
+        g.grad(); o.grad()
+        g.ef_compress(0.01, w.lr); o.ef_compress(0.01, w.lr)
+        assert_step_state_equal(g, o, w.n, check_grad=(t >= 1), what=("non-iid", fuse, t))
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert_model_equal(g, o, what=("non-iid", fuse, t))
+    g.close()
