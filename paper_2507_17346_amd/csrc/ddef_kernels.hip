@@ -711,7 +711,9 @@ __global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState
 // the old bound.  The error buffers drift (they ramp up while the model is far from its
 // optimum and relax later), so the bound is then moved by the factor the threshold is
 // expected to move by: linear extrapolation of the last two thresholds,
-// T_next / T = 2 - T_prev / T.  The bound only decides which search runs; the selection
+// T_next / T = 2 - T_prev / T.  Too high a bound (fewer than k caught) and too low a bound
+// (buffer overflow) both cost a whole-row search, and the target kb = 2.5 k sits in the
+// middle of the usable window [k, 7.5 k], so the trend is followed in full.  The bound only decides which search runs; the selection
 // itself is exact either way.
 __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k, uint32_t kb,
                                            uint32_t* bound, const uint32_t* cand_total,
@@ -733,11 +735,9 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
     }
     if (sel[w].k_prev == k && sel[w].T_prev != 0u && T != 0u && T < 0x7f800000u && nb != 0u) {
         float ratio = 2.0f - __uint_as_float(sel[w].T_prev) / __uint_as_float(T);
-        // a jump is not a trend: leave the bound where the last selection put it
-        if (ratio < 0.75f || ratio > 1.34f) ratio = 1.0f;
-        // a bound that is too high costs a whole-row search, one that is too low only a few
-        // more candidates: follow a rising threshold half way, a falling one fully
-        if (ratio > 1.0f) ratio = 1.0f + 0.5f * (ratio - 1.0f);
+        // a jump is not a trend: leave the bound where the last selection put it.  (A linear
+        // ramp from the second to the third selection has ratio 1.5 and is still followed.)
+        if (ratio < 0.75f || ratio > 1.5f) ratio = 1.0f;
         const float moved = __uint_as_float(nb) * ratio;
         if (moved > 0.0f && moved < 3.0e38f) nb = __float_as_uint(moved);
     }

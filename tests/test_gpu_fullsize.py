@@ -134,3 +134,50 @@ def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
     # both searches ran at this size: the whole-row one at first and after delta jumped
     assert 0 < g.full_select_count() < 5 * w.n
     g.close()
+
+
+def test_coordinates_beyond_2_to_31(ddef, oracle_mod):
+    """One worker with d = 3e9 + 11: indices above 2^31, ragged last quad.  Properties of the
+    selection plus gradients / error-feedback values on sampled coordinates (the oracle's noise is
+    evaluated one coordinate at a time)."""
+    d, n, delta, lr, seed = 3_000_000_011, 1, 1e-4, 0.05, 77
+    rng = np.random.default_rng(5)
+    lam = np.empty(d, dtype=F32); xstar = np.empty(d, dtype=F32); x0 = np.empty(d, dtype=F32)
+    step = 1 << 26
+    for lo in range(0, d, step):
+        hi = min(d, lo + step)
+        lam[lo:hi] = (10.0 ** rng.uniform(-3, 0, hi - lo)).astype(F32)
+        xstar[lo:hi] = rng.standard_normal(hi - lo, dtype=F32)
+        x0[lo:hi] = rng.standard_normal(hi - lo, dtype=F32)
+    c = ddef.Context(d, n, 0)
+    c.set_problem(lam, xstar, x0, seed, 1, 0.05)
+    c.set_tau(0)
+    k = ddef.k_from_delta(delta, d)
+    sample = np.unique(np.concatenate([rng.integers(0, d, 3000), [0, d - 1, 2 ** 31 - 1, 2 ** 31, 2 ** 31 + 1]]))
+    e_prev = np.zeros(len(sample), dtype=F32)
+    x_cur = x0
+    for t in range(5):
+        c.grad()
+        c.ef_compress(delta, lr)
+        idx, val = c.get_message(0)
+        T, r = c.get_threshold(0)
+        assert len(idx) == k and np.all(np.diff(idx.astype(np.int64)) > 0) and int(idx[-1]) < d
+        assert int((idx >= 2 ** 31).sum()) > k // 4
+        vkeys = bits(val) & np.uint32(0x7FFFFFFF)
+        assert int(vkeys.min()) == T and int((vkeys == T).sum()) == r
+        e_new = c.get_error(0)
+        assert int((bits(e_new) & np.uint32(0x7FFFFFFF)).max()) <= T and np.all(bits(e_new[idx]) == 0)
+        gs = c.get_grad(0)[sample]
+        z = np.array([oracle_mod.noise_z(seed, t, 0, int(j), 1) for j in sample], dtype=F32)
+        assert np.array_equal(bits(gs), bits(lam[sample] * (x_cur[sample] - xstar[sample]) + F32(0.05) * z))
+        p = e_prev + F32(lr) * gs
+        sent = np.isin(sample, idx)
+        assert np.array_equal(bits(val[np.searchsorted(idx, sample[sent])]), bits(p[sent]))
+        assert np.array_equal(bits(e_new[sample][~sent]), bits(p[~sent]))
+        e_prev = e_new[sample]
+        del e_new
+        c.aggregate()
+        c.apply_delayed(lr)
+        x_cur = c.get_model()
+    assert c.full_select_count() < 5          # the candidate filter carried the later selections
+    c.close()
