@@ -79,6 +79,15 @@ def lib():
         "oracle_set_heterogeneity": (None, [vp, C.c_float]),
         "oracle_phi_prime": (C.c_double, [C.c_double, C.c_double]),
         "oracle_deco_noniid": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
+        "oracle_queue_create": (vp, [C.c_uint64, C.c_uint32, C.c_uint32]),
+        "oracle_queue_destroy": (None, [vp]),
+        "oracle_queue_set_problem": (None, [vp, f32p, f32p, f32p, C.c_uint64, C.c_int, C.c_float]),
+        "oracle_queue_step": (None, [vp, C.c_double, C.c_float]),
+        "oracle_queue_get_model": (None, [vp, f32p]),
+        "oracle_queue_get_update": (None, [vp, f32p]),
+        "oracle_queue_get_error": (None, [vp, C.c_uint32, f32p]),
+        "oracle_queue_message_size": (C.c_uint64, [vp, C.c_uint32]),
+        "oracle_queue_get_message": (None, [vp, C.c_uint32, u32p, f32p]),
         "oracle_phi": (C.c_double, [C.c_double, C.c_double]),
         "oracle_delta_star": (C.c_double, [C.c_double] * 5),
         "oracle_deco": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
@@ -337,3 +346,54 @@ class Oracle:
         T, r = C.c_uint32(), C.c_uint64()
         lib().oracle_get_threshold(self._h, int(w), C.byref(T), C.byref(r))
         return int(T.value), int(r.value)
+
+
+class QueueOracle:
+    """Algorithm 1 as printed, one iteration at a time: workers at the current x, the server
+    applying the message sent tau iterations earlier (constant tau)."""
+
+    def __init__(self, d: int, n: int, tau: int):
+        self.d, self.n, self.tau = int(d), int(n), int(tau)
+        self._h = C.c_void_p(lib().oracle_queue_create(self.d, self.n, self.tau))
+
+    def close(self):
+        if self._h:
+            lib().oracle_queue_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_problem(self, lam, xstar, x0, seed, noise_kind, noise_scale):
+        _, lp = _f32(lam)
+        _, sp = _f32(xstar)
+        _, xp = _f32(x0)
+        lib().oracle_queue_set_problem(self._h, lp, sp, xp, int(seed), int(noise_kind), float(noise_scale))
+
+    def step(self, delta, lr):
+        lib().oracle_queue_step(self._h, float(delta), float(lr))
+
+    def _vec(self, fn, *args):
+        out = np.empty(self.d, dtype=np.float32)
+        fn(self._h, *args, out.ctypes.data_as(C.POINTER(C.c_float)))
+        return out
+
+    def get_model(self):
+        return self._vec(lib().oracle_queue_get_model)
+
+    def get_update(self):
+        return self._vec(lib().oracle_queue_get_update)
+
+    def get_error(self, w):
+        return self._vec(lib().oracle_queue_get_error, int(w))
+
+    def get_message(self, w):
+        k = int(lib().oracle_queue_message_size(self._h, int(w)))
+        idx = np.empty(k, dtype=np.uint32)
+        val = np.empty(k, dtype=np.float32)
+        lib().oracle_queue_get_message(self._h, int(w), idx.ctypes.data_as(C.POINTER(C.c_uint32)),
+                                       val.ctypes.data_as(C.POINTER(C.c_float)))
+        return idx, val

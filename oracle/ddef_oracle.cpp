@@ -512,6 +512,88 @@ void oracle_queue_run(uint64_t d, uint32_t n, uint32_t tau, uint64_t T, double d
     if (x_final) std::copy(x.begin(), x.end(), x_final);
 }
 
+// The same literal form, one iteration at a time, so that its error buffers and messages can be
+// inspected: state = x_u, e_i (already advanced to time u), and the messages sent so far.
+struct QueueOracle {
+    uint64_t d = 0, u = 0, seed = 0;
+    uint32_t n = 0, tau = 0;
+    int noise_kind = 0;
+    float noise_scale = 0.0f;
+    std::vector<float> lambda, xstar, x, U;
+    std::vector<std::vector<float>> e;
+    std::vector<std::vector<std::vector<uint32_t>>> sent_idx;   // [iteration][worker]
+    std::vector<std::vector<std::vector<float>>> sent_val;
+};
+
+void* oracle_queue_create(uint64_t d, uint32_t n, uint32_t tau) {
+    QueueOracle* q = new QueueOracle;
+    q->d = d; q->n = n; q->tau = tau;
+    q->lambda.assign(d, 0.0f); q->xstar.assign(d, 0.0f); q->x.assign(d, 0.0f); q->U.assign(d, 0.0f);
+    q->e.assign(n, std::vector<float>(d, 0.0f));
+    return q;
+}
+void oracle_queue_destroy(void* h) { delete (QueueOracle*)h; }
+void oracle_queue_set_problem(void* h, const float* lambda, const float* xstar, const float* x0, uint64_t seed,
+                              int noise_kind, float noise_scale) {
+    QueueOracle* q = (QueueOracle*)h;
+    std::copy(lambda, lambda + q->d, q->lambda.begin());
+    std::copy(xstar, xstar + q->d, q->xstar.begin());
+    std::copy(x0, x0 + q->d, q->x.begin());
+    for (auto& e : q->e) std::fill(e.begin(), e.end(), 0.0f);
+    q->sent_idx.clear(); q->sent_val.clear();
+    q->seed = seed; q->noise_kind = noise_kind; q->noise_scale = noise_scale; q->u = 0;
+}
+void oracle_queue_step(void* h, double delta, float lr) {
+    QueueOracle* q = (QueueOracle*)h;
+    const uint64_t d = q->d, k = k_from_delta(delta, d), u = q->u;
+    q->sent_idx.emplace_back(q->n); q->sent_val.emplace_back(q->n);
+    std::vector<float> p(d), dense(d);
+    for (uint32_t i = 0; i < q->n; ++i) {                          // worker side, at the current x_u
+        for (uint64_t j = 0; j < d; ++j) {
+            float diff = q->x[j] - q->xstar[j];
+            float mean = q->lambda[j] * diff;
+            float xi = q->noise_scale * noise_z(q->seed, u + q->tau, i, (uint32_t)j, q->noise_kind);
+            float g = mean + xi;
+            float scaled = lr * g;
+            p[j] = q->e[i][j] + scaled;
+        }
+        std::vector<uint32_t>& idx = q->sent_idx[u][i];
+        std::vector<float>& val = q->sent_val[u][i];
+        idx.assign(k, 0u); val.assign(k, 0.0f);
+        topk_select(p.data(), d, k, idx.data(), nullptr, nullptr);
+        std::fill(dense.begin(), dense.end(), 0.0f);
+        for (uint64_t m = 0; m < k; ++m) { val[m] = p[idx[m]]; dense[idx[m]] = p[idx[m]]; }
+        for (uint64_t j = 0; j < d; ++j) q->e[i][j] = p[j] - dense[j];
+    }
+    std::fill(q->U.begin(), q->U.end(), 0.0f);                      // server side: the message of u - tau
+    if (u >= q->tau)
+        for (uint32_t i = 0; i < q->n; ++i) {
+            const std::vector<uint32_t>& idx = q->sent_idx[u - q->tau][i];
+            const std::vector<float>& val = q->sent_val[u - q->tau][i];
+            for (size_t m = 0; m < idx.size(); ++m) q->U[idx[m]] = q->U[idx[m]] + val[m];
+        }
+    float nf = (float)q->n;
+    for (uint64_t j = 0; j < d; ++j) { float avg = q->U[j] / nf; q->x[j] = q->x[j] - avg; }
+    q->u += 1;
+}
+void oracle_queue_get_model(void* h, float* x) { QueueOracle* q = (QueueOracle*)h; std::copy(q->x.begin(), q->x.end(), x); }
+void oracle_queue_get_update(void* h, float* U) { QueueOracle* q = (QueueOracle*)h; std::copy(q->U.begin(), q->U.end(), U); }
+void oracle_queue_get_error(void* h, uint32_t w, float* e) {
+    QueueOracle* q = (QueueOracle*)h;
+    std::copy(q->e[w].begin(), q->e[w].end(), e);
+}
+uint64_t oracle_queue_message_size(void* h, uint32_t w) {
+    QueueOracle* q = (QueueOracle*)h;
+    return q->u == 0 ? 0 : q->sent_idx[q->u - 1][w].size();
+}
+// the message worker w sent in the last iteration
+void oracle_queue_get_message(void* h, uint32_t w, uint32_t* idx, float* val) {
+    QueueOracle* q = (QueueOracle*)h;
+    if (q->u == 0) return;
+    std::copy(q->sent_idx[q->u - 1][w].begin(), q->sent_idx[q->u - 1][w].end(), idx);
+    std::copy(q->sent_val[q->u - 1][w].begin(), q->sent_val[q->u - 1][w].end(), val);
+}
+
 // ---- DeCo (Algorithm 3) and the timing model (Section 4, Theorem 3) ----------------
 double oracle_phi(double delta, double tau) { return phi_value(delta, tau); }
 

@@ -248,3 +248,35 @@ def test_aggregate_sums_in_worker_order(oracle_mod):
     assert U[0] == F32(1.0) and U[1] == F32(0.5) and U[3] == 0.0
     o.apply_delayed()
     assert np.array_equal(o.get_model(), -U / F32(3))
+
+
+# --- the literal form one iteration at a time: same x as the batch run and as the ring form ---------
+@pytest.mark.parametrize("tau,delta", [(0, 0.05), (2, 0.03), (4, 0.2)])
+def test_stepwise_queue_form(oracle_mod, tau, delta):
+    w, lam, xstar, x0 = small_problem(seed=40 + tau, d=900, n=3)
+    lr, T = 0.05, 12
+    q = oracle_mod.QueueOracle(w.d, w.n, tau)
+    q.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    ring = make_oracle(oracle_mod, w, lam, xstar, x0, tau)
+    _, traj = oracle_mod.queue_run(lam, xstar, x0, w.n, tau, T, delta, lr, w.seed, w.noise_kind,
+                                   w.noise_scale, trajectory=True)
+    for t in range(T):
+        q.step(delta, lr)
+        ring.step(delta, lr)
+        assert np.array_equal(bits(q.get_model()), bits(traj[t + 1]))
+        assert np.array_equal(bits(q.get_model()), bits(ring.get_model()))
+    # the message the queue form sends at time t is the one the ring form computes at t + tau, and
+    # the queue form's error buffers run tau iterations ahead of the ring form's
+    q2 = oracle_mod.QueueOracle(w.d, w.n, tau)
+    q2.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    ring2 = make_oracle(oracle_mod, w, lam, xstar, x0, tau)
+    for t in range(tau):
+        ring2.step(delta, lr)                      # the ring form's empty start-up iterations
+    for t in range(T - tau):
+        q2.step(delta, lr)
+        ring2.step(delta, lr)
+        for i in range(w.n):
+            qi, qv = q2.get_message(i)
+            ri, rv = ring2.get_message(i)
+            assert np.array_equal(qi, ri) and np.array_equal(bits(qv), bits(rv))
+            assert np.array_equal(bits(q2.get_error(i)), bits(ring2.get_error(i)))
