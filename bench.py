@@ -130,6 +130,9 @@ def main():
                     help="1: generate the next iteration's gradient on a second stream meanwhile")
     ap.add_argument("--fuse-grad", type=int, default=0,
                     help="1: generate the gradient inside the accumulate pass (never stored)")
+    ap.add_argument("--queue-form", type=int, default=0,
+                    help="1: server state as a message queue (one model, tau_max+1 queued messages) "
+                         "instead of the snapshot ring; same iterates for constant tau")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -152,7 +155,7 @@ def main():
     t0 = time.perf_counter()
     lam, xstar, x0 = workloads.make_problem(w)
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
-    ctx = binding.Context(w.d, w.n, w.tau_max)
+    ctx = binding.Context(w.d, w.n, w.tau_max, queue_form=bool(args.queue_form))
     ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
     compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK}[args.compressor]
     ctx.set_compressor(compressor)
@@ -266,7 +269,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad),
+                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring",
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,

@@ -63,6 +63,24 @@ typedef struct ddef_ctx ddef_ctx;
  * on the current device; tau starts at tau_max.  d in [1, 2^32), n >= 1, tau_max <= 4096.
  * On failure *out is NULL.  ENOMEM when the device cannot hold the state. */
 int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out);
+
+/* The same problem with the server state of Algorithm 1 held literally: one model x_t, updated
+ * in place, and a queue of the messages of the last tau_max+1 iterations in place of the
+ * snapshot ring.  The four calls keep their order and meaning, except that in iteration t
+ *   ddef_grad            takes the gradient at the current x_t (no iteration is empty) and
+ *                        draws the noise keyed by t + tau, the iteration at which the message
+ *                        is applied, so that a constant tau gives bit for bit the iterates of
+ *                        the ring form;
+ *   ddef_ef_compress     queues the messages Delta_{i,t} (these are what ddef_get_message
+ *                        returns);
+ *   ddef_aggregate       sums the messages Delta_{i,t-tau} sent tau iterations earlier; U = 0
+ *                        while t < tau (Section 3.2's convention).
+ * tau may change between iterations within [0, tau_max]: the server then applies whatever was
+ * sent tau_t iterations before t, so a message can be applied twice or never, as with a real
+ * queue whose delay changes.  Top-k only: ddef_set_compressor rejects the others with EINVAL.
+ * Memory: x[d] and messages [tau_max+1][n][k] (index, value), not [tau_max+1][d] snapshots;
+ * the gradient prefetch option has no effect (the next gradient needs x_{t+1}). */
+int ddef_init_queue(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out);
 int ddef_destroy(ddef_ctx* ctx);
 
 /* Use a caller-provided hipStream_t (passed as void*) for all later work; NULL restores

@@ -81,6 +81,8 @@ def lib():
         "oracle_deco_noniid": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
         "oracle_queue_create": (vp, [C.c_uint64, C.c_uint32, C.c_uint32]),
         "oracle_queue_destroy": (None, [vp]),
+        "oracle_queue_set_tau": (None, [vp, C.c_uint32]),
+        "oracle_queue_set_heterogeneity": (None, [vp, C.c_float]),
         "oracle_queue_set_problem": (None, [vp, f32p, f32p, f32p, C.c_uint64, C.c_int, C.c_float]),
         "oracle_queue_step": (None, [vp, C.c_double, C.c_float]),
         "oracle_queue_get_model": (None, [vp, f32p]),
@@ -372,6 +374,13 @@ class QueueOracle:
         _, sp = _f32(xstar)
         _, xp = _f32(x0)
         lib().oracle_queue_set_problem(self._h, lp, sp, xp, int(seed), int(noise_kind), float(noise_scale))
+
+    def set_tau(self, tau):
+        self.tau = int(tau)
+        lib().oracle_queue_set_tau(self._h, self.tau)
+
+    def set_heterogeneity(self, zeta):
+        lib().oracle_queue_set_heterogeneity(self._h, float(zeta))
 
     def step(self, delta, lr):
         lib().oracle_queue_step(self._h, float(delta), float(lr))

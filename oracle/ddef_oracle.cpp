@@ -519,6 +519,7 @@ struct QueueOracle {
     uint32_t n = 0, tau = 0;
     int noise_kind = 0;
     float noise_scale = 0.0f;
+    float zeta = 0.0f;                  // non-IID: worker i's optimum is x* + zeta * u_i
     std::vector<float> lambda, xstar, x, U;
     std::vector<std::vector<float>> e;
     std::vector<std::vector<std::vector<uint32_t>>> sent_idx;   // [iteration][worker]
@@ -533,6 +534,9 @@ void* oracle_queue_create(uint64_t d, uint32_t n, uint32_t tau) {
     return q;
 }
 void oracle_queue_destroy(void* h) { delete (QueueOracle*)h; }
+// tau may change between iterations: the server applies what was sent tau iterations earlier
+void oracle_queue_set_tau(void* h, uint32_t tau) { ((QueueOracle*)h)->tau = tau; }
+void oracle_queue_set_heterogeneity(void* h, float zeta) { ((QueueOracle*)h)->zeta = zeta; }
 void oracle_queue_set_problem(void* h, const float* lambda, const float* xstar, const float* x0, uint64_t seed,
                               int noise_kind, float noise_scale) {
     QueueOracle* q = (QueueOracle*)h;
@@ -550,7 +554,9 @@ void oracle_queue_step(void* h, double delta, float lr) {
     std::vector<float> p(d), dense(d);
     for (uint32_t i = 0; i < q->n; ++i) {                          // worker side, at the current x_u
         for (uint64_t j = 0; j < d; ++j) {
-            float diff = q->x[j] - q->xstar[j];
+            float optimum = q->xstar[j];
+            if (q->zeta != 0.0f) optimum = q->xstar[j] + q->zeta * noise_z(q->seed, kHeterogeneityKey, i, (uint32_t)j, 1);
+            float diff = q->x[j] - optimum;
             float mean = q->lambda[j] * diff;
             float xi = q->noise_scale * noise_z(q->seed, u + q->tau, i, (uint32_t)j, q->noise_kind);
             float g = mean + xi;

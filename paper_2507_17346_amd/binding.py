@@ -23,6 +23,7 @@ _ctx = C.c_void_p
 
 SIGNATURES = {
     "ddef_init": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(_ctx)]),
+    "ddef_init_queue": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.POINTER(_ctx)]),
     "ddef_destroy": (C.c_int, [_ctx]),
     "ddef_set_stream": (C.c_int, [_ctx, C.c_void_p]),
     "ddef_set_problem": (C.c_int, [_ctx, _f32p, _f32p, _f32p, C.c_uint64, C.c_int, C.c_float]),
@@ -187,13 +188,15 @@ class Context:
     """One ddef_ctx.  Methods carry the C names without the prefix and raise on error codes;
     `raw_*` variants return the code instead (for error-path tests)."""
 
-    def __init__(self, d: int, n: int, tau_max: int):
+    def __init__(self, d: int, n: int, tau_max: int, queue_form: bool = False):
         self._lib = load()
         self.d, self.n, self.tau_max = int(d), int(n), int(tau_max)
+        self.queue_form = bool(queue_form)
         h = _ctx()
-        rc = self._lib.ddef_init(self.d, self.n, self.tau_max, C.byref(h))
+        init = self._lib.ddef_init_queue if self.queue_form else self._lib.ddef_init
+        rc = init(self.d, self.n, self.tau_max, C.byref(h))
         if rc != OK:
-            raise DdefError(rc, "ddef_init")
+            raise DdefError(rc, "ddef_init_queue" if self.queue_form else "ddef_init")
         self._h = h
 
     def close(self):

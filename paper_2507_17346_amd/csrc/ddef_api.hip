@@ -3,6 +3,7 @@
 // arguments, owns the device memory and enqueues launches on the context's stream.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -39,9 +40,17 @@ struct ddef_ctx {
     uint64_t d = 0, ld = 0, t = 0;
     uint32_t n = 0, tau_max = 0, tau = 0, nchunks = 0;
     float *lambda = nullptr, *xstar = nullptr, *ring = nullptr, *e = nullptr, *g = nullptr, *U = nullptr;
+    // messages: [q_slots][n][msg_ld].  Ring form keeps one slot (the messages of this iteration);
+    // queue form keeps the messages of the last tau_max+1 iterations, slot = iteration % q_slots,
+    // q_k[slot] entries per worker
     uint32_t* msg_idx = nullptr;
     float* msg_val = nullptr;
     uint64_t msg_ld = 0;
+    bool queue_form = false;
+    uint32_t ring_slots = 1, q_slots = 1;
+    uint32_t msg_slot = 0;               // slot of the messages ddef_ef_compress wrote last
+    uint32_t u_dirty_slot = 0;           // slot of the messages the last aggregate scattered into U
+    std::vector<uint64_t> q_k;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
     // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite], slot
@@ -92,7 +101,14 @@ struct ddef_ctx {
     uint64_t prof_launches[SL_COUNT] = {};
     double prof_ms[SL_COUNT] = {};
 
-    float* slot(uint64_t step) const { return ring + (step % (uint64_t)(tau_max + 1)) * ld; }
+    float* slot(uint64_t step) const { return ring + (step % (uint64_t)ring_slots) * ld; }
+    uint32_t* slot_idx(uint32_t s) const { return msg_idx + (uint64_t)s * n * msg_ld; }
+    float* slot_val(uint32_t s) const { return msg_val + (uint64_t)s * n * msg_ld; }
+    // The gradient of the iteration in progress: ring form takes it at the snapshot x_{t-tau} with
+    // the noise of iteration t; queue form at the current x_t with the noise of the iteration at
+    // which its message will be applied, so that both forms draw the same noise for the same update.
+    uint64_t grad_key() const { return queue_form ? t + tau : t; }
+    const float* grad_snapshot() const { return queue_form ? ring : slot(t - tau); }
 };
 
 namespace {
@@ -176,17 +192,29 @@ uint32_t blocks_for(ddef_ctx* c, uint64_t items_per_row_blocks, uint32_t rows, u
 
 int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
     if (k > c->msg_ld) {
+        // longer rows; the messages held so far (queued ones in queue form) move over
         HIP_TRY(c, hipStreamSynchronize(c->stream));
+        const uint64_t len = (k + 1023u) & ~(uint64_t)1023u;
+        const size_t rows = (size_t)c->q_slots * c->n;
+        uint32_t* idx = nullptr;
+        float* val = nullptr;
+        HIP_TRY(c, hipMalloc((void**)&idx, rows * len * 4u));
+        hipError_t err = hipMalloc((void**)&val, rows * len * 4u);
+        if (err != hipSuccess) {
+            (void)hipFree(idx);
+            return hip_fail(c, err);
+        }
+        err = hipMemset(idx, 0, rows * len * 4u);
+        if (err == hipSuccess) err = hipMemset(val, 0, rows * len * 4u);
+        if (err == hipSuccess && c->msg_ld)
+            err = hipMemcpy2D(idx, len * 4u, c->msg_idx, c->msg_ld * 4u, c->msg_ld * 4u, rows, hipMemcpyDeviceToDevice);
+        if (err == hipSuccess && c->msg_ld)
+            err = hipMemcpy2D(val, len * 4u, c->msg_val, c->msg_ld * 4u, c->msg_ld * 4u, rows, hipMemcpyDeviceToDevice);
+        if (err == hipSuccess) err = hipDeviceSynchronize();
+        if (err != hipSuccess) { (void)hipFree(idx); (void)hipFree(val); return hip_fail(c, err); }
         if (c->msg_idx) (void)hipFree(c->msg_idx);
         if (c->msg_val) (void)hipFree(c->msg_val);
-        c->msg_idx = nullptr; c->msg_val = nullptr; c->msg_ld = 0;
-        c->k_step = 0;                      // the last messages are gone with their buffers
-        const uint64_t len = (k + 1023u) & ~(uint64_t)1023u;
-        HIP_TRY(c, hipMalloc((void**)&c->msg_idx, (size_t)c->n * len * 4u));
-        HIP_TRY(c, hipMalloc((void**)&c->msg_val, (size_t)c->n * len * 4u));
-        HIP_TRY(c, hipMemset(c->msg_idx, 0, (size_t)c->n * len * 4u));
-        HIP_TRY(c, hipMemset(c->msg_val, 0, (size_t)c->n * len * 4u));
-        c->msg_ld = len;
+        c->msg_idx = idx; c->msg_val = val; c->msg_ld = len;
     }
     // room for the candidates: three times the target while messages are sparse, twice otherwise,
     // at least 32 slots in each of the kSubs parts of the buffer, plus one whole 256-entry group
@@ -232,8 +260,8 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
     LAUNCH(c, SL_CHUNK_SCAN, k_chunk_scan, dim3(n), dim3(1024), vs, c->sel, c->cnt_gt, c->cnt_eq, c->nchunks,
            k, kb, bound, cand_count, overflow);
     LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel,
-           (const uint32_t*)c->cnt_gt, (const uint32_t*)c->cnt_eq, c->nchunks, c->e, c->msg_idx, c->msg_val,
-           c->msg_ld, k);
+           (const uint32_t*)c->cnt_gt, (const uint32_t*)c->cnt_eq, c->nchunks, c->e, c->slot_idx(c->msg_slot),
+           c->slot_val(c->msg_slot), c->msg_ld, k);
 }
 
 // Puts U back to all-zero.  With sparse messages only the coordinates the last aggregate wrote
@@ -245,7 +273,7 @@ void clean_update(ddef_ctx* c) {
     const uint64_t k = c->u_dirty_k;
     if (k * c->n * 64u < c->d) {
         LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
-               c->U, (const uint32_t*)c->msg_idx, c->msg_ld, (uint32_t)k, (uint32_t)c->d);
+               c->U, (const uint32_t*)c->slot_idx(c->u_dirty_slot), c->msg_ld, (uint32_t)k, (uint32_t)c->d);
     } else {
         const uint64_t quads = c->ld / 4u;
         LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
@@ -253,15 +281,17 @@ void clean_update(ddef_ctx* c) {
     c->u_dirty_k = 0;
 }
 
-GradSource grad_source(const ddef_ctx* c, uint64_t t, uint32_t tau) {
-    return GradSource{c->lambda, c->xstar, c->slot(t - tau), (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-                      (uint32_t)t, (uint32_t)(t >> 32), c->noise_kind, c->noise_scale, c->zeta};
+// Gradient generator inputs: snapshot xs and the iteration number `key` the noise is drawn for.
+GradSource grad_source(const ddef_ctx* c, uint64_t key, const float* xs) {
+    return GradSource{c->lambda, c->xstar, xs, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+                      (uint32_t)key, (uint32_t)(key >> 32), c->noise_kind, c->noise_scale, c->zeta};
 }
 
-void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t t, uint32_t tau, uint32_t blocks_per_cu) {
+void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t key, const float* xs,
+                  uint32_t blocks_per_cu) {
     const uint64_t quads = (c->d + 3) / 4;
     const uint32_t gx = blocks_for(c, (quads + 255) / 256, 1, blocks_per_cu);
-    LAUNCH_ON(c, stream, SL_GRAD, k_grad, dim3(gx), dim3(256), grad_source(c, t, tau), dest, c->ld,
+    LAUNCH_ON(c, stream, SL_GRAD, k_grad, dim3(gx), dim3(256), grad_source(c, key, xs), dest, c->ld,
               (uint32_t)c->d, c->n);
 }
 
@@ -269,7 +299,7 @@ void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t t, uint
 // kernel that reads g needs it).  Valid until the iteration is applied.
 void materialize_grad(ddef_ctx* c) {
     if (!c->grad_pending) return;
-    if (!c->grad_stored) enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+    if (!c->grad_stored) enqueue_grad(c, c->stream, c->g, c->grad_key(), c->grad_snapshot(), 64u);
     c->grad_stored = true;
     c->grad_pending = false;
 }
@@ -287,7 +317,8 @@ int drop_prefetch(ddef_ctx* c) {
 // different ring slot from the one iteration t writes, as 1 <= tau <= tau_max) and writes the
 // buffer the accumulate pass of iteration t-1 has finished reading.
 int start_prefetch(ddef_ctx* c) {
-    if (!c->opt_prefetch || c->opt_fuse || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
+    // (queue form takes the next gradient at x_{t+1}, which does not exist yet)
+    if (!c->opt_prefetch || c->opt_fuse || c->queue_form || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
     if (!c->side) {
         HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
         HIP_TRY(c, hipEventCreateWithFlags(&c->ev_applied, hipEventDisableTiming));
@@ -298,7 +329,7 @@ int start_prefetch(ddef_ctx* c) {
     HIP_TRY(c, hipEventRecord(c->ev_applied, c->stream));        // everything up to here on the main stream
     HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_applied, 0));
     // fewer resident blocks than the stand-alone launch: the two kernels share the CUs' wave slots
-    enqueue_grad(c, c->side, c->g_next, c->t + 1, c->tau, 16u);
+    enqueue_grad(c, c->side, c->g_next, c->t + 1, c->slot(c->t + 1 - c->tau), 16u);
     HIP_TRY(c, hipEventRecord(c->ev_prefetched, c->side));
     c->pf_valid = true; c->pf_t = c->t + 1; c->pf_tau = c->tau;
     return DDEF_OK;
@@ -363,7 +394,7 @@ const char* ddef_strerror(int code) {
     }
 }
 
-int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
+static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, ddef_ctx** out) {
     if (!out) return DDEF_EINVAL;
     *out = nullptr;
     if (d == 0 || d >= 0xFFFFE000ull || n == 0 || n > 65535u || tau_max > 4096u) return DDEF_EINVAL;
@@ -376,6 +407,10 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     if (hipGetDeviceProperties(&prop, c->device) == hipSuccess && prop.multiProcessorCount > 0)
         c->cus = prop.multiProcessorCount;
     c->d = d; c->n = n; c->tau_max = tau_max; c->tau = tau_max;
+    c->queue_form = queue_form;
+    c->ring_slots = queue_form ? 1u : tau_max + 1u;
+    c->q_slots = queue_form ? tau_max + 1u : 1u;
+    c->q_k.assign(c->q_slots, 0);
     c->ld = (d + 4095u) & ~(uint64_t)4095u;
     c->nchunks = (uint32_t)(c->ld / 4096u);
     c->nwc = (uint32_t)(c->ld / 256u);          // 256-entry groups of the filter kernel
@@ -386,7 +421,7 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     struct Want { void** p; size_t bytes; };
     Want wants[] = {
         {(void**)&c->lambda, row}, {(void**)&c->xstar, row}, {(void**)&c->U, row},
-        {(void**)&c->ring, row * (tau_max + 1u)}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
+        {(void**)&c->ring, row * c->ring_slots}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
         {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
@@ -401,6 +436,14 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(DDEF_EHIP);
     *out = c;
     return DDEF_OK;
+}
+
+int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
+    return init_ctx(d, n, tau_max, false, out);
+}
+
+int ddef_init_queue(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out) {
+    return init_ctx(d, n, tau_max, true, out);
 }
 
 int ddef_destroy(ddef_ctx* c) {
@@ -448,8 +491,9 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     const size_t bytes = (size_t)c->d * 4u;
     HIP_TRY(c, hipMemcpy(c->lambda, host_lambda, bytes, hipMemcpyHostToDevice));
     HIP_TRY(c, hipMemcpy(c->xstar, host_xstar, bytes, hipMemcpyHostToDevice));
-    for (uint32_t s = 0; s <= c->tau_max; ++s)
+    for (uint32_t s = 0; s < c->ring_slots; ++s)
         HIP_TRY(c, hipMemcpy(c->ring + (uint64_t)s * c->ld, host_x0, bytes, hipMemcpyHostToDevice));
+    std::fill(c->q_k.begin(), c->q_k.end(), (uint64_t)0);
     HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
@@ -467,6 +511,7 @@ int ddef_set_compressor(ddef_ctx* c, int kind) {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK) return DDEF_EINVAL;
+    if (c->queue_form && kind != DDEF_COMPRESSOR_TOPK) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     c->compressor = kind;
     return DDEF_OK;
@@ -499,7 +544,7 @@ int ddef_grad(ddef_ctx* c) {
     if (rc) return rc;
     if (!c->problem_set || c->phase != PH_IDLE) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
-    c->step_empty = c->t < c->tau;
+    c->step_empty = !c->queue_form && c->t < c->tau;
     c->grad_pending = false;
     c->grad_stored = false;
     c->grad_live = !c->step_empty;
@@ -513,7 +558,7 @@ int ddef_grad(ddef_ctx* c) {
             c->g = ready;
             c->pf_valid = false;
         } else {
-            enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+            enqueue_grad(c, c->stream, c->g, c->grad_key(), c->grad_snapshot(), 64u);
         }
         HIP_TRY(c, hipGetLastError());
         rc = start_prefetch(c);
@@ -558,6 +603,8 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     if (kb > c->d) kb = c->d;
     rc = ensure_capacity(c, k, kb);
     if (rc) return rc;
+    c->msg_slot = (uint32_t)(c->t % c->q_slots);
+    c->q_k[c->msg_slot] = 0;               // set again once the launches are enqueued
     const uint32_t n = c->n;
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     uint32_t* cand_total = c->filt + 3 * n;
@@ -579,16 +626,17 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                (uint32_t)k, c->sel, cand_total, cand_count);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
-               c->msg_idx, c->msg_val, c->msg_ld);
+               c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld);
         HIP_TRY(c, hipGetLastError());
         c->have_bound = false;          // a Top-k bound from before no longer describes e
         c->k_step = k;
+        c->q_k[c->msg_slot] = k;
         c->phase = PH_COMPRESSED;
         return DDEF_OK;
     }
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
-    const GradSource src = grad_source(c, c->t, c->tau);
+    const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
     if (c->grad_pending) {
         LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
                n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count,
@@ -616,6 +664,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     c->have_bound = true;
     HIP_TRY(c, hipGetLastError());
     c->k_step = k;
+    c->q_k[c->msg_slot] = k;
     c->phase = PH_COMPRESSED;
     return DDEF_OK;
 }
@@ -626,13 +675,24 @@ int ddef_aggregate(ddef_ctx* c) {
     if (c->phase != PH_COMPRESSED) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
     clean_update(c);
-    if (c->k_step) {
-        const uint32_t k = (uint32_t)c->k_step;
+    // ring form: the messages of this iteration; queue form: the ones sent tau iterations ago,
+    // nothing while t < tau (Delta_{t-tau} = 0 by convention, Section 3.2)
+    uint32_t src = c->msg_slot;
+    uint64_t ka = c->k_step;
+    if (c->queue_form) {
+        src = (uint32_t)((c->t + c->q_slots - c->tau) % c->q_slots);
+        ka = c->t >= c->tau ? c->q_k[src] : 0;
+    }
+    if (ka) {
+        const uint32_t k = (uint32_t)ka;
         const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
+        const uint32_t* idx = c->slot_idx(src);
+        const float* val = c->slot_val(src);
         for (uint32_t i = 0; i < c->n; ++i)
-            LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U,
-                   c->msg_idx + (uint64_t)i * c->msg_ld, c->msg_val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
-        c->u_dirty_k = c->k_step;
+            LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U, idx + (uint64_t)i * c->msg_ld,
+                   val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
+        c->u_dirty_k = ka;
+        c->u_dirty_slot = src;
     }
     HIP_TRY(c, hipGetLastError());
     c->phase = PH_AGGREGATED;
@@ -714,7 +774,7 @@ int ddef_get_grad(ddef_ctx* c, uint32_t worker, float* host_g) {
     DeviceGuard guard(c->device);
     if (c->opt_fuse && !c->grad_stored && c->phase != PH_IDLE) {
         // generate it from the same inputs (the snapshot is intact until the iteration is applied)
-        enqueue_grad(c, c->stream, c->g, c->t, c->tau, 64u);
+        enqueue_grad(c, c->stream, c->g, c->grad_key(), c->grad_snapshot(), 64u);
         c->grad_stored = true;
     }
     return copy_row_out(c, c->g + (uint64_t)worker * c->ld, host_g);
@@ -739,10 +799,10 @@ int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* ho
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     rc = check_device_flags(c);
     if (rc) return rc;
-    HIP_TRY(c, hipMemcpy(host_idx, c->msg_idx + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
-                         hipMemcpyDeviceToHost));
-    HIP_TRY(c, hipMemcpy(host_val, c->msg_val + (uint64_t)worker * c->msg_ld, (size_t)c->k_step * 4u,
-                         hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(host_idx, c->slot_idx(c->msg_slot) + (uint64_t)worker * c->msg_ld,
+                         (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(host_val, c->slot_val(c->msg_slot) + (uint64_t)worker * c->msg_ld,
+                         (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
     return DDEF_OK;
 }
 

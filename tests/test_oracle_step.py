@@ -280,3 +280,52 @@ def test_stepwise_queue_form(oracle_mod, tau, delta):
             ri, rv = ring2.get_message(i)
             assert np.array_equal(qi, ri) and np.array_equal(bits(qv), bits(rv))
             assert np.array_equal(bits(q2.get_error(i)), bits(ring2.get_error(i)))
+
+
+def test_stepwise_queue_form_changing_tau_is_delayed_sgd_at_delta_one(oracle_mod):
+    """delta = 1 keeps every e_i at zero, so the message of iteration u is lr * g_u and the server's
+    rule is x_{t+1} = x_t - (1/n) sum_i lr * g_{i, t - tau_t}: replayed here in numpy."""
+    w, lam, xstar, x0 = small_problem(seed=61, d=700, n=2)
+    lr = 0.05
+    taus = [0, 0, 2, 2, 1, 3, 3, 0, 2, 1, 1, 3]
+    q = oracle_mod.QueueOracle(w.d, w.n, 0)
+    q.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    x = x0.copy()
+    sent = []
+    for t, tau in enumerate(taus):
+        q.set_tau(tau)
+        q.step(1.0, lr)
+        msgs = []
+        for i in range(w.n):
+            z = oracle_mod.noise_fill(w.seed, t + tau, i, 0, w.d, w.noise_kind)
+            msgs.append(F32(lr) * (lam * (x - xstar) + F32(w.noise_scale) * z))
+            assert np.all(bits(q.get_error(i)) == 0)
+            idx, val = q.get_message(i)
+            assert np.array_equal(idx, np.arange(w.d)) and np.array_equal(bits(val), bits(msgs[i]))
+        sent.append(msgs)
+        upd = np.zeros(w.d, dtype=F32)
+        if t >= tau:
+            for i in range(w.n):
+                upd = upd + sent[t - tau][i]
+        x = x - upd / F32(w.n)
+        assert np.array_equal(bits(q.get_update()), bits(upd))
+        assert np.array_equal(bits(q.get_model()), bits(x))
+
+
+def test_stepwise_queue_form_non_iid_matches_ring_form(oracle_mod):
+    tau, delta, lr, T = 2, 0.05, 0.05, 10
+    w, lam, xstar, x0 = small_problem(seed=62, d=600, n=3)
+    q = oracle_mod.QueueOracle(w.d, w.n, tau)
+    q.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    q.set_heterogeneity(0.7)
+    ring = make_oracle(oracle_mod, w, lam, xstar, x0, tau)
+    ring.set_heterogeneity(0.7)
+    for t in range(T):
+        q.step(delta, lr)
+        ring.step(delta, lr)
+        assert np.array_equal(bits(q.get_model()), bits(ring.get_model()))
+    plain = oracle_mod.QueueOracle(w.d, w.n, tau)
+    plain.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    for t in range(T):
+        plain.step(delta, lr)
+    assert not np.array_equal(bits(plain.get_model()), bits(q.get_model()))
