@@ -22,12 +22,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
-    SL_APPLY, SL_COPY_PROBE, SL_COUNT
+    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_apply", "k_copy_f4"};
+    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_msg_offsets", "k_aggregate_tiles", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -82,8 +82,12 @@ struct ddef_ctx {
     uint64_t pf_t = 0;
     uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
-    // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each)
+    // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each),
+    // or, after a dense aggregation, holds a full sum (u_dense) that the next one overwrites
     uint64_t u_dirty_k = 0;
+    bool u_dense = false;
+    uint32_t* agg_off = nullptr;         // dense aggregation: [n][ld/kTile + 1] message offsets at tile boundaries
+    uint32_t ntiles = 0;
     Phase phase = PH_IDLE;
     bool problem_set = false, step_empty = true;
     float lr_step = 0.0f;
@@ -264,21 +268,29 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
            c->slot_val(c->msg_slot), c->msg_ld, k);
 }
 
-// Puts U back to all-zero.  With sparse messages only the coordinates the last aggregate wrote
-// are cleared; a scattered 4-byte store costs far more than its 4 bytes (measured: about 190
-// bytes of fill bandwidth each), so this pays while n*k < d/64; otherwise the row is filled.  Must run before the message buffers are
-// overwritten or reallocated.
-void clean_update(ddef_ctx* c) {
+// A scattered 4-byte access costs far more than its 4 bytes (measured: about 190 bytes of fill
+// bandwidth each), so messages are summed by scatter-add, and U cleared at the same coordinates
+// afterwards, only while n*k < d/64; denser messages are summed tile by tile into a U that is
+// overwritten as a whole.
+bool sparse_messages(const ddef_ctx* c, uint64_t k) { return k * c->n * 64u < c->d; }
+
+// After a scatter-add: puts U back to all-zero by clearing the coordinates the messages named.
+// Must run before those message buffers are overwritten or reallocated.
+void clean_sparse_update(ddef_ctx* c) {
     if (!c->u_dirty_k) return;
     const uint64_t k = c->u_dirty_k;
-    if (k * c->n * 64u < c->d) {
-        LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
-               c->U, (const uint32_t*)c->slot_idx(c->u_dirty_slot), c->msg_ld, (uint32_t)k, (uint32_t)c->d);
-    } else {
-        const uint64_t quads = c->ld / 4u;
-        LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
-    }
+    LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
+           c->U, (const uint32_t*)c->slot_idx(c->u_dirty_slot), c->msg_ld, (uint32_t)k, (uint32_t)c->d);
     c->u_dirty_k = 0;
+}
+
+// After a dense aggregation: fills the row with zeros (only needed when the next aggregation
+// does not overwrite it).
+void clean_dense_update(ddef_ctx* c) {
+    if (!c->u_dense) return;
+    const uint64_t quads = c->ld / 4u;
+    LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
+    c->u_dense = false;
 }
 
 // Gradient generator inputs: snapshot xs and the iteration number `key` the noise is drawn for.
@@ -415,6 +427,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
     c->nchunks = (uint32_t)(c->ld / 4096u);
     c->nwc = (uint32_t)(c->ld / 256u);          // 256-entry groups of the filter kernel
     c->nspans = (c->nwc + kSpan - 1u) / kSpan;
+    c->ntiles = (uint32_t)(c->ld / kTile);
     if (hipStreamCreateWithFlags(&c->own_stream, hipStreamNonBlocking) != hipSuccess) return fail(DDEF_EHIP);
     c->stream = c->own_stream;
     const size_t row = (size_t)c->ld * 4u;
@@ -426,6 +439,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
         {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
+        {(void**)&c->agg_off, (size_t)n * (c->ntiles + 1u) * 4},
     };
     for (const Want& w : wants) {
         err = hipMalloc(w.p, w.bytes);
@@ -456,7 +470,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->bitmap, c->g_next, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->bitmap, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -504,6 +518,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
     c->u_dirty_k = 0;
+    c->u_dense = false;
     return DDEF_OK;
 }
 
@@ -596,7 +611,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         return DDEF_OK;
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
-    clean_update(c);
+    clean_sparse_update(c);
     // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
     uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
     if (kb < k) kb = k;
@@ -674,7 +689,7 @@ int ddef_aggregate(ddef_ctx* c) {
     if (rc) return rc;
     if (c->phase != PH_COMPRESSED) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
-    clean_update(c);
+    clean_sparse_update(c);
     // ring form: the messages of this iteration; queue form: the ones sent tau iterations ago,
     // nothing while t < tau (Delta_{t-tau} = 0 by convention, Section 3.2)
     uint32_t src = c->msg_slot;
@@ -683,16 +698,25 @@ int ddef_aggregate(ddef_ctx* c) {
         src = (uint32_t)((c->t + c->q_slots - c->tau) % c->q_slots);
         ka = c->t >= c->tau ? c->q_k[src] : 0;
     }
-    if (ka) {
-        const uint32_t k = (uint32_t)ka;
-        const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
-        const uint32_t* idx = c->slot_idx(src);
-        const float* val = c->slot_val(src);
-        for (uint32_t i = 0; i < c->n; ++i)
-            LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U, idx + (uint64_t)i * c->msg_ld,
-                   val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
-        c->u_dirty_k = ka;
-        c->u_dirty_slot = src;
+    const uint32_t* idx = c->slot_idx(src);
+    const float* val = c->slot_val(src);
+    if (ka && !sparse_messages(c, ka)) {
+        LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, c->n), dim3(256), idx,
+               c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off);
+        LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles, dim3(c->ntiles), dim3(256), c->U, idx, val, c->msg_ld,
+               (const uint32_t*)c->agg_off, c->ntiles, c->n);
+        c->u_dense = true;
+    } else {
+        clean_dense_update(c);
+        if (ka) {
+            const uint32_t k = (uint32_t)ka;
+            const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
+            for (uint32_t i = 0; i < c->n; ++i)
+                LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U, idx + (uint64_t)i * c->msg_ld,
+                       val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
+            c->u_dirty_k = ka;
+            c->u_dirty_slot = src;
+        }
     }
     HIP_TRY(c, hipGetLastError());
     c->phase = PH_AGGREGATED;

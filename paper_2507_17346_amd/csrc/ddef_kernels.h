@@ -13,6 +13,7 @@ constexpr uint32_t kSubs = 256;
 constexpr uint32_t kSubStride = 32;
 // The run table is scanned in spans of this many 256-entry groups (one block each).
 constexpr uint32_t kSpan = 1024;
+constexpr uint32_t kTile = 4096;      // coordinates per block of the dense aggregation
 
 // Per-worker selection state in device memory.
 struct SelState {
@@ -84,6 +85,9 @@ __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* o
                              float* msg_val, uint64_t msg_ld, uint32_t k);
 __global__ void k_scatter_add(float* U, const uint32_t* idx, const float* val, uint32_t k, uint32_t d);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
+__global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off);
+__global__ void k_aggregate_tiles(float* U, const uint32_t* idx, const float* val, uint64_t msg_ld,
+                                  const uint32_t* off, uint32_t ntiles, uint32_t n);
 __global__ void k_unscatter(float* U, const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t d);
 __global__ void k_fill_f4(float* p, uint64_t quads);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);

@@ -862,6 +862,63 @@ __global__ __launch_bounds__(256) void k_scatter_add(float* __restrict__ U,
     }
 }
 
+// S4, dense messages: the same sum, tile by tile.  k_msg_offsets finds, for every worker and
+// every boundary b * kTile, how many of the worker's (ascending) indices lie below it; then one
+// block per tile of kTile coordinates adds the workers' entries of its range into a tile in
+// LDS, worker after worker (a barrier between workers keeps the summation order; indices
+// inside one message are distinct, so the adds of one worker never collide), and writes the
+// tile out with coalesced stores.  U is overwritten as a whole: no clearing before or after,
+// and no scattered read-modify-write in HBM.
+__global__ __launch_bounds__(256) void k_msg_offsets(const uint32_t* __restrict__ idx, uint64_t msg_ld,
+                                                     uint32_t k, uint32_t ntiles,
+                                                     uint32_t* __restrict__ off) {
+    const uint32_t w = blockIdx.y;
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b > ntiles) return;
+    const uint32_t* row = idx + (uint64_t)w * msg_ld;
+    const uint64_t edge = (uint64_t)b * kTile;             // may exceed 2^32 at the last boundary
+    uint32_t lo = 0, hi = k;                               // first position with row[pos] >= edge
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if ((uint64_t)row[mid] < edge) lo = mid + 1u; else hi = mid;
+    }
+    off[(uint64_t)w * (ntiles + 1u) + b] = lo;
+}
+
+__global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
+                                                         const uint32_t* __restrict__ idx,
+                                                         const float* __restrict__ val, uint64_t msg_ld,
+                                                         const uint32_t* __restrict__ off,
+                                                         uint32_t ntiles, uint32_t n) {
+    __shared__ __attribute__((aligned(16))) float tile[kTile];
+    __shared__ uint32_t lo_s[256], hi_s[256];
+    const uint32_t b = blockIdx.x;
+    const uint32_t base = b * kTile;
+    for (uint32_t q = threadIdx.x; q < kTile; q += 256u) tile[q] = 0.0f;
+    for (uint32_t w0 = 0; w0 < n; w0 += 256u) {
+        const uint32_t batch = n - w0 < 256u ? n - w0 : 256u;
+        __syncthreads();                                   // tile zeroed / last batch's bounds consumed
+        if (threadIdx.x < batch) {
+            const uint32_t* o = off + (uint64_t)(w0 + threadIdx.x) * (ntiles + 1u) + b;
+            lo_s[threadIdx.x] = o[0];
+            hi_s[threadIdx.x] = o[1];
+        }
+        __syncthreads();
+        for (uint32_t i = 0; i < batch; ++i) {
+            const uint32_t* ri = idx + (uint64_t)(w0 + i) * msg_ld;
+            const float* rv = val + (uint64_t)(w0 + i) * msg_ld;
+            const uint32_t hi = hi_s[i];
+            for (uint32_t m = lo_s[i] + threadIdx.x; m < hi; m += 256u) {
+                const uint32_t at = ri[m] - base;          // < kTile by the choice of lo, hi
+                tile[at] = tile[at] + rv[m];
+            }
+            __syncthreads();
+        }
+    }
+    float4* out = reinterpret_cast<float4*>(U + (uint64_t)base);
+    for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) out[q] = reinterpret_cast<const float4*>(tile)[q];
+}
+
 // S5  x_{t+1} = x_t - U / n, written into the next ring slot (may alias x_t when the ring
 // has a single slot: element-wise, so in place is fine).  One quad per thread, single-wave
 // blocks in address order.
