@@ -53,7 +53,7 @@ struct ddef_ctx {
     std::vector<uint64_t> q_k;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
-    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite], slot
+    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite | zero_at], slot
     // counters [n][kSubs], the run table per 256-entry group with its prefixes, and the
     // candidate buffers of `cap` entries per worker
     uint32_t* filt = nullptr;
@@ -262,7 +262,7 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
     LAUNCH(c, SL_CHUNK_COUNT, k_chunk_count, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel, c->cnt_gt,
            c->cnt_eq, c->nchunks);
     LAUNCH(c, SL_CHUNK_SCAN, k_chunk_scan, dim3(n), dim3(1024), vs, c->sel, c->cnt_gt, c->cnt_eq, c->nchunks,
-           k, kb, bound, cand_count, overflow);
+           k, kb, bound, c->filt + 5 * n, cand_count, overflow);
     LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel,
            (const uint32_t*)c->cnt_gt, (const uint32_t*)c->cnt_eq, c->nchunks, c->e, c->slot_idx(c->msg_slot),
            c->slot_val(c->msg_slot), c->msg_ld, k);
@@ -437,7 +437,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
         {(void**)&c->ring, row * c->ring_slots}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
-        {(void**)&c->filt, (size_t)5 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->filt, (size_t)6 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
         {(void**)&c->agg_off, (size_t)n * (c->ntiles + 1u) * 4},
     };
@@ -511,7 +511,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
     HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
     HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
-    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)5 * c->n * 4));
+    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)6 * c->n * 4));
     HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
     c->have_bound = false;
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
@@ -623,6 +623,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     const uint32_t n = c->n;
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     uint32_t* cand_total = c->filt + 3 * n;
+    uint32_t* zero_at = c->filt + 5 * n;
     if (c->compressor == DDEF_COMPRESSOR_RANDK) {
         materialize_grad(c);
         const uint64_t bitmap_ld = c->ld / 32u;
@@ -641,7 +642,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                (uint32_t)k, c->sel, cand_total, cand_count);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
-               c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld);
+               c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld, (float*)nullptr, (uint64_t)0);
         HIP_TRY(c, hipGetLastError());
         c->have_bound = false;          // a Top-k bound from before no longer describes e
         c->k_step = k;
@@ -654,22 +655,22 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
     if (c->grad_pending) {
         LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
-               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count,
-               overflow, c->tab, c->nwc, c->filt + 4 * n);
+               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
     } else {
         LAUNCH(c, SL_EF_FILTER, k_ef_filter<false>, dim3(c->nwc, n), dim3(64), c->e, (const float*)c->g, src, n,
-               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, use_filter ? 1 : 0, c->cand, c->cap, cand_count,
-               overflow, c->tab, c->nwc, c->filt + 4 * n);
+               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
     }
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide, dim3(n), dim3(256), c->span_sum, c->nspans,
                (const uint32_t*)overflow, (uint32_t)k, (uint32_t)kb, (uint32_t)c->d, n, c->sel, cand_total,
-               stat_full, c->hist);
+               stat_full, (const uint32_t*)zero_at, c->hist);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
-               c->sorted_idx, c->sorted_val, c->cap);
+               c->sorted_idx, c->sorted_val, c->cap, c->e, c->ld);
     } else {
         LAUNCH(c, SL_SEL_BEGIN_ROWS, k_sel_begin_rows, dim3(n), dim3(256), c->sel, n, (uint32_t)k, (uint32_t)kb,
                (uint32_t)c->d, cand_total, c->hist);

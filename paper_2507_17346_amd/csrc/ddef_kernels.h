@@ -25,6 +25,7 @@ struct SelState {
     uint32_t seen;        // candidates the filter caught in the last selection
     uint32_t T_prev;      // threshold pattern of the selection before the last one
     uint32_t k_prev;      // its k (0: none)
+    uint32_t zero_used;   // candidates at or above this pattern were written to e as +0 ahead of time
 };
 
 // Where the selection kernels find a worker's entries: its whole row of e (d entries, the
@@ -54,18 +55,18 @@ struct GradSource {
 __global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);
 template <bool kFusedGrad>
 __global__ void k_ef_filter(float* e, const float* g, GradSource src, uint32_t n, uint64_t ld, uint32_t d,
-                            float lr, const uint32_t* bound, int use_filter, uint2* cand, uint64_t cap,
+                            float lr, const uint32_t* bound, const uint32_t* zero_at, int use_filter, uint2* cand, uint64_t cap,
                             uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups,
                             uint32_t* nonfinite);
 __global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
 __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
                              uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,
-                             uint32_t* stat_full, uint32_t* hist);
+                             uint32_t* stat_full, const uint32_t* zero_at, uint32_t* hist);
 __global__ void k_sel_begin_rows(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t d,
                                  uint32_t* cand_total, uint32_t* hist);
 __global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* span_off, uint32_t nspans,
                             const SelState* sel, const uint2* cand, uint64_t cap, uint32_t* sorted_idx,
-                            float* sorted_val, uint64_t out_ld);
+                            float* sorted_val, uint64_t out_ld, float* e_row, uint64_t e_ld);
 __global__ void k_randk_mark(uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d, uint32_t k, uint32_t seed_lo,
                              uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
 __global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, uint32_t* bitmap,
@@ -78,7 +79,7 @@ __global__ void k_digit_pick(SelState* sel, const uint32_t* hist, int level);
 __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
                               uint32_t stride);
 __global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
-                             uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound,
+                             uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound, uint32_t* zero_at,
                              uint32_t* cand_count, uint32_t* overflow);
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,

@@ -229,12 +229,20 @@ __global__ __launch_bounds__(256) void k_grad(GradSource s, float* __restrict__ 
 // with a counter each, and group number mod kSubs picks the part.
 // With use_filter == 0 this is the plain accumulate pass.  With kFusedGrad the gradient is not
 // read from g but generated in place (same arithmetic as k_grad), so it never touches HBM.
+//
+// Residual ahead of time: candidates whose magnitude pattern is >= zero_at[w] (the threshold
+// this selection is expected to end at) are written to e as +0 right here, in the dense store
+// that happens anyway, on the guess that they will be sent.  Their values live on in the
+// candidate buffer; once the exact threshold is known, only the entries between the guess and
+// the truth need a scattered store (k_chunk_emit), instead of all k sent ones.  A group that
+// gets no slots keeps all its entries in e and records an empty run.
 // ------------------------------------------------------------------------------------
 template <bool kFusedGrad>
 __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
                                                   GradSource src, uint32_t n,
                                                   uint64_t ld, uint32_t d, float lr,
-                                                  const uint32_t* __restrict__ bound, int use_filter,
+                                                  const uint32_t* __restrict__ bound,
+                                                  const uint32_t* __restrict__ zero_at, int use_filter,
                                                   uint2* __restrict__ cand, uint64_t cap,
                                                   uint32_t* __restrict__ cand_count,
                                                   uint32_t* __restrict__ overflow,
@@ -247,8 +255,8 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
     const uint32_t lane = threadIdx.x;
     const uint32_t j = grp * 256u + lane * 4u;
     float pv[4] = {0.f, 0.f, 0.f, 0.f};
+    float* ep = e + (uint64_t)w * ld + j;
     if (j < d) {
-        float* ep = e + (uint64_t)w * ld + j;
         const float4 ev = load_stream4(ep);
         float gq[4];
         if (kFusedGrad) {
@@ -261,16 +269,19 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         pv[1] = ev.y + lr * gq[1];
         pv[2] = ev.z + lr * gq[2];
         pv[3] = ev.w + lr * gq[3];
-        store_stream4(ep, pv);
     }
     if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
-    if (!use_filter) return;
-    const uint32_t L = bound[w];
+    if (!use_filter) {
+        if (j < d) store_stream4(ep, pv);
+        return;
+    }
+    const uint32_t L = bound[w], H = zero_at[w];
     bool f[4];
     bool any = false;
 #pragma unroll
     for (int c = 0; c < 4; ++c) { f[c] = (j + c < d) && mag_key(pv[c]) >= L; any |= f[c]; }
     uint32_t first = 0, total = 0;
+    bool placed = false;                       // the group's candidates are in the buffer
     if (__ballot(any)) {                       // most groups hold no candidate at all
         uint32_t below = 0;
 #pragma unroll
@@ -286,7 +297,9 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         got = __shfl(got, 0, 64);
         if (got + total > sub_cap) {
             if (lane == 0) overflow[w] = 1u;
+            total = 0;                         // nothing recorded for this group
         } else {
+            placed = true;
             first = sub * sub_cap + got;
             uint2* cw = cand + (uint64_t)w * cap;
             uint32_t pos = first + below;
@@ -295,15 +308,21 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
                 if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
         }
     }
+    if (j < d) {
+        float ov[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ov[c] = (placed && f[c] && mag_key(pv[c]) >= H) ? 0.0f : pv[c];
+        store_stream4(ep, ov);
+    }
     if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
 }
 
 template __global__ void k_ef_filter<false>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
-                                            const uint32_t*, int, uint2*, uint64_t, uint32_t*, uint32_t*, uint2*,
-                                            uint32_t, uint32_t*);
+                                            const uint32_t*, const uint32_t*, int, uint2*, uint64_t, uint32_t*,
+                                            uint32_t*, uint2*, uint32_t, uint32_t*);
 template __global__ void k_ef_filter<true>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
-                                           const uint32_t*, int, uint2*, uint64_t, uint32_t*, uint32_t*, uint2*,
-                                           uint32_t, uint32_t*);
+                                           const uint32_t*, const uint32_t*, int, uint2*, uint64_t, uint32_t*,
+                                           uint32_t*, uint2*, uint32_t, uint32_t*);
 
 // ------------------------------------------------------------------------------------
 // Random-k sparsifier (the paper's appendix on other sparsifiers): worker w keeps the k
@@ -484,6 +503,7 @@ __global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_
                                                     SelState* __restrict__ sel,
                                                     uint32_t* __restrict__ cand_total,
                                                     uint32_t* __restrict__ stat_full,
+                                                    const uint32_t* __restrict__ zero_at,
                                                     uint32_t* __restrict__ hist) {
     __shared__ uint32_t lds[5];
     const uint32_t w = blockIdx.x;
@@ -502,6 +522,7 @@ __global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_
     if (threadIdx.x == 0) {
         cand_total[w] = M;
         sel[w].active = usable ? 0u : 1u;
+        sel[w].zero_used = zero_at[w];          // what the accumulate pass zeroed ahead of time
         if (!usable) stat_full[w] += 1u;
     }
     begin_selection(sel, w, n, k, kb, usable ? M : d, hist);
@@ -513,7 +534,7 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
                                                         uint32_t* __restrict__ cand_total,
                                                         uint32_t* __restrict__ hist) {
     const uint32_t w = blockIdx.x;
-    if (threadIdx.x == 0) { sel[w].active = 1u; cand_total[w] = 0u; }
+    if (threadIdx.x == 0) { sel[w].active = 1u; sel[w].zero_used = 0xffffffffu; cand_total[w] = 0u; }
     begin_selection(sel, w, n, k, kb, d, hist);
 }
 
@@ -521,17 +542,24 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 // cand[first .. first+len) goes to positions [at, at+len) of the ordered arrays (index,
 // value; rows of out_ld entries).  The block copies its span's candidates together: thread q takes the q-th, finds
 // its group by bisection over the span's prefixes in LDS, and the stores are coalesced.
+// A worker whose selection falls back to its whole row (active == 1) gets its row completed
+// instead: the recorded candidates that the accumulate pass had zeroed ahead of time are
+// written back to e (e_row non-null; rows of e_ld floats).
 __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ tab, uint32_t ngroups,
                                                     const uint32_t* __restrict__ span_off,
                                                     uint32_t nspans, const SelState* __restrict__ sel,
                                                     const uint2* __restrict__ cand, uint64_t cap,
                                                     uint32_t* __restrict__ sorted_idx,
-                                                    float* __restrict__ sorted_val, uint64_t out_ld) {
+                                                    float* __restrict__ sorted_val, uint64_t out_ld,
+                                                    float* __restrict__ e_row, uint64_t e_ld) {
     __shared__ uint32_t lds[17];
     __shared__ uint32_t at_of[kSpan];        // exclusive prefix of the run lengths inside the span
     __shared__ uint32_t first_of[kSpan];     // first slot of each run
     const uint32_t w = blockIdx.y, sp = blockIdx.x;
-    if (sel[w].active) return;
+    const uint32_t mode = sel[w].active;
+    const bool restore = mode == 1u && e_row != nullptr;
+    if (mode != 0u && !restore) return;
+    const uint32_t zero_used = sel[w].zero_used;
     const uint32_t c = sp * kSpan + threadIdx.x;
     const uint2 run = c < ngroups ? tab[(uint64_t)w * ngroups + c] : make_uint2(0u, 0u);
     uint32_t total;
@@ -550,8 +578,12 @@ __global__ __launch_bounds__(1024) void k_tab_order(const uint2* __restrict__ ta
         }
         const uint32_t grp = lo - 1u;           // at_of[0] = 0 <= q, so lo >= 1; empty runs are skipped
         const uint2 item = cw[first_of[grp] + (q - at_of[grp])];
-        sorted_idx[out0 + q] = item.x;
-        sorted_val[out0 + q] = __uint_as_float(item.y);
+        if (restore) {
+            if ((item.y & 0x7fffffffu) >= zero_used) e_row[(uint64_t)w * e_ld + item.x] = __uint_as_float(item.y);
+        } else {
+            sorted_idx[out0 + q] = item.x;
+            sorted_val[out0 + q] = __uint_as_float(item.y);
+        }
     }
 }
 
@@ -716,10 +748,11 @@ __global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState
 // middle of the usable window [k, 7.5 k], so the trend is followed in full.  The bound only decides which search runs; the selection
 // itself is exact either way.
 __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k, uint32_t kb,
-                                           uint32_t* bound, const uint32_t* cand_total,
+                                           uint32_t* bound, uint32_t* zero_at, const uint32_t* cand_total,
                                            uint32_t* overflow) {
     uint32_t nb = sel[w].next_bound;
     const uint32_t T = sel[w].T;
+    uint32_t nz = T;                            // expected threshold of the next selection
     if (sel[w].active == 0u) {
         const uint32_t M = cand_total[w], L = bound[w];
         if (M < kb) {
@@ -740,11 +773,14 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
         if (ratio < 0.75f || ratio > 1.5f) ratio = 1.0f;
         const float moved = __uint_as_float(nb) * ratio;
         if (moved > 0.0f && moved < 3.0e38f) nb = __float_as_uint(moved);
+        const float moved_T = __uint_as_float(T) * ratio;
+        if (moved_T > 0.0f && moved_T < 3.0e38f) nz = __float_as_uint(moved_T);
     }
     sel[w].T_prev = T;
     sel[w].k_prev = k;
     sel[w].seen = cand_total[w];
     bound[w] = nb;
+    zero_at[w] = nz;
     overflow[w] = 0u;
 }
 
@@ -755,6 +791,7 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __re
                                                      uint32_t* __restrict__ cnt_gt,
                                                      uint32_t* __restrict__ cnt_eq, uint32_t stride,
                                                      uint32_t k, uint32_t kb, uint32_t* __restrict__ bound,
+                                                     uint32_t* __restrict__ zero_at,
                                                      uint32_t* __restrict__ cand_count,
                                                      uint32_t* __restrict__ overflow) {
     __shared__ uint32_t lds[17];
@@ -778,13 +815,15 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __re
         eq_carry += eq_total;
         out_carry += out_total;
     }
-    if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, vs.cand_total, overflow);
+    if (threadIdx.x == 0) next_bound(sel, w, k, kb, bound, zero_at, vs.cand_total, overflow);
     for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[(w * kSubs + q) * kSubStride] = 0u;
 }
 
-// Writes the message (ascending coordinate) and sets the sent entries of e to +0.  In a
-// candidate view map[pos] is the coordinate of entry pos; in a row view the position is the
-// coordinate.
+// Writes the message (ascending coordinate) and makes e the residual: sent entries +0, all
+// others their value.  In a row view the position is the coordinate and every sent entry is
+// cleared.  In a candidate view map[pos] is the coordinate of entry pos, and the accumulate
+// pass has already cleared the candidates at or above zero_used: only a sent entry below it
+// still has to be cleared, and an unsent one at or above it gets its value back.
 __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState* __restrict__ sel,
                                                     const uint32_t* __restrict__ out_base,
                                                     const uint32_t* __restrict__ eq_before,
@@ -797,6 +836,7 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
     const View v = view_of(vs, sel, w);
     const uint32_t nchunks = (v.count + 4095u) >> 12;
     const uint32_t T = sel[w].T, r = sel[w].r;
+    const uint32_t zero_used = v.map ? sel[w].zero_used : 0xffffffffu;
     float* erow = e + (uint64_t)w * vs.ld;
     uint32_t* oi = msg_idx + (uint64_t)w * msg_ld;
     float* ov = msg_val + (uint64_t)w * msg_ld;
@@ -834,13 +874,17 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
             uint32_t send_total;
             uint32_t pos = out_run + block_excl_scan(nsend, lds, &send_total);
 #pragma unroll
-            for (int m = 0; m < 4; ++m)
+            for (int m = 0; m < 4; ++m) {
+                const bool cleared = key[m] >= zero_used;          // already +0 in e
                 if (send[m]) {
                     const uint32_t coord = v.map ? v.map[j + m] : j + m;
                     if (pos < k) { oi[pos] = coord; ov[pos] = vv[m]; }
                     ++pos;
-                    erow[coord] = 0.0f;
+                    if (!cleared) erow[coord] = 0.0f;
+                } else if (valid[m] && cleared) {
+                    erow[v.map[j + m]] = vv[m];
                 }
+            }
             eq_run += eq_total;
             out_run += send_total;
         }

@@ -309,7 +309,7 @@ def test_filter_bound_too_high_and_too_low_fall_back(ddef, oracle_mod):
     for h in (g, o):
         h.set_problem(np.ones(d, dtype=F32), zero, zero, 1, 0, 0.0)
     delta = 0.004
-    scales = [1.0, 1.0, 1e-3, 1e-3, 1e3, 1e3, 1.0, 0.5, 2.0, 1.0]
+    scales = [1.0, 1.0, 1e-3, 1e-3, 1e3, 1e3, 1.0, 0.5, 2.0, 1.0, 1.0, 1.0, 0.85, 0.85]
     fulls = []
     for step, sc in enumerate(scales):
         for i in range(n):
@@ -326,6 +326,9 @@ def test_filter_bound_too_high_and_too_low_fall_back(ddef, oracle_mod):
     assert fulls[0] == n and fulls[1] == n
     assert fulls[2] == 2 * n and fulls[3] == 2 * n
     assert fulls[4] == 3 * n and fulls[5] == 3 * n
+    # step 12: 15 % smaller -> fewer than k candidates, a good part of them above the expected
+    # threshold (already cleared from e by the accumulate pass and put back for the row search)
+    assert fulls[11] == fulls[10] and fulls[12] == fulls[11] + n
     g.close()
 
 
