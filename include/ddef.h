@@ -130,7 +130,12 @@ int ddef_load_grad(ddef_ctx* ctx, uint32_t worker, const float* host_g);
 int ddef_ef_compress(ddef_ctx* ctx, double delta, float lr);
 
 /* Dense sum of the n messages, U[j] = ((0 + Delta_0[j]) + Delta_1[j]) + ..., in worker
- * order, which makes the fp32 result reproducible. */
+ * order, which makes the fp32 result reproducible.  Sparse messages (n*k < d/64) are
+ * scatter-added into U here.  Denser ones are summed tile by tile in on-chip memory, and that
+ * sum is carried out by ddef_apply_delayed in the same pass that updates the model, so the
+ * dense U never travels through device memory; this call then only locates each tile's
+ * entries in the messages.  ddef_get_update returns the same U either way (it computes the
+ * deferred sum on its own when asked), from this call until the next ddef_ef_compress. */
 int ddef_aggregate(ddef_ctx* ctx);
 
 /* x_{t+1} = x_t - U / (float)n, stored as the next snapshot; t <- t + 1.  lr must be the
@@ -151,7 +156,7 @@ int ddef_set_model(ddef_ctx* ctx, const float* host_x);                 /* overw
 int ddef_get_error(ddef_ctx* ctx, uint32_t worker, float* host_e);
 int ddef_set_error(ddef_ctx* ctx, uint32_t worker, const float* host_e);
 int ddef_get_grad(ddef_ctx* ctx, uint32_t worker, float* host_g);
-int ddef_get_update(ddef_ctx* ctx, float* host_U);
+int ddef_get_update(ddef_ctx* ctx, float* host_U);   /* U of the last ddef_aggregate; valid until the next ddef_ef_compress */
 /* Last message of a worker: *k entries (0 on an empty iteration), ascending index.
  * host_idx / host_val may be NULL to query k only; otherwise they hold at least k items. */
 int ddef_get_message(ddef_ctx* ctx, uint32_t worker, uint32_t* host_idx, float* host_val,

@@ -22,12 +22,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
-    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_APPLY, SL_COPY_PROBE, SL_COUNT
+    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_msg_offsets", "k_aggregate_tiles", "k_apply", "k_copy_f4"};
+    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -88,6 +88,12 @@ struct ddef_ctx {
     bool u_dense = false;
     uint32_t* agg_off = nullptr;         // dense aggregation: [n][ld/kTile + 1] message offsets at tile boundaries
     uint32_t ntiles = 0;
+    // A dense aggregation is carried out by ddef_apply_delayed, fused with the model update;
+    // ddef_aggregate only locates the tiles' entries.  agg_deferred holds from ddef_aggregate to
+    // the next ddef_ef_compress (the messages are intact that long); U is computed on its own only
+    // when somebody asks for it (agg_in_U).
+    bool agg_deferred = false, agg_in_U = false;
+    uint32_t agg_slot = 0;
     Phase phase = PH_IDLE;
     bool problem_set = false, step_empty = true;
     float lr_step = 0.0f;
@@ -282,6 +288,16 @@ void clean_sparse_update(ddef_ctx* c) {
     LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
            c->U, (const uint32_t*)c->slot_idx(c->u_dirty_slot), c->msg_ld, (uint32_t)k, (uint32_t)c->d);
     c->u_dirty_k = 0;
+}
+
+// The deferred dense sum, written to U after all (a getter wants it).
+void materialize_update(ddef_ctx* c) {
+    if (!c->agg_deferred || c->agg_in_U) return;
+    LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles<false>, dim3(c->ntiles), dim3(256), c->U,
+           (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
+           (const uint32_t*)c->agg_off, c->ntiles, c->n, (const float*)nullptr, (float*)nullptr, 1.0f);
+    c->u_dense = true;
+    c->agg_in_U = true;
 }
 
 // After a dense aggregation: fills the row with zeros (only needed when the next aggregation
@@ -519,6 +535,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->full_selects = 0;
     c->u_dirty_k = 0;
     c->u_dense = false;
+    c->agg_deferred = false;
     return DDEF_OK;
 }
 
@@ -612,6 +629,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
     clean_sparse_update(c);
+    c->agg_deferred = false;               // the messages it would read are about to be replaced
     // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
     uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
     if (kb < k) kb = k;
@@ -704,10 +722,11 @@ int ddef_aggregate(ddef_ctx* c) {
     if (ka && !sparse_messages(c, ka)) {
         LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, c->n), dim3(256), idx,
                c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off);
-        LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles, dim3(c->ntiles), dim3(256), c->U, idx, val, c->msg_ld,
-               (const uint32_t*)c->agg_off, c->ntiles, c->n);
-        c->u_dense = true;
+        c->agg_deferred = true;
+        c->agg_in_U = false;
+        c->agg_slot = src;
     } else {
+        c->agg_deferred = false;
         clean_dense_update(c);
         if (ka) {
             const uint32_t k = (uint32_t)ka;
@@ -731,8 +750,15 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
     if (std::memcmp(&lr, &c->lr_step, sizeof(float)) != 0) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     const uint64_t quads = (c->d + 3) / 4;
-    LAUNCH(c, SL_APPLY, k_apply, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->slot(c->t),
-           c->U, c->slot(c->t + 1), (uint32_t)c->d, (float)c->n);
+    if (c->agg_deferred && !c->agg_in_U) {
+        LAUNCH(c, SL_AGGREGATE_APPLY, k_aggregate_tiles<true>, dim3(c->ntiles), dim3(256), (float*)nullptr,
+               (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
+               (const uint32_t*)c->agg_off, c->ntiles, c->n, (const float*)c->slot(c->t), c->slot(c->t + 1),
+               (float)c->n);
+    } else {
+        LAUNCH(c, SL_APPLY, k_apply, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->slot(c->t),
+               c->U, c->slot(c->t + 1), (uint32_t)c->d, (float)c->n);
+    }
     HIP_TRY(c, hipGetLastError());
     c->t += 1;
     c->phase = PH_IDLE;
@@ -810,6 +836,7 @@ int ddef_get_update(ddef_ctx* c, float* host_U) {
     if (rc) return rc;
     if (!host_U) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
+    materialize_update(c);
     return copy_row_out(c, c->U, host_U);
 }
 

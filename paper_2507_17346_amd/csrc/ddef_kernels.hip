@@ -929,11 +929,15 @@ __global__ __launch_bounds__(256) void k_msg_offsets(const uint32_t* __restrict_
     off[(uint64_t)w * (ntiles + 1u) + b] = lo;
 }
 
+// With kApply the tile is not stored but used at once: xn = x - tile / n (S5 fused into S4; x and
+// xn may be the same row), so the dense update never goes through HBM.
+template <bool kApply>
 __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
                                                          const uint32_t* __restrict__ idx,
                                                          const float* __restrict__ val, uint64_t msg_ld,
                                                          const uint32_t* __restrict__ off,
-                                                         uint32_t ntiles, uint32_t n) {
+                                                         uint32_t ntiles, uint32_t n,
+                                                         const float* x, float* xn, float nf) {
     __shared__ __attribute__((aligned(16))) float tile[kTile];
     __shared__ uint32_t lo_s[256], hi_s[256];
     const uint32_t b = blockIdx.x;
@@ -959,9 +963,29 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
             __syncthreads();
         }
     }
-    float4* out = reinterpret_cast<float4*>(U + (uint64_t)base);
-    for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) out[q] = reinterpret_cast<const float4*>(tile)[q];
+    if (kApply) {
+        const float4* xin = reinterpret_cast<const float4*>(x + (uint64_t)base);
+        float4* xout = reinterpret_cast<float4*>(xn + (uint64_t)base);
+        for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) {
+            const float4 xv = xin[q];
+            const float4 uv = reinterpret_cast<const float4*>(tile)[q];
+            float4 o;
+            o.x = xv.x - uv.x / nf;
+            o.y = xv.y - uv.y / nf;
+            o.z = xv.z - uv.z / nf;
+            o.w = xv.w - uv.w / nf;
+            xout[q] = o;
+        }
+    } else {
+        float4* out = reinterpret_cast<float4*>(U + (uint64_t)base);
+        for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) out[q] = reinterpret_cast<const float4*>(tile)[q];
+    }
 }
+
+template __global__ void k_aggregate_tiles<false>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
+                                                  uint32_t, uint32_t, const float*, float*, float);
+template __global__ void k_aggregate_tiles<true>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
+                                                 uint32_t, uint32_t, const float*, float*, float);
 
 // S5  x_{t+1} = x_t - U / n, written into the next ring slot (may alias x_t when the ring
 // has a single slot: element-wise, so in place is fine).  One quad per thread, single-wave
