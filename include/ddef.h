@@ -130,12 +130,11 @@ int ddef_load_grad(ddef_ctx* ctx, uint32_t worker, const float* host_g);
 int ddef_ef_compress(ddef_ctx* ctx, double delta, float lr);
 
 /* Dense sum of the n messages, U[j] = ((0 + Delta_0[j]) + Delta_1[j]) + ..., in worker
- * order, which makes the fp32 result reproducible.  Sparse messages (n*k < d/64) are
- * scatter-added into U here.  Denser ones are summed tile by tile in on-chip memory, and that
- * sum is carried out by ddef_apply_delayed in the same pass that updates the model, so the
- * dense U never travels through device memory; this call then only locates each tile's
- * entries in the messages.  ddef_get_update returns the same U either way (it computes the
- * deferred sum on its own when asked), from this call until the next ddef_ef_compress. */
+ * order, which makes the fp32 result reproducible.  The sum is formed tile by tile in on-chip
+ * memory, and that is carried out by ddef_apply_delayed in the same pass that updates the
+ * model, so the dense U never travels through device memory; this call only locates each
+ * tile's entries in the (index-ordered) messages.  ddef_get_update returns U all the same (it
+ * computes the sum on its own when asked), from this call until the next ddef_ef_compress. */
 int ddef_aggregate(ddef_ctx* ctx);
 
 /* x_{t+1} = x_t - U / (float)n, stored as the next snapshot; t <- t + 1.  lr must be the

@@ -21,13 +21,13 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_UNSCATTER, SL_FILL, SL_SCATTER_ADD,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_unscatter", "k_fill_f4", "k_scatter_add", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
+    "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -49,7 +49,6 @@ struct ddef_ctx {
     bool queue_form = false;
     uint32_t ring_slots = 1, q_slots = 1;
     uint32_t msg_slot = 0;               // slot of the messages ddef_ef_compress wrote last
-    uint32_t u_dirty_slot = 0;           // slot of the messages the last aggregate scattered into U
     std::vector<uint64_t> q_k;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
@@ -82,17 +81,14 @@ struct ddef_ctx {
     uint64_t pf_t = 0;
     uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
-    // U is all-zero except at the coordinates of the last aggregated messages (u_dirty_k each),
-    // or, after a dense aggregation, holds a full sum (u_dense) that the next one overwrites
-    uint64_t u_dirty_k = 0;
-    bool u_dense = false;
-    uint32_t* agg_off = nullptr;         // dense aggregation: [n][ld/kTile + 1] message offsets at tile boundaries
+    // The messages are summed tile by tile in LDS by ddef_apply_delayed, in the pass that updates
+    // the model; ddef_aggregate only locates each tile's entries (agg_off: [n][ld/kTile + 1]
+    // message offsets at the tile boundaries).  agg_deferred holds from ddef_aggregate to the next
+    // ddef_ef_compress (the messages are intact that long); U is computed on its own only when
+    // somebody asks for it (agg_in_U).  u_zero: U is known to be all-zero.
+    uint32_t* agg_off = nullptr;
     uint32_t ntiles = 0;
-    // A dense aggregation is carried out by ddef_apply_delayed, fused with the model update;
-    // ddef_aggregate only locates the tiles' entries.  agg_deferred holds from ddef_aggregate to
-    // the next ddef_ef_compress (the messages are intact that long); U is computed on its own only
-    // when somebody asks for it (agg_in_U).
-    bool agg_deferred = false, agg_in_U = false;
+    bool agg_deferred = false, agg_in_U = false, u_zero = true;
     uint32_t agg_slot = 0;
     Phase phase = PH_IDLE;
     bool problem_set = false, step_empty = true;
@@ -274,39 +270,23 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
            c->slot_val(c->msg_slot), c->msg_ld, k);
 }
 
-// A scattered 4-byte access costs far more than its 4 bytes (measured: about 190 bytes of fill
-// bandwidth each), so messages are summed by scatter-add, and U cleared at the same coordinates
-// afterwards, only while n*k < d/64; denser messages are summed tile by tile into a U that is
-// overwritten as a whole.
-bool sparse_messages(const ddef_ctx* c, uint64_t k) { return k * c->n * 64u < c->d; }
-
-// After a scatter-add: puts U back to all-zero by clearing the coordinates the messages named.
-// Must run before those message buffers are overwritten or reallocated.
-void clean_sparse_update(ddef_ctx* c) {
-    if (!c->u_dirty_k) return;
-    const uint64_t k = c->u_dirty_k;
-    LAUNCH(c, SL_UNSCATTER, k_unscatter, dim3(blocks_for(c, (k + 255u) / 256u, c->n, 8), c->n), dim3(256),
-           c->U, (const uint32_t*)c->slot_idx(c->u_dirty_slot), c->msg_ld, (uint32_t)k, (uint32_t)c->d);
-    c->u_dirty_k = 0;
-}
-
-// The deferred dense sum, written to U after all (a getter wants it).
+// The sum of the messages named by the last ddef_aggregate, written to U (a getter wants it;
+// the iteration itself never needs U in memory).
 void materialize_update(ddef_ctx* c) {
     if (!c->agg_deferred || c->agg_in_U) return;
     LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles<false>, dim3(c->ntiles), dim3(256), c->U,
            (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
            (const uint32_t*)c->agg_off, c->ntiles, c->n, (const float*)nullptr, (float*)nullptr, 1.0f);
-    c->u_dense = true;
+    c->u_zero = false;
     c->agg_in_U = true;
 }
 
-// After a dense aggregation: fills the row with zeros (only needed when the next aggregation
-// does not overwrite it).
-void clean_dense_update(ddef_ctx* c) {
-    if (!c->u_dense) return;
+// U = 0, for an aggregation without messages.
+void zero_update(ddef_ctx* c) {
+    if (c->u_zero) return;
     const uint64_t quads = c->ld / 4u;
     LAUNCH(c, SL_FILL, k_fill_f4, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->U, quads);
-    c->u_dense = false;
+    c->u_zero = true;
 }
 
 // Gradient generator inputs: snapshot xs and the iteration number `key` the noise is drawn for.
@@ -533,8 +513,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
-    c->u_dirty_k = 0;
-    c->u_dense = false;
+    c->u_zero = true;
     c->agg_deferred = false;
     return DDEF_OK;
 }
@@ -628,7 +607,6 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         return DDEF_OK;
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
-    clean_sparse_update(c);
     c->agg_deferred = false;               // the messages it would read are about to be replaced
     // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
     uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
@@ -708,7 +686,6 @@ int ddef_aggregate(ddef_ctx* c) {
     if (rc) return rc;
     if (c->phase != PH_COMPRESSED) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
-    clean_sparse_update(c);
     // ring form: the messages of this iteration; queue form: the ones sent tau iterations ago,
     // nothing while t < tau (Delta_{t-tau} = 0 by convention, Section 3.2)
     uint32_t src = c->msg_slot;
@@ -717,26 +694,15 @@ int ddef_aggregate(ddef_ctx* c) {
         src = (uint32_t)((c->t + c->q_slots - c->tau) % c->q_slots);
         ka = c->t >= c->tau ? c->q_k[src] : 0;
     }
-    const uint32_t* idx = c->slot_idx(src);
-    const float* val = c->slot_val(src);
-    if (ka && !sparse_messages(c, ka)) {
-        LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, c->n), dim3(256), idx,
-               c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off);
+    if (ka) {
+        LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, c->n), dim3(256),
+               (const uint32_t*)c->slot_idx(src), c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off);
         c->agg_deferred = true;
         c->agg_in_U = false;
         c->agg_slot = src;
     } else {
         c->agg_deferred = false;
-        clean_dense_update(c);
-        if (ka) {
-            const uint32_t k = (uint32_t)ka;
-            const uint32_t gx = blocks_for(c, (k + 255u) / 256u, 1, 16);
-            for (uint32_t i = 0; i < c->n; ++i)
-                LAUNCH(c, SL_SCATTER_ADD, k_scatter_add, dim3(gx), dim3(256), c->U, idx + (uint64_t)i * c->msg_ld,
-                       val + (uint64_t)i * c->msg_ld, k, (uint32_t)c->d);
-            c->u_dirty_k = ka;
-            c->u_dirty_slot = src;
-        }
+        zero_update(c);
     }
     HIP_TRY(c, hipGetLastError());
     c->phase = PH_AGGREGATED;

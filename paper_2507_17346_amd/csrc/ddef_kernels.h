@@ -84,14 +84,12 @@ __global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint3
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,
                              float* msg_val, uint64_t msg_ld, uint32_t k);
-__global__ void k_scatter_add(float* U, const uint32_t* idx, const float* val, uint32_t k, uint32_t d);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
 __global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off);
 template <bool kApply>
 __global__ void k_aggregate_tiles(float* U, const uint32_t* idx, const float* val, uint64_t msg_ld,
                                   const uint32_t* off, uint32_t ntiles, uint32_t n, const float* x, float* xn,
                                   float nf);
-__global__ void k_unscatter(float* U, const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t d);
 __global__ void k_fill_f4(float* p, uint64_t quads);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);
 

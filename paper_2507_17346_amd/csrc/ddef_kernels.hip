@@ -611,6 +611,21 @@ __device__ __forceinline__ View view_of(const SelViews& vs, const SelState* sel,
     return v;
 }
 
+// One count per lane with `on` into an LDS histogram.  The entries of a candidate view are
+// close in magnitude, so on the upper digits nearly every lane of a wave names the same bin,
+// and LDS atomics on one address are served one after another: the lanes that share the
+// first active lane's bin are counted with a ballot and added once; the rest add singly.
+// All lanes of the wave must call this together.
+__device__ __forceinline__ void hist_add(uint32_t* h, uint32_t digit, bool on) {
+    const uint64_t todo = __ballot(on);
+    if (todo == 0ull) return;
+    const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
+    const uint32_t lead_digit = (uint32_t)__builtin_amdgcn_readlane((int)digit, (int)leader);
+    const uint64_t same = __ballot(on && digit == lead_digit);
+    if (lane_id() == leader) atomicAdd(&h[lead_digit], (uint32_t)__popcll(same));
+    if (on && digit != lead_digit) atomicAdd(&h[digit], 1u);
+}
+
 // Histogram of one digit over each worker's view.  Level 0 builds one histogram shared by
 // both ranks; levels 1, 2 build one per rank, over the entries whose higher bits match that
 // rank's prefix.  hist layout: [worker][2][2048].
@@ -620,27 +635,31 @@ __global__ __launch_bounds__(256) void k_digit_hist(SelViews vs, const SelState*
     const uint32_t w = blockIdx.y;
     const View v = view_of(vs, sel, w);
     const uint32_t quads = (v.count + 3u) >> 2;
-    if (blockIdx.x * blockDim.x >= quads) return;         // nothing for this block (uniform)
+    // A short view is shared among few blocks (at least 16 quads per thread): every block ends
+    // with device atomics into the worker's histogram, where nearly all of a candidate view
+    // falls into a handful of bins, and atomics on one address are served one after another.
+    uint32_t used = (quads + 16u * blockDim.x - 1u) / (16u * blockDim.x);
+    used = used < gridDim.x ? used : gridDim.x;
+    if (blockIdx.x >= used) return;                        // nothing for this block (uniform)
     const uint32_t lo = lvl_lo(level), hi = lvl_hi(level), bins = lvl_bins(level);
     const int nrank = level == 0 ? 1 : 2;
     for (uint32_t b = threadIdx.x; b < 2048u; b += blockDim.x) { h[0][b] = 0; h[1][b] = 0; }
     __syncthreads();
     const uint32_t pre0 = sel[w].prefix[0] >> hi, pre1 = sel[w].prefix[1] >> hi;
-    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += used * blockDim.x) {
         const float4 x = reinterpret_cast<const float4*>(v.row)[q];
         const float vv[4] = {x.x, x.y, x.z, x.w};
         const uint32_t j = q << 2;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (j + c < v.count) {
-                const uint32_t key = mag_key(vv[c]);
-                const uint32_t digit = (key >> lo) & (bins - 1u);
-                if (level == 0) {
-                    atomicAdd(&h[0][digit], 1u);
-                } else {
-                    if ((key >> hi) == pre0) atomicAdd(&h[0][digit], 1u);
-                    if ((key >> hi) == pre1) atomicAdd(&h[1][digit], 1u);
-                }
+            const bool in = j + c < v.count;
+            const uint32_t key = mag_key(vv[c]);
+            const uint32_t digit = (key >> lo) & (bins - 1u);
+            if (level == 0) {
+                hist_add(h[0], digit, in);
+            } else {
+                hist_add(h[0], digit, in && (key >> hi) == pre0);
+                hist_add(h[1], digit, in && (key >> hi) == pre1);
             }
         }
     }
@@ -892,21 +911,9 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
 }
 
 // ------------------------------------------------------------------------------------
-// S4  U += Delta_i for one worker (launched once per worker, in worker order, on one
-// stream: indices inside one message are distinct, so plain read-modify-write is exact
-// and the summation order is the worker order).
+// S4  U = sum_i Delta_i in worker order (Algorithm 1, server side), tile by tile.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_scatter_add(float* __restrict__ U,
-                                                     const uint32_t* __restrict__ idx,
-                                                     const float* __restrict__ val, uint32_t k,
-                                                     uint32_t d) {
-    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
-        const uint32_t j = idx[m];
-        if (j < d) U[j] = U[j] + val[m];
-    }
-}
-
-// S4, dense messages: the same sum, tile by tile.  k_msg_offsets finds, for every worker and
+// k_msg_offsets finds, for every worker and
 // every boundary b * kTile, how many of the worker's (ascending) indices lie below it; then one
 // block per tile of kTile coordinates adds the workers' entries of its range into a tile in
 // LDS, worker after worker (a barrier between workers keeps the summation order; indices
@@ -956,6 +963,7 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
             const uint32_t* ri = idx + (uint64_t)(w0 + i) * msg_ld;
             const float* rv = val + (uint64_t)(w0 + i) * msg_ld;
             const uint32_t hi = hi_s[i];
+            if (lo_s[i] == hi) continue;                   // same for the whole block
             for (uint32_t m = lo_s[i] + threadIdx.x; m < hi; m += 256u) {
                 const uint32_t at = ri[m] - base;          // < kTile by the choice of lo, hi
                 tile[at] = tile[at] + rv[m];
@@ -1002,17 +1010,6 @@ __global__ __launch_bounds__(64) void k_apply(const float* x, const float* __res
     o.z = xv.z - uv.z / nf;
     o.w = xv.w - uv.w / nf;
     reinterpret_cast<float4*>(xn)[q] = o;
-}
-
-// U[j] <- +0 at every coordinate of the last messages (all workers, grid (gx, n)): puts U
-// back to all-zero without touching the other d - n*k entries.
-__global__ __launch_bounds__(256) void k_unscatter(float* __restrict__ U, const uint32_t* __restrict__ idx,
-                                                   uint64_t msg_ld, uint32_t k, uint32_t d) {
-    const uint32_t* row = idx + (uint64_t)blockIdx.y * msg_ld;
-    for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
-        const uint32_t j = row[m];
-        if (j < d) U[j] = 0.0f;
-    }
 }
 
 // Dense zero fill of a row (one quad per thread, single-wave blocks).
