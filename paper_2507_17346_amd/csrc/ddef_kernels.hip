@@ -635,18 +635,13 @@ __global__ __launch_bounds__(256) void k_digit_hist(SelViews vs, const SelState*
     const uint32_t w = blockIdx.y;
     const View v = view_of(vs, sel, w);
     const uint32_t quads = (v.count + 3u) >> 2;
-    // A short view is shared among few blocks (at least 16 quads per thread): every block ends
-    // with device atomics into the worker's histogram, where nearly all of a candidate view
-    // falls into a handful of bins, and atomics on one address are served one after another.
-    uint32_t used = (quads + 16u * blockDim.x - 1u) / (16u * blockDim.x);
-    used = used < gridDim.x ? used : gridDim.x;
-    if (blockIdx.x >= used) return;                        // nothing for this block (uniform)
+    if (blockIdx.x * blockDim.x >= quads) return;         // nothing for this block (uniform)
     const uint32_t lo = lvl_lo(level), hi = lvl_hi(level), bins = lvl_bins(level);
     const int nrank = level == 0 ? 1 : 2;
     for (uint32_t b = threadIdx.x; b < 2048u; b += blockDim.x) { h[0][b] = 0; h[1][b] = 0; }
     __syncthreads();
     const uint32_t pre0 = sel[w].prefix[0] >> hi, pre1 = sel[w].prefix[1] >> hi;
-    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += used * blockDim.x) {
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
         const float4 x = reinterpret_cast<const float4*>(v.row)[q];
         const float vv[4] = {x.x, x.y, x.z, x.w};
         const uint32_t j = q << 2;
