@@ -280,8 +280,15 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
     bool any = false;
 #pragma unroll
     for (int c = 0; c < 4; ++c) { f[c] = (j + c < d) && mag_key(pv[c]) >= L; any |= f[c]; }
+    // the dense store goes out first, already with +0 at the candidates expected to be sent
+    // (a group that then gets no slots stores its values once more, below)
+    if (j < d) {
+        float ov[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ov[c] = (f[c] && mag_key(pv[c]) >= H) ? 0.0f : pv[c];
+        store_stream4(ep, ov);
+    }
     uint32_t first = 0, total = 0;
-    bool placed = false;                       // the group's candidates are in the buffer
     if (__ballot(any)) {                       // most groups hold no candidate at all
         uint32_t below = 0;
 #pragma unroll
@@ -297,9 +304,9 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         got = __shfl(got, 0, 64);
         if (got + total > sub_cap) {
             if (lane == 0) overflow[w] = 1u;
-            total = 0;                         // nothing recorded for this group
+            total = 0;                         // nothing recorded for this group:
+            if (j < d) store_stream4(ep, pv);  // all its entries stay in e (same lane, same address: in order)
         } else {
-            placed = true;
             first = sub * sub_cap + got;
             uint2* cw = cand + (uint64_t)w * cap;
             uint32_t pos = first + below;
@@ -307,12 +314,6 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
             for (int c = 0; c < 4; ++c)
                 if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
         }
-    }
-    if (j < d) {
-        float ov[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) ov[c] = (placed && f[c] && mag_key(pv[c]) >= H) ? 0.0f : pv[c];
-        store_stream4(ep, ov);
     }
     if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
 }
