@@ -21,13 +21,13 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_FILL,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_REBOUND, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
+    "k_rebound", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -65,6 +65,7 @@ struct ddef_ctx {
     float* sorted_val = nullptr;
     uint64_t cap = 0;
     bool have_bound = false;
+    uint64_t bound_k = 0;                // the k the bound was placed for
     int compressor = DDEF_COMPRESSOR_TOPK;
     // gradient prefetch: the gradient of iteration t+1 only needs x_{t+1-tau}, which exists as soon
     // as iteration t starts (tau >= 1), so it is generated on a second stream into a second buffer
@@ -648,6 +649,9 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     // the filter needs a bound from an earlier selection and pays off only for sparse messages
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
+    if (use_filter && c->bound_k != k)
+        LAUNCH(c, SL_REBOUND, k_rebound, dim3((n + 255u) / 256u), dim3(256), (const SelState*)c->sel, n,
+               (uint32_t)c->bound_k, (uint32_t)k, (uint32_t)kb, bound, zero_at);
     const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
     if (c->grad_pending) {
         LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
@@ -674,6 +678,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     enqueue_select(c, (uint32_t)k, (uint32_t)kb);
     c->have_bound = true;
+    c->bound_k = k;
     HIP_TRY(c, hipGetLastError());
     c->k_step = k;
     c->q_k[c->msg_slot] = k;

@@ -757,8 +757,8 @@ __global__ __launch_bounds__(256) void k_chunk_count(SelViews vs, const SelState
 // assuming the count keeps growing towards smaller magnitudes at the rate seen between T and
 // the old bound.  The error buffers drift (they ramp up while the model is far from its
 // optimum and relax later), so the bound is then moved by the factor the threshold is
-// expected to move by: linear extrapolation of the last two thresholds,
-// T_next / T = 2 - T_prev / T.  Too high a bound (fewer than k caught) and too low a bound
+// expected to move by: linear continuation of the last two thresholds while they rise,
+// T_next / T = 2 - T_prev / T, geometric while they fall, T_next / T = T / T_prev.  Too high a bound (fewer than k caught) and too low a bound
 // (buffer overflow) both cost a whole-row search, and the target kb = 2.5 k sits in the
 // middle of the usable window [k, 7.5 k], so the trend is followed in full.  The bound only decides which search runs; the selection
 // itself is exact either way.
@@ -782,14 +782,25 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
         }
     }
     if (sel[w].k_prev == k && sel[w].T_prev != 0u && T != 0u && T < 0x7f800000u && nb != 0u) {
-        float ratio = 2.0f - __uint_as_float(sel[w].T_prev) / __uint_as_float(T);
+        // rising thresholds ramp (linear continuation: T_next / T = 2 - T_prev / T), falling ones
+        // decay (after k grew the accumulated residual drains by a constant factor per
+        // iteration: T_next / T = T / T_prev)
+        const float back = __uint_as_float(sel[w].T_prev) / __uint_as_float(T);
+        float ratio = back <= 1.0f ? 2.0f - back : 1.0f / back;
         // a jump is not a trend: leave the bound where the last selection put it.  (A linear
         // ramp from the second to the third selection has ratio 1.5 and is still followed.)
-        if (ratio < 0.75f || ratio > 1.5f) ratio = 1.0f;
+        if (ratio < 0.4f || ratio > 1.5f) ratio = 1.0f;
         const float moved = __uint_as_float(nb) * ratio;
         if (moved > 0.0f && moved < 3.0e38f) nb = __float_as_uint(moved);
         const float moved_T = __uint_as_float(T) * ratio;
         if (moved_T > 0.0f && moved_T < 3.0e38f) nz = __float_as_uint(moved_T);
+    }
+    // what the last selection measured, for k_rebound: the pattern sel[w].next_bound sits at this rank
+    {
+        const uint32_t view = sel[w].active == 0u ? cand_total[w] : 0xffffffffu;
+        sel[w].nb_rank = kb < view ? kb : view;
+        sel[w].trend = (sel[w].next_bound != 0u && nb != 0u)
+                           ? __uint_as_float(nb) / __uint_as_float(sel[w].next_bound) : 1.0f;
     }
     sel[w].T_prev = T;
     sel[w].k_prev = k;
@@ -797,6 +808,43 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
     bound[w] = nb;
     zero_at[w] = nz;
     overflow[w] = 0u;
+}
+
+// k changed since the last selection (Algorithm 2 re-chooses delta): the bound was placed for
+// the old k.  The magnitudes of e + lr*g are distributed much as in the last iteration,
+// whatever k is, and the last selection measured two points of that distribution's tail: the
+// pattern T at rank k_old and the pattern B at rank rank_B > k_old.
+//   kb_new <= k_old:  the bound goes to the threshold expected for the old k, which catches
+//     about k_old >= kb_new entries (the buffers still have room for the old k's candidates).
+//     Above T the tail cannot be extrapolated: it was cut off when the last message was sent.
+//   k_old < kb_new <= rank_B:  a power law through the two points (ln count linear in
+//     ln magnitude), evaluated between them.
+//   kb_new > rank_B:  the same law continued below B with 0.4 times its exponent (towards the
+//     bulk the tail flattens; measured on the Student-t workload a tenfold k needed about that).
+// The factor the old bound carried for the threshold's trend is kept.  Nothing is cleared ahead
+// of time in this iteration (zero_at = infinity).  As always the bound only decides which search
+// runs.  One thread per worker.
+__global__ __launch_bounds__(256) void k_rebound(const SelState* __restrict__ sel, uint32_t n, uint32_t k_old,
+                                                 uint32_t k_new, uint32_t kb_new,
+                                                 uint32_t* __restrict__ bound, uint32_t* __restrict__ zero_at) {
+    const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= n) return;
+    const uint32_t expected_T = zero_at[w];
+    zero_at[w] = 0x7f800000u;
+    if (kb_new <= k_old) {
+        if (expected_T != 0u && expected_T < 0x7f800000u) bound[w] = expected_T;
+        return;
+    }
+    const uint32_t T = sel[w].T, B = sel[w].next_bound, rank_B = sel[w].nb_rank;
+    if (T == 0u || B == 0u || B >= T || T >= 0x7f800000u || rank_B <= k_old) return;
+    const float lt = __logf(__uint_as_float(T)), lb = __logf(__uint_as_float(B));
+    const float slope = (__logf((float)rank_B) - __logf((float)k_old)) / (lt - lb);   // -d ln count / d ln x
+    if (!(slope > 0.05f && slope < 400.0f)) return;
+    float ln_x;
+    if (kb_new <= rank_B) ln_x = lt - (__logf((float)kb_new) - __logf((float)k_old)) / slope;
+    else ln_x = lb - (__logf((float)kb_new) - __logf((float)rank_B)) / (0.4f * slope);
+    const float x = __expf(ln_x) * sel[w].trend;
+    if (x > 0.0f && x < 3.0e38f) bound[w] = __float_as_uint(x);
 }
 
 // One block of 1024 threads per worker walks the chunk counts in order and turns them into

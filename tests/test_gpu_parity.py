@@ -206,6 +206,22 @@ def test_adaptive_schedule_changing_delta_and_tau(ddef, oracle_mod):
     g.close()
 
 
+def test_changing_k_keeps_the_candidate_filter(ddef, oracle_mod):
+    """delta moves by factors of 3 to 10 in both directions (Algorithm 2 re-chooses it): the bound
+    is re-placed for the new k from the tail the last selection measured, so the filter keeps
+    carrying the selections; whatever search runs, the result equals the oracle's."""
+    w = workloads.get("C3", d=2_000_000, n=2)
+    g, o, _ = make_pair(ddef, oracle_mod, w, tau=0, tau_max=0, threads=2)
+    schedule = [0.001] * 6 + [0.01] * 4 + [0.001] * 4 + [0.003] * 3 + [0.0005] * 3
+    for t, delta in enumerate(schedule):
+        g.step(delta, w.lr); o.step(delta, w.lr)
+        assert_step_state_equal(g, o, w.n, check_grad=False, what=("k change", t, delta))
+        assert_model_equal(g, o, what=("k change", t))
+    # the first two iterations search the rows (no bound, then no trend); the changes of k must not
+    assert g.full_select_count() <= 2 * w.n + w.n, g.full_select_count()
+    g.close()
+
+
 # ---- checkpoint hooks and teacher forcing ---------------------------------------------------------
 def test_teacher_forced_step(ddef, oracle_mod):
     w = workloads.get("C1", d=30_000, n=2)
