@@ -154,6 +154,8 @@ def test_compress_ties_across_chunks(ddef, oracle_mod):
     ("C3", 150_001, 8, 3, 0.001, 9),
     ("C4", 131_072, 4, 1, 0.1, 6),
     ("C1", 4_096, 3, 5, 1.0, 9),
+    ("C1", 9_001, 300, 1, 0.02, 5),        # more workers than one batch of the tile sum holds
+    ("C1", 3, 2, 0, 0.5, 4),
 ])
 def test_trajectory_free_running(ddef, oracle_mod, name, d, n, tau, delta, steps):
     w = workloads.get(name, d=d, n=n)
