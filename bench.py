@@ -241,6 +241,16 @@ def main():
                 "algorithmic_bytes_per_launch": algo_bytes,
                 "avg_launch_ms": kernels[dominant]["avg_ms"]}
 
+    if dominant == "k_ef_filter_fused" and w.noise_kind in VALU_PER_DRAW:
+        # with the generator fused in, the pass is bound by vector issue like k_grad: lane-instructions
+        # per element = k_grad's per draw + k_ef_filter's 67 wave instructions per 256 coordinates
+        per_elem_instr = VALU_PER_DRAW[w.noise_kind] + 67.0 * 64.0 / 256.0
+        rate = per_elem_instr * elems / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": dominant, "achieved": rate, "peak": VALU_NOMINAL_TINSTR,
+                    "unit": "T lane-instr/s", "frac": rate / VALU_NOMINAL_TINSTR, "traffic": None,
+                    "lane_instr_per_element": per_elem_instr, "avg_launch_ms": kernels[dominant]["avg_ms"],
+                    "hbm_GBps": 4.0 * elems * 2 / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9}
+
     # the gradient generator is bound by vector ALU work (Philox + Box-Muller), not by HBM: report
     # its rate in draws and in vector lane-instructions (count per draw from the hardware counter
     # SQ_INSTS_VALU, profiles/k_grad_C3_valu.txt) next to the nominal plain-VALU issue rate
