@@ -130,6 +130,8 @@ def main():
                     help="1: generate the next iteration's gradient on a second stream meanwhile")
     ap.add_argument("--fuse-grad", type=int, default=0,
                     help="1: generate the gradient inside the accumulate pass (never stored)")
+    ap.add_argument("--graph", type=int, default=0,
+                    help="1: steady iterations are replayed from one recorded HIP graph (ddef_step)")
     ap.add_argument("--queue-form", type=int, default=0,
                     help="1: server state as a message queue (one model, tau_max+1 queued messages) "
                          "instead of the snapshot ring; same iterates for constant tau")
@@ -161,6 +163,7 @@ def main():
     ctx.set_compressor(compressor)
     ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
     ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
+    ctx.set_option(binding.OPT_GRAPH, 1 if args.graph else 0)
 
     state = {"tau": None}
 
@@ -279,7 +282,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring",
+                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,

@@ -142,6 +142,17 @@ int ddef_aggregate(ddef_ctx* ctx);
  * feedback, as in Algorithm 1; it is checked, not applied a second time), else EINVAL. */
 int ddef_apply_delayed(ddef_ctx* ctx, float lr);
 
+/* One whole iteration: the four calls above in order, with the same results and errors.
+ * With DDEF_OPT_GRAPH set, a steady iteration (ring form, Top-k, t >= tau, the same k, lr and
+ * tau as the iteration before, no buffer to grow, profiling and prefetch off) is recorded once
+ * as a HIP graph and replayed from then on: one graph launch instead of some sixteen kernel
+ * launches, which is what small problems are bound by.  Inside the graph the iteration number
+ * is read from device memory, so nothing in it changes from replay to replay.  Any change of
+ * k, lr, tau, an option, the stream or the problem drops the recording; the next steady
+ * iteration records a new one.  Iterations that do not qualify run the four calls as usual. */
+int ddef_step(ddef_ctx* ctx, double delta, float lr);
+int ddef_graph_replays(ddef_ctx* ctx, uint64_t* count);   /* iterations served by a replay so far */
+
 /* Wait for the context's stream.  Also reports what the kernels flagged meanwhile:
  * DDEF_ENONFINITE when some e + lr*g was Inf or NaN (the method needs finite values; the
  * context then refuses further work until ddef_set_problem), DDEF_EINTERNAL when a device-side
@@ -234,6 +245,7 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                                   * kernels share the chip poorly (the whole step gains about
                                   * 10 %, the streaming pass loses most of its bandwidth while
                                   * they overlap).                                              */
+#define DDEF_OPT_GRAPH 5     /* 1: ddef_step records steady iterations as a HIP graph and replays it */
 #define DDEF_OPT_FUSE_GRAD 4 /* 1: ddef_grad launches nothing; ddef_ef_compress generates the gradient
                               * inside the accumulate pass, so it never touches HBM (8 bytes less per
                               * worker and element).  Results are unchanged.  ddef_get_grad then works

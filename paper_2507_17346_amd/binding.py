@@ -16,7 +16,7 @@ from . import build as _build
 OK, EINVAL, ESTATE, ENOMEM, EHIP, ENONFINITE, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
 COMPRESSOR_TOPK, COMPRESSOR_RANDK = 0, 1
 NOISE_NONE, NOISE_GAUSS, NOISE_STUDENT_T3 = 0, 1, 2
-OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16, OPT_PREFETCH_GRAD, OPT_FUSE_GRAD = 1, 2, 3, 4
+OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16, OPT_PREFETCH_GRAD, OPT_FUSE_GRAD, OPT_GRAPH = 1, 2, 3, 4, 5
 
 _u32p, _f32p, _u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
 _ctx = C.c_void_p
@@ -36,6 +36,8 @@ SIGNATURES = {
     "ddef_load_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
     "ddef_aggregate": (C.c_int, [_ctx]),
+    "ddef_step": (C.c_int, [_ctx, C.c_double, C.c_float]),
+    "ddef_graph_replays": (C.c_int, [_ctx, _u64p]),
     "ddef_apply_delayed": (C.c_int, [_ctx, C.c_float]),
     "ddef_sync": (C.c_int, [_ctx]),
     "ddef_step_index": (C.c_int, [_ctx, _u64p]),
@@ -266,10 +268,12 @@ class Context:
         self._check(self._lib.ddef_apply_delayed(self._h, float(lr)), "ddef_apply_delayed")
 
     def step(self, delta: float, lr: float):
-        self.grad()
-        self.ef_compress(delta, lr)
-        self.aggregate()
-        self.apply_delayed(lr)
+        self._check(self._lib.ddef_step(self._h, float(delta), float(lr)), "ddef_step")
+
+    def graph_replays(self) -> int:
+        n = C.c_uint64()
+        self._check(self._lib.ddef_graph_replays(self._h, C.byref(n)), "ddef_graph_replays")
+        return int(n.value)
 
     def sync(self):
         self._check(self._lib.ddef_sync(self._h), "ddef_sync")

@@ -22,12 +22,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_REBOUND, SL_FILL,
-    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_APPLY, SL_COPY_PROBE, SL_COUNT
+    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_rebound", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_apply", "k_copy_f4"};
+    "k_rebound", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -102,6 +102,17 @@ struct ddef_ctx {
     int sticky = DDEF_OK;
     uint64_t full_selects = 0;
     int64_t opt_force_full = 0, opt_slack_x16 = 40;
+    // ddef_step as a captured graph: the launches of one steady iteration, replayed while
+    // (k, lr, tau) stay the same.  Inside the graph the iteration number comes from t_dev.
+    int64_t opt_graph = 0;
+    uint64_t* t_dev = nullptr;
+    uint64_t t_dev_value = ~0ull;        // what *t_dev holds (host's record)
+    hipGraphExec_t graph_exec = nullptr;
+    bool capturing = false;
+    uint64_t graph_k = 0;
+    uint32_t graph_lr_bits = 0, graph_tau = 0;
+    uint64_t graph_full_selects = 0;     // whole-row selections per replayed iteration
+    uint64_t graph_replays = 0;
     bool profiling = false;
     std::vector<ProfRecord> pending;
     std::vector<hipEvent_t> free_events;
@@ -197,8 +208,35 @@ uint32_t blocks_for(ddef_ctx* c, uint64_t items_per_row_blocks, uint32_t rows, u
     return (uint32_t)(b < 1 ? 1 : b);
 }
 
+// The captured iteration is no longer valid (a pointer, an option or the problem changed).
+void drop_graph(ddef_ctx* c) {
+    if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
+}
+
+// Candidate slots per worker that a selection of k with candidate target kb wants:
+// three times the target while messages are sparse, twice otherwise,
+// at least 32 slots in each of the kSubs parts of the buffer, plus one whole 256-entry group
+// per part (a part fills unevenly when d is small or the selection is dense); never more than
+// every coordinate can need
+uint64_t candidate_capacity(const ddef_ctx* c, uint64_t k, uint64_t kb) {
+    const bool sparse = k * 32u <= c->d;
+    uint64_t want = (sparse ? 3u : 2u) * kb;
+    if (want < 32u * kSubs) want = 32u * kSubs;
+    if (want > c->ld) want = c->ld;
+    return ((want + 4095u) & ~(uint64_t)4095u) + 256u * kSubs;
+}
+
+// candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
+uint64_t candidate_target(const ddef_ctx* c, uint64_t k) {
+    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
+    if (kb < k) kb = k;
+    if (kb > c->d) kb = c->d;
+    return kb;
+}
+
 int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
     if (k > c->msg_ld) {
+        drop_graph(c);
         // longer rows; the messages held so far (queued ones in queue form) move over
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         const uint64_t len = (k + 1023u) & ~(uint64_t)1023u;
@@ -223,16 +261,9 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
         if (c->msg_val) (void)hipFree(c->msg_val);
         c->msg_idx = idx; c->msg_val = val; c->msg_ld = len;
     }
-    // room for the candidates: three times the target while messages are sparse, twice otherwise,
-    // at least 32 slots in each of the kSubs parts of the buffer, plus one whole 256-entry group
-    // per part (a part fills unevenly when d is small or the selection is dense); never more than
-    // every coordinate can need
-    const bool sparse = k * 32u <= c->d;
-    uint64_t want = (sparse ? 3u : 2u) * kb;
-    if (want < 32u * kSubs) want = 32u * kSubs;
-    if (want > c->ld) want = c->ld;
-    want = ((want + 4095u) & ~(uint64_t)4095u) + 256u * kSubs;
+    const uint64_t want = candidate_capacity(c, k, kb);
     if (want > c->cap) {
+        drop_graph(c);
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         if (c->cand) (void)hipFree(c->cand);
         if (c->sorted_idx) (void)hipFree(c->sorted_idx);
@@ -277,7 +308,7 @@ void materialize_update(ddef_ctx* c) {
     if (!c->agg_deferred || c->agg_in_U) return;
     LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles<false>, dim3(c->ntiles), dim3(256), c->U,
            (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
-           (const uint32_t*)c->agg_off, c->ntiles, c->n, (const float*)nullptr, (float*)nullptr, 1.0f);
+           (const uint32_t*)c->agg_off, c->ntiles, c->n, ModelRows{nullptr, nullptr, nullptr, nullptr, 1u, 0u}, 1.0f);
     c->u_zero = false;
     c->agg_in_U = true;
 }
@@ -292,8 +323,11 @@ void zero_update(ddef_ctx* c) {
 
 // Gradient generator inputs: snapshot xs and the iteration number `key` the noise is drawn for.
 GradSource grad_source(const ddef_ctx* c, uint64_t key, const float* xs) {
-    return GradSource{c->lambda, c->xstar, xs, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-                      (uint32_t)key, (uint32_t)(key >> 32), c->noise_kind, c->noise_scale, c->zeta};
+    GradSource s{c->lambda, c->xstar, xs, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+                 (uint32_t)key, (uint32_t)(key >> 32), c->noise_kind, c->noise_scale, c->zeta,
+                 nullptr, c->ring, c->ring_slots, c->tau, c->ld};
+    if (c->capturing) s.t_dev = c->t_dev;          // ring form only: key = t, snapshot = slot(t - tau)
+    return s;
 }
 
 void enqueue_grad(ddef_ctx* c, hipStream_t stream, float* dest, uint64_t key, const float* xs,
@@ -437,6 +471,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
         {(void**)&c->filt, (size_t)6 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
         {(void**)&c->agg_off, (size_t)n * (c->ntiles + 1u) * 4},
+        {(void**)&c->t_dev, 8},
     };
     for (const Want& w : wants) {
         err = hipMalloc(w.p, w.bytes);
@@ -461,13 +496,14 @@ int ddef_destroy(ddef_ctx* c) {
     if (!c) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     if (c->stream) (void)hipStreamSynchronize(c->stream);
+    drop_graph(c);
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     if (c->ev_applied) (void)hipEventDestroy(c->ev_applied);
     if (c->ev_prefetched) (void)hipEventDestroy(c->ev_prefetched);
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->bitmap, c->g_next, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->bitmap, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -483,6 +519,7 @@ int ddef_set_stream(ddef_ctx* c, void* hip_stream) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     rc = drop_prefetch(c);
     if (rc) return rc;
+    drop_graph(c);
     c->stream = hip_stream ? (hipStream_t)hip_stream : c->own_stream;
     return DDEF_OK;
 }
@@ -511,6 +548,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->filt, 0, (size_t)6 * c->n * 4));
     HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
     c->have_bound = false;
+    drop_graph(c);
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
@@ -525,6 +563,7 @@ int ddef_set_compressor(ddef_ctx* c, int kind) {
     if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK) return DDEF_EINVAL;
     if (c->queue_form && kind != DDEF_COMPRESSOR_TOPK) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    drop_graph(c);
     c->compressor = kind;
     return DDEF_OK;
 }
@@ -537,6 +576,7 @@ int ddef_set_heterogeneity(ddef_ctx* c, float zeta) {
     DeviceGuard guard(c->device);
     rc = drop_prefetch(c);
     if (rc) return rc;
+    drop_graph(c);
     c->zeta = zeta;
     return DDEF_OK;
 }
@@ -609,10 +649,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     const uint64_t k = ddef_k_from_delta(delta, c->d);
     c->agg_deferred = false;               // the messages it would read are about to be replaced
-    // candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
-    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
-    if (kb < k) kb = k;
-    if (kb > c->d) kb = c->d;
+    const uint64_t kb = candidate_target(c, k);
     rc = ensure_capacity(c, k, kb);
     if (rc) return rc;
     c->msg_slot = (uint32_t)(c->t % c->q_slots);
@@ -724,7 +761,9 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
     if (c->agg_deferred && !c->agg_in_U) {
         LAUNCH(c, SL_AGGREGATE_APPLY, k_aggregate_tiles<true>, dim3(c->ntiles), dim3(256), (float*)nullptr,
                (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
-               (const uint32_t*)c->agg_off, c->ntiles, c->n, (const float*)c->slot(c->t), c->slot(c->t + 1),
+               (const uint32_t*)c->agg_off, c->ntiles, c->n,
+               ModelRows{c->slot(c->t), c->slot(c->t + 1), c->capturing ? c->t_dev : nullptr, c->ring,
+                         c->ring_slots, c->ld},
                (float)c->n);
     } else {
         LAUNCH(c, SL_APPLY, k_apply, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->slot(c->t),
@@ -734,6 +773,85 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
     c->t += 1;
     c->phase = PH_IDLE;
     if (c->opt_fuse) c->grad_live = false;
+    return DDEF_OK;
+}
+
+static int step_eager(ddef_ctx* c, double delta, float lr) {
+    int rc = ddef_grad(c);
+    if (rc == DDEF_OK) rc = ddef_ef_compress(c, delta, lr);
+    if (rc == DDEF_OK) rc = ddef_aggregate(c);
+    if (rc == DDEF_OK) rc = ddef_apply_delayed(c, lr);
+    return rc;
+}
+
+int ddef_step(ddef_ctx* c, double delta, float lr) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!(delta > 0.0) || !(delta <= 1.0) || !std::isfinite(lr)) return DDEF_EINVAL;
+    if (!c->problem_set || c->phase != PH_IDLE) return DDEF_ESTATE;
+    const uint64_t k = ddef_k_from_delta(delta, c->d);
+    const uint64_t kb = candidate_target(c, k);
+    uint32_t lr_bits;
+    std::memcpy(&lr_bits, &lr, 4);
+    // A steady iteration only: ring form, Top-k, not empty, a filter bound placed for this very k
+    // (so that neither the whole-row start nor k_rebound is part of it), nothing to reallocate,
+    // no per-launch events, no second stream.
+    const bool steady = c->opt_graph && !c->queue_form && c->compressor == DDEF_COMPRESSOR_TOPK &&
+                        !c->profiling && !c->opt_prefetch && c->t >= c->tau && c->have_bound && c->bound_k == k &&
+                        k <= c->msg_ld && candidate_capacity(c, k, kb) <= c->cap;
+    if (!steady) return step_eager(c, delta, lr);
+    DeviceGuard guard(c->device);
+    if (c->graph_exec && (c->graph_k != k || c->graph_lr_bits != lr_bits || c->graph_tau != c->tau)) drop_graph(c);
+    if (c->t_dev_value != c->t) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipMemcpy(c->t_dev, &c->t, 8, hipMemcpyHostToDevice));
+        c->t_dev_value = c->t;
+    }
+    if (!c->graph_exec) {
+        // record this iteration's launches (nothing runs yet), then run the recording once
+        const uint64_t fulls_before = c->full_selects;
+        hipGraph_t graph = nullptr;
+        HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+        c->capturing = true;
+        rc = step_eager(c, delta, lr);
+        if (rc == DDEF_OK) LAUNCH(c, SL_ADVANCE, k_advance, dim3(1), dim3(64), c->t_dev);
+        c->capturing = false;
+        const hipError_t ended = hipStreamEndCapture(c->stream, &graph);
+        if (rc != DDEF_OK || ended != hipSuccess || graph == nullptr) {
+            if (graph) (void)hipGraphDestroy(graph);
+            c->sticky = DDEF_EHIP;           // the host state has moved on without the device
+            return rc != DDEF_OK ? rc : DDEF_EHIP;
+        }
+        const hipError_t made = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (made != hipSuccess) { c->graph_exec = nullptr; c->sticky = DDEF_EHIP; return DDEF_EHIP; }
+        c->graph_k = k; c->graph_lr_bits = lr_bits; c->graph_tau = c->tau;
+        c->graph_full_selects = c->full_selects - fulls_before;
+        HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
+        c->t_dev_value = c->t;               // the host counter moved during the recording
+        return DDEF_OK;
+    }
+    HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->stream));
+    // what the four calls would have left on the host
+    c->t += 1;
+    c->t_dev_value = c->t;
+    c->full_selects += c->graph_full_selects;
+    c->graph_replays += 1;
+    c->lr_step = lr;
+    c->k_step = k;
+    c->step_empty = false;
+    c->grad_stored = false;
+    c->grad_pending = c->opt_fuse != 0;
+    c->grad_live = c->opt_fuse == 0;
+    c->agg_deferred = true;
+    c->agg_in_U = false;
+    c->agg_slot = c->msg_slot;
+    return DDEF_OK;
+}
+
+int ddef_graph_replays(ddef_ctx* c, uint64_t* count) {
+    if (!c || !count) return DDEF_EINVAL;
+    *count = c->graph_replays;
     return DDEF_OK;
 }
 
@@ -917,6 +1035,7 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    drop_graph(c);
     switch (option) {
         case DDEF_OPT_FORCE_FULL_SELECT: c->opt_force_full = value != 0; return DDEF_OK;
         case DDEF_OPT_PREFETCH_GRAD:
@@ -927,6 +1046,7 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
             c->opt_fuse = value != 0;
             if (c->opt_fuse) return drop_prefetch(c);
             return DDEF_OK;
+        case DDEF_OPT_GRAPH: c->opt_graph = value != 0; return DDEF_OK;
         case DDEF_OPT_CANDIDATE_SLACK_X16:
             if (value < 16 || value > 1024) return DDEF_EINVAL;
             c->opt_slack_x16 = value;

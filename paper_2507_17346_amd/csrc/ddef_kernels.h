@@ -52,6 +52,13 @@ struct GradSource {
     int kind;
     float scale;
     float zeta;                  // 0: all workers share the optimum xstar
+    // Inside a captured graph nothing may change from launch to launch, so the iteration number
+    // comes from device memory (t_dev non-null) and with it the noise key (t_lo, t_hi) and the
+    // snapshot xs = ring + ((t - tau) mod ring_slots) * ring_ld, both overriding the fields above.
+    const uint64_t* t_dev;
+    const float* ring;
+    uint32_t ring_slots, tau;
+    uint64_t ring_ld;
 };
 
 __global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);
@@ -90,10 +97,20 @@ __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* o
                              float* msg_val, uint64_t msg_ld, uint32_t k);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
 __global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off);
+// Where the model update reads x_t and writes x_{t+1}: given rows, or (inside a captured graph)
+// slots t and t+1 of the ring with t read from device memory.
+struct ModelRows {
+    const float* x;
+    float* xn;
+    const uint64_t* t_dev;
+    float* ring;
+    uint32_t ring_slots;
+    uint64_t ring_ld;
+};
 template <bool kApply>
 __global__ void k_aggregate_tiles(float* U, const uint32_t* idx, const float* val, uint64_t msg_ld,
-                                  const uint32_t* off, uint32_t ntiles, uint32_t n, const float* x, float* xn,
-                                  float nf);
+                                  const uint32_t* off, uint32_t ntiles, uint32_t n, ModelRows rows, float nf);
+__global__ void k_advance(uint64_t* t_dev);
 __global__ void k_fill_f4(float* p, uint64_t quads);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);
 

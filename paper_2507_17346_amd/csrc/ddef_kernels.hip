@@ -170,6 +170,15 @@ __device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_
 // ------------------------------------------------------------------------------------
 // S0  g_i = lambda * (x_{t-tau} - x*) + scale * z      (Assumption 2; stale iterate)
 // ------------------------------------------------------------------------------------
+// The iteration number from device memory, where the launch is part of a captured graph.
+__device__ __forceinline__ void resolve_iteration(GradSource& s) {
+    if (s.t_dev == nullptr) return;
+    const uint64_t t = *s.t_dev;
+    s.t_lo = (uint32_t)t;
+    s.t_hi = (uint32_t)(t >> 32);
+    s.xs = s.ring + ((t - s.tau) % s.ring_slots) * s.ring_ld;
+}
+
 // what all workers share at four consecutive coordinates
 struct Shared4 { float lam[4], opt[4], x[4]; };
 
@@ -202,6 +211,7 @@ __device__ __forceinline__ void grad_quad(const GradSource& s, const Shared4& sh
 // the snapshot are read once for all n workers.
 __global__ __launch_bounds__(256) void k_grad(GradSource s, float* __restrict__ g, uint64_t ld, uint32_t d,
                                               uint32_t n) {
+    resolve_iteration(s);
     const uint32_t quads = (d + 3u) >> 2;
     for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
         const uint32_t j = q << 2;
@@ -250,6 +260,7 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
                                                   uint32_t* __restrict__ nonfinite) {
     // plain: grid (groups, n).  fused: 1-D grid with the worker index fastest, so that the blocks
     // that need the same lambda / x* / snapshot lines run at about the same time
+    if (kFusedGrad) resolve_iteration(src);
     const uint32_t w = kFusedGrad ? blockIdx.x % n : blockIdx.y;
     const uint32_t grp = kFusedGrad ? blockIdx.x / n : blockIdx.x;
     const uint32_t lane = threadIdx.x;
@@ -987,8 +998,8 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
                                                          const uint32_t* __restrict__ idx,
                                                          const float* __restrict__ val, uint64_t msg_ld,
                                                          const uint32_t* __restrict__ off,
-                                                         uint32_t ntiles, uint32_t n,
-                                                         const float* x, float* xn, float nf) {
+                                                         uint32_t ntiles, uint32_t n, ModelRows rows,
+                                                         float nf) {
     __shared__ __attribute__((aligned(16))) float tile[kTile];
     __shared__ uint32_t lo_s[256], hi_s[256];
     const uint32_t b = blockIdx.x;
@@ -1016,6 +1027,13 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
         }
     }
     if (kApply) {
+        const float* x = rows.x;
+        float* xn = rows.xn;
+        if (rows.t_dev != nullptr) {
+            const uint64_t t = *rows.t_dev;
+            x = rows.ring + (t % rows.ring_slots) * rows.ring_ld;
+            xn = rows.ring + ((t + 1u) % rows.ring_slots) * rows.ring_ld;
+        }
         const float4* xin = reinterpret_cast<const float4*>(x + (uint64_t)base);
         float4* xout = reinterpret_cast<float4*>(xn + (uint64_t)base);
         for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) {
@@ -1035,9 +1053,14 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
 }
 
 template __global__ void k_aggregate_tiles<false>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
-                                                  uint32_t, uint32_t, const float*, float*, float);
+                                                  uint32_t, uint32_t, ModelRows, float);
 template __global__ void k_aggregate_tiles<true>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
-                                                 uint32_t, uint32_t, const float*, float*, float);
+                                                 uint32_t, uint32_t, ModelRows, float);
+
+// Last node of a captured iteration: t <- t + 1 in device memory.
+__global__ void k_advance(uint64_t* t_dev) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *t_dev += 1u;
+}
 
 // S5  x_{t+1} = x_t - U / n, written into the next ring slot (may alias x_t when the ring
 // has a single slot: element-wise, so in place is fine).  One quad per thread, single-wave
