@@ -82,8 +82,27 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, com
     dt = time.perf_counter() - t0
     o.close()
     return {"value": w.n * sample_d / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "host": host_description(),
             "sample": f"1 non-empty iteration, all {w.n} workers, first {sample_d} of {w.d} coordinates "
                       f"({dt:.1f} s wall, {threads} threads){budget_note}"}
+
+
+def host_description():
+    """CPU model and the number of logical CPUs this process may use."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except Exception:
+        usable = os.cpu_count() or 1
+    return {"cpu_model": model, "logical_cpus": os.cpu_count() or 1, "usable_cpus": usable}
 
 
 def describe(w, sched):
@@ -197,6 +216,7 @@ def main():
     # ---- the same K steps again, once with a wait after each call (time per call), once with
     # HIP events around every kernel launch on the library's stream (time per kernel) -----------
     phase = {"grad": 0.0, "ef_compress": 0.0, "aggregate": 0.0, "apply_delayed": 0.0}
+    samples = {k: [] for k in phase}
     floor_bytes_sum = 0.0
     for _ in range(args.steps):
         delta = begin_iteration()
@@ -207,8 +227,12 @@ def main():
             p0 = time.perf_counter()
             call()
             ctx.sync()
-            phase[name] += time.perf_counter() - p0
+            dt = time.perf_counter() - p0
+            phase[name] += dt
+            samples[name].append(1e3 * dt)
     phase_ms = {k: 1e3 * v / args.steps for k, v in phase.items()}
+    phase_median = {k: sorted(v)[len(v) // 2] for k, v in samples.items()}
+    phase_min = {k: min(v) for k, v in samples.items()}
     full0 = ctx.full_select_count()
     ctx.profile_enable(True)
     for _ in range(args.steps):
@@ -288,6 +312,9 @@ def main():
         "grad": grad_info,
         "ef_topk_aggregate_apply": path,
         "ms_per_call": phase_ms,
+        "ms_per_call_median": phase_median,
+        "ms_per_call_min": phase_min,
+        "device": ctx.device_info(),
         "kernels_ms_per_step": {k: round(v["ms_per_step"], 5) for k, v in kernels.items()},
         "full_row_selects_per_step": full_selects / args.steps,
     }

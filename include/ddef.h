@@ -221,6 +221,14 @@ int ddef_profile_enable(ddef_ctx* ctx, int on);
 int ddef_profile_slots(void);
 int ddef_profile_read(ddef_ctx* ctx, int slot, const char** name, uint64_t* launches,
                       double* total_ms);
+/* What the device of this context reports about itself (hipGetDeviceProperties): compute
+ * units, wavefront width, LDS bytes per compute unit, device memory in bytes, shader and memory
+ * clocks in kHz, memory bus width in bits, and the architecture name (at most name_len - 1
+ * characters, NUL-terminated).  Any pointer may be NULL. */
+int ddef_device_info(ddef_ctx* ctx, uint32_t* compute_units, uint32_t* wave_size, uint64_t* lds_bytes_per_cu,
+                     uint64_t* memory_bytes, uint32_t* clock_khz, uint32_t* memory_clock_khz,
+                     uint32_t* memory_bus_bits, char* arch_name, uint32_t name_len);
+
 /* Yardstick for hardware byte counters: one launch of a plain copy kernel (k_copy_f4) that
  * reads and rewrites the gradient scratch row of worker 0 in place; *bytes_each_way is the
  * number of bytes it reads (= writes).  Between iterations only; the gradient scratch is

@@ -37,6 +37,7 @@ SIGNATURES = {
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
     "ddef_aggregate": (C.c_int, [_ctx]),
     "ddef_step": (C.c_int, [_ctx, C.c_double, C.c_float]),
+    "ddef_device_info": (C.c_int, [_ctx, _u32p, _u32p, _u64p, _u64p, _u32p, _u32p, _u32p, C.c_char_p, C.c_uint32]),
     "ddef_graph_replays": (C.c_int, [_ctx, _u64p]),
     "ddef_apply_delayed": (C.c_int, [_ctx, C.c_float]),
     "ddef_sync": (C.c_int, [_ctx]),
@@ -269,6 +270,16 @@ class Context:
 
     def step(self, delta: float, lr: float):
         self._check(self._lib.ddef_step(self._h, float(delta), float(lr)), "ddef_step")
+
+    def device_info(self) -> dict:
+        cu, wave, clk, mclk, bus = (C.c_uint32() for _ in range(5))
+        lds, mem = C.c_uint64(), C.c_uint64()
+        name = C.create_string_buffer(64)
+        self._check(self._lib.ddef_device_info(self._h, C.byref(cu), C.byref(wave), C.byref(lds), C.byref(mem),
+                                               C.byref(clk), C.byref(mclk), C.byref(bus), name, 64), "ddef_device_info")
+        return {"arch": name.value.decode(), "compute_units": cu.value, "wave_size": wave.value,
+                "lds_bytes_per_cu": lds.value, "memory_bytes": mem.value, "clock_khz": clk.value,
+                "memory_clock_khz": mclk.value, "memory_bus_bits": bus.value}
 
     def graph_replays(self) -> int:
         n = C.c_uint64()

@@ -977,6 +977,26 @@ int ddef_get_filter_state(ddef_ctx* c, uint32_t worker, uint32_t* next_bound, ui
     return DDEF_OK;
 }
 
+int ddef_device_info(ddef_ctx* c, uint32_t* compute_units, uint32_t* wave_size, uint64_t* lds_bytes_per_cu,
+                     uint64_t* memory_bytes, uint32_t* clock_khz, uint32_t* memory_clock_khz,
+                     uint32_t* memory_bus_bits, char* arch_name, uint32_t name_len) {
+    if (!c) return DDEF_EINVAL;
+    hipDeviceProp_t prop;
+    HIP_TRY(c, hipGetDeviceProperties(&prop, c->device));
+    if (compute_units) *compute_units = (uint32_t)prop.multiProcessorCount;
+    if (wave_size) *wave_size = (uint32_t)prop.warpSize;
+    if (lds_bytes_per_cu) *lds_bytes_per_cu = (uint64_t)prop.maxSharedMemoryPerMultiProcessor;
+    if (memory_bytes) *memory_bytes = (uint64_t)prop.totalGlobalMem;
+    if (clock_khz) *clock_khz = (uint32_t)prop.clockRate;
+    if (memory_clock_khz) *memory_clock_khz = (uint32_t)prop.memoryClockRate;
+    if (memory_bus_bits) *memory_bus_bits = (uint32_t)prop.memoryBusWidth;
+    if (arch_name && name_len) {
+        std::strncpy(arch_name, prop.gcnArchName, name_len - 1u);
+        arch_name[name_len - 1u] = '\0';
+    }
+    return DDEF_OK;
+}
+
 int ddef_copy_probe(ddef_ctx* c, uint64_t* bytes_each_way) {
     int rc = check_ctx(c);
     if (rc) return rc;

@@ -71,6 +71,49 @@ def test_c3_full_size_bench_configuration(ddef, oracle_mod):
     assert used >= w.n                # at least the last iterations ran through the filter
 
 
+def test_c5_full_size_across_a_change_of_tau_and_delta(ddef, oracle_mod):
+    """The adaptive workload at its real shape (d = 124e6, n = 16, ring of 17 snapshots): the last
+    iterations of DeCo's first period and the first of its second, i.e. across a change of both tau
+    and delta (re-placed filter bound, messages of a different length), against the oracle."""
+    w = workloads.get("C5")
+    trace = workloads.network_trace(w)
+    plan = []
+    for p in range(2):
+        tau, delta = ddef.deco(trace.v_g_bits, trace.bandwidth_bps[p], trace.latency_s[p], trace.t_comp_s)
+        plan.append((int(np.clip(tau, *trace.tau_bounds)), float(np.clip(delta, *trace.delta_bounds))))
+    (tau1, delta1), (tau2, delta2) = plan
+    assert (tau1, delta1) != (tau2, delta2)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, w.tau_max)
+    o = oracle_mod.Oracle(w.d, w.n, w.tau_max, threads=w.n)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    # period 1: tau1 empty iterations, then two real ones; period 2 starts at t = tau1 + 2 and runs
+    # until it has produced two real iterations as well (t - tau2 >= 0)
+    switch = tau1 + 2
+    last = max(switch, tau2) + 2
+    real = 0
+    for t in range(last):
+        tau, delta = (tau1, delta1) if t < switch else (tau2, delta2)
+        for h in (g, o):
+            h.set_tau(tau)
+            h.step(delta, w.lr)
+        if t >= tau:
+            real += 1
+            for i in (0, 7, w.n - 1):
+                gi, gv = g.get_message(i)
+                oi, ov = o.get_message(i)
+                assert np.array_equal(gi, oi), ("C5", t, i)
+                assert np.array_equal(bits(gv), bits(ov)), ("C5", t, i)
+            assert np.array_equal(bits(g.get_model()), bits(o.get_model())), ("C5 model", t)
+    assert real >= 4
+    for i in (0, w.n - 1):
+        assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), ("C5 error buffer", i)
+    assert np.array_equal(bits(g.get_update()), bits(o.get_update()))
+    g.close()
+    o.close()
+
+
 def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
     w = workloads.get("C4")
     lam, xstar, x0 = workloads.make_problem(w)
