@@ -40,14 +40,14 @@ ALGO_BYTES_PER_ELEM = {
 }
 
 
-def measured_traffic(kernel, workload_name):
-    """HBM bytes per launch from the committed hardware-counter summary (rocprofv3 --pmc
-    FETCH_SIZE / WRITE_SIZE, scaled by the copy yardstick), or None when there is none for
-    this kernel and workload."""
+def measured_traffic(kernel, workload_name, key="traffic_bytes_per_launch"):
+    """HBM bytes from the committed hardware-counter summary (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, scaled by the copy yardstick): per launch of `kernel`, or with another key the
+    figure the summary holds under it; None when there is none for this kernel and workload."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload_name}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith(key + ":"):
                 return float(line.split(":", 1)[1])
     except OSError:
         pass
@@ -298,6 +298,17 @@ def main():
             "floor_bytes_per_step": floor_bytes,
             "floor_GBps": floor_bytes / (path_ms * 1e-3) / 1e9,
             "floor_frac_of_peak": floor_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # bytes the hardware counters saw for all kernels of the path in one iteration (default
+    # configuration of this workload only), and the rate and share of the peak they give
+    counted = None
+    if args.d is None and args.delta is None and args.compressor == "topk" and not (
+            args.fuse_grad or args.prefetch or args.queue_form):
+        counted = measured_traffic("k_ef_filter", w.name, key="path_traffic_bytes_per_step")
+    if counted:
+        path["measured_bytes_per_step"] = counted
+        path["measured_bytes_per_worker_element"] = counted / elems
+        path["measured_GBps"] = counted / (path_ms * 1e-3) / 1e9
+        path["measured_frac_of_peak"] = counted / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     out = {
         "metric": "EF+top-k+aggregate step: gradient elements/s and achieved HBM GB/s (% of peak)",
