@@ -69,9 +69,11 @@ void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// -2 ln(u) for u = ((w >> 8) + 1) / 2^24 in (0, 1], from +,-,*,/ and fused multiply-add
+// -2 ln(u) for u = ((w >> 8) + 1) / 2^24 in (0, 1], from +,-,* and fused multiply-add
 // (std::fmaf: one rounding, the same on every IEEE machine):
-// u = 2^(e-24) * m, m folded into (sqrt(1/2), sqrt(2)], ln m = 2 atanh((m-1)/(m+1)).
+// u = 2^(e-24) * m, m folded into (sqrt(1/2), sqrt(2)], f = m - 1,
+// ln(1 + f) = f + f^2 g(f) with g a degree-7 polynomial (the Chebyshev interpolant of
+// (ln(1+f) - f) / f^2 on that interval, coefficients rounded to fp32; |error of ln m| < 4e-8).
 float neg2ln_uniform(uint32_t w) {
     uint32_t a = (w >> 8) + 1u;                       // 1 .. 2^24, exact as a float
     uint32_t fb = bits_of((float)a);
@@ -79,14 +81,16 @@ float neg2ln_uniform(uint32_t w) {
     uint32_t mant = fb & 0x7fffffu;
     float m = float_of(mant | 0x3f800000u);           // [1, 2)
     if (mant > 0x3504f3u) { m = m * 0.5f; e += 1; }   // fold above sqrt(2)
-    float s = (m - 1.0f) / (m + 1.0f);
-    float s2 = s * s;
-    float poly = 1.0f / 9.0f;
-    poly = std::fmaf(poly, s2, 1.0f / 7.0f);
-    poly = std::fmaf(poly, s2, 1.0f / 5.0f);
-    poly = std::fmaf(poly, s2, 1.0f / 3.0f);
-    poly = std::fmaf(poly, s2, 1.0f);
-    float lnm = (2.0f * s) * poly;
+    float f = m - 1.0f;
+    float g = 0x1.67ed28p-4f;
+    g = std::fmaf(g, f, -0x1.21fd54p-3f);
+    g = std::fmaf(g, f, 0x1.2fd102p-3f);
+    g = std::fmaf(g, f, -0x1.53bb74p-3f);
+    g = std::fmaf(g, f, 0x1.99071p-3f);
+    g = std::fmaf(g, f, -0x1.000302p-2f);
+    g = std::fmaf(g, f, 0x1.555638p-2f);
+    g = std::fmaf(g, f, -0x1.fffffep-2f);
+    float lnm = std::fmaf(f * f, g, f);
     float v = std::fmaf((float)(24 - e), 0x1.62e43p-1f, -lnm);   // (24-e) ln 2 - ln m = -ln u >= 0
     v = v < 0.0f ? 0.0f : v;
     return 2.0f * v;
@@ -125,7 +129,9 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
 // kind 2: Student-t with 3 degrees of freedom, z0 / sqrt(chi2_3 / 3), where chi2_3 is the
 //   square of the second Box-Muller normal z1 = sqrt(-2 ln u(w0)) sin(angle(w1)) plus an
 //   independent chi-square with 2 degrees of freedom, -2 ln u(w2) (the squared radius of a
-//   second Box-Muller pair, which needs no angle).  w3 is not used.
+//   second Box-Muller pair, which needs no angle).  With R2 = -2 ln u(w0), z0 = sqrt(R2) cos and
+//   z1^2 = R2 sin^2, the quotient is cos * sqrt(3 R2 / (R2 sin^2 + chi2_2)): one division and
+//   one square root.  w3 is not used.
 // kind 0: no noise.
 float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) {
     if (kind == 0) return 0.0f;
@@ -134,16 +140,14 @@ float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) 
     uint32_t w[4];
     philox4x32_10(ctr, key, w);
     float c01, s01;
-    float r01 = std::sqrt(neg2ln_uniform(w[0]));
+    float r2 = neg2ln_uniform(w[0]);
     unit_circle_point(w[1], &c01, &s01);
-    float z0 = r01 * c01;
-    if (kind == 1) return z0;
-    float z1 = r01 * s01;
+    if (kind == 1) return std::sqrt(r2) * c01;
     float chi2_2 = neg2ln_uniform(w[2]);
-    float q = std::fmaf(z1, z1, chi2_2) / 3.0f;
-    float den = std::sqrt(q);
-    if (den == 0.0f) return 0.0f;
-    return z0 / den;
+    float chi2_3 = std::fmaf(r2, s01 * s01, chi2_2);
+    if (chi2_3 == 0.0f) return 0.0f;
+    float ratio = (3.0f * r2) / chi2_3;
+    return c01 * std::sqrt(ratio);
 }
 
 // ---------------------------------------------------------------------------------

@@ -106,22 +106,25 @@ __device__ __forceinline__ U4 philox_block(uint32_t c0, uint32_t c1, uint32_t c2
 }
 
 // -2 ln u, u = ((w >> 8) + 1) 2^-24: split off the exponent, fold the mantissa into
-// (sqrt 1/2, sqrt 2], ln m = 2 atanh s with s = (m-1)/(m+1), odd series up to s^9 in Horner
-// form with explicit fused multiply-adds (single rounding, reproducible on the CPU).
+// (sqrt 1/2, sqrt 2], ln(1 + f) = f + f^2 g(f) for f = m - 1 with a degree-7 polynomial g (the
+// Chebyshev interpolant of (ln(1+f) - f) / f^2 on that interval) in Horner form with explicit
+// fused multiply-adds (single rounding, reproducible on the CPU); no division.
 __device__ __forceinline__ float radius_sq(uint32_t w) {
     const uint32_t fb = __float_as_uint((float)((w >> 8) + 1u));
     int ex = (int)(fb >> 23) - 127;
     const uint32_t mant = fb & 0x7fffffu;
     float m = __uint_as_float(mant | 0x3f800000u);
     if (mant > 0x3504f3u) { m = m * 0.5f; ex += 1; }
-    const float s = (m - 1.0f) / (m + 1.0f);
-    const float s2 = s * s;
-    float h = 1.0f / 9.0f;
-    h = __builtin_fmaf(h, s2, 1.0f / 7.0f);
-    h = __builtin_fmaf(h, s2, 1.0f / 5.0f);
-    h = __builtin_fmaf(h, s2, 1.0f / 3.0f);
-    h = __builtin_fmaf(h, s2, 1.0f);
-    const float lnm = (2.0f * s) * h;
+    const float f = m - 1.0f;
+    float h = 0x1.67ed28p-4f;
+    h = __builtin_fmaf(h, f, -0x1.21fd54p-3f);
+    h = __builtin_fmaf(h, f, 0x1.2fd102p-3f);
+    h = __builtin_fmaf(h, f, -0x1.53bb74p-3f);
+    h = __builtin_fmaf(h, f, 0x1.99071p-3f);
+    h = __builtin_fmaf(h, f, -0x1.000302p-2f);
+    h = __builtin_fmaf(h, f, 0x1.555638p-2f);
+    h = __builtin_fmaf(h, f, -0x1.fffffep-2f);
+    const float lnm = __builtin_fmaf(f * f, h, f);
     float v = __builtin_fmaf((float)(24 - ex), 0x1.62e43p-1f, -lnm);
     v = v < 0.0f ? 0.0f : v;
     return 2.0f * v;
@@ -152,19 +155,19 @@ __device__ __forceinline__ void circle_point(uint32_t w, float& co, float& si) {
 }
 
 // kind 1: normal z0 = R cos.  kind 2: Student-t(3) = z0 / sqrt((z1^2 + chi2_2) / 3) with
-// z1 = R sin the pair's second normal and chi2_2 = -2 ln u of the block's third word.
+// z1 = R sin the pair's second normal and chi2_2 = -2 ln u of the block's third word, computed
+// as cos * sqrt(3 R^2 / (R^2 sin^2 + chi2_2)): one division and one square root.
 __device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
                                         uint32_t seed_lo, uint32_t seed_hi, int kind) {
     const U4 w = philox_block(j, worker, t_lo, t_hi, seed_lo, seed_hi);
     float c01, s01;
-    const float r01 = __builtin_sqrtf(radius_sq(w.a));
+    const float r2 = radius_sq(w.a);
     circle_point(w.b, c01, s01);
-    const float z0 = r01 * c01;
-    if (kind == 1) return z0;
-    const float z1 = r01 * s01;
-    const float q = __builtin_fmaf(z1, z1, radius_sq(w.c)) / 3.0f;
-    const float den = __builtin_sqrtf(q);
-    return den == 0.0f ? 0.0f : z0 / den;
+    if (kind == 1) return __builtin_sqrtf(r2) * c01;
+    const float chi2_3 = __builtin_fmaf(r2, s01 * s01, radius_sq(w.c));
+    if (chi2_3 == 0.0f) return 0.0f;
+    const float ratio = (3.0f * r2) / chi2_3;
+    return c01 * __builtin_sqrtf(ratio);
 }
 
 // ------------------------------------------------------------------------------------
