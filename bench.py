@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 VALU_NOMINAL_TINSTR = 256 * 64 * 2.4e9 / 1e12
 # vector lane-instructions k_grad executes per noise draw, by noise kind: SQ_INSTS_VALU x 64 / draws
 # (profiles/k_grad_C3_valu.txt)
-VALU_PER_DRAW = {2: 214.8}
+VALU_PER_DRAW = {2: 171.8}
 
 # algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
 ALGO_BYTES_PER_ELEM = {
@@ -270,8 +270,8 @@ def main():
 
     if dominant == "k_ef_filter_fused" and w.noise_kind in VALU_PER_DRAW:
         # with the generator fused in, the pass is bound by vector issue like k_grad: lane-instructions
-        # per element = k_grad's per draw + k_ef_filter's 67 wave instructions per 256 coordinates
-        per_elem_instr = VALU_PER_DRAW[w.noise_kind] + 67.0 * 64.0 / 256.0
+        # per element = k_grad's per draw + k_ef_filter's 82 wave instructions per 256 coordinates
+        per_elem_instr = VALU_PER_DRAW[w.noise_kind] + 82.1 * 64.0 / 256.0
         rate = per_elem_instr * elems / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": dominant, "achieved": rate, "peak": VALU_NOMINAL_TINSTR,
                     "unit": "T lane-instr/s", "frac": rate / VALU_NOMINAL_TINSTR, "traffic": None,
