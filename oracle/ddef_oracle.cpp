@@ -125,7 +125,9 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
 }
 
 // Standard draw z(seed, t, worker, j) from one Philox block (w0..w3).
-// kind 1: Box-Muller normal, z0 = sqrt(-2 ln u(w0)) cos(angle(w1)).
+// kind 1: Box-Muller normals, four coordinates to a block: the block of counter (j >> 2, worker,
+//   t) serves coordinates 4q .. 4q+3 with the two independent pairs
+//   (sqrt(-2 ln u(w0)) cos(angle(w1)), the same radius times sin) and likewise from (w2, w3).
 // kind 2: Student-t with 3 degrees of freedom, z0 / sqrt(chi2_3 / 3), where chi2_3 is the
 //   square of the second Box-Muller normal z1 = sqrt(-2 ln u(w0)) sin(angle(w1)) plus an
 //   independent chi-square with 2 degrees of freedom, -2 ln u(w2) (the squared radius of a
@@ -135,14 +137,21 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
 // kind 0: no noise.
 float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) {
     if (kind == 0) return 0.0f;
-    uint32_t ctr[4] = {j, worker, (uint32_t)t, (uint32_t)(t >> 32)};
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
     uint32_t w[4];
-    philox4x32_10(ctr, key, w);
     float c01, s01;
+    if (kind == 1) {
+        uint32_t ctr[4] = {j >> 2, worker, (uint32_t)t, (uint32_t)(t >> 32)};
+        philox4x32_10(ctr, key, w);
+        uint32_t pair = (j >> 1) & 1u;
+        float radius = std::sqrt(neg2ln_uniform(w[2 * pair]));
+        unit_circle_point(w[2 * pair + 1], &c01, &s01);
+        return (j & 1u) ? radius * s01 : radius * c01;
+    }
+    uint32_t ctr[4] = {j, worker, (uint32_t)t, (uint32_t)(t >> 32)};
+    philox4x32_10(ctr, key, w);
     float r2 = neg2ln_uniform(w[0]);
     unit_circle_point(w[1], &c01, &s01);
-    if (kind == 1) return std::sqrt(r2) * c01;
     float chi2_2 = neg2ln_uniform(w[2]);
     float chi2_3 = std::fmaf(r2, s01 * s01, chi2_2);
     if (chi2_3 == 0.0f) return 0.0f;

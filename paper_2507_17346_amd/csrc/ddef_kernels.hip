@@ -154,16 +154,32 @@ __device__ __forceinline__ void circle_point(uint32_t w, float& co, float& si) {
     si = (quad == 0u) ? s : (quad == 1u) ? c : (quad == 2u) ? -s : -c;
 }
 
-// kind 1: normal z0 = R cos.  kind 2: Student-t(3) = z0 / sqrt((z1^2 + chi2_2) / 3) with
-// z1 = R sin the pair's second normal and chi2_2 = -2 ln u of the block's third word, computed
-// as cos * sqrt(3 R^2 / (R^2 sin^2 + chi2_2)): one division and one square root.
-__device__ __forceinline__ float draw_z(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
-                                        uint32_t seed_lo, uint32_t seed_hi, int kind) {
+// Normal draws for the four coordinates 4q .. 4q+3 from the one block of counter (q, worker, t):
+// two Box-Muller pairs, (R cos, R sin) from words (0, 1) and from words (2, 3).
+__device__ __forceinline__ void draw_normal4(uint32_t q, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
+                                             uint32_t seed_lo, uint32_t seed_hi, float (&z)[4]) {
+    const U4 w = philox_block(q, worker, t_lo, t_hi, seed_lo, seed_hi);
+    float co, si;
+    float radius = __builtin_sqrtf(radius_sq(w.a));
+    circle_point(w.b, co, si);
+    z[0] = radius * co;
+    z[1] = radius * si;
+    radius = __builtin_sqrtf(radius_sq(w.c));
+    circle_point(w.d, co, si);
+    z[2] = radius * co;
+    z[3] = radius * si;
+}
+
+// Student-t(3) draw for coordinate j from the block of counter (j, worker, t):
+// z0 / sqrt((z1^2 + chi2_2) / 3) with (z0, z1) = (R cos, R sin) the Box-Muller pair of words
+// (0, 1) and chi2_2 = -2 ln u of the third word, computed as
+// cos * sqrt(3 R^2 / (R^2 sin^2 + chi2_2)): one division and one square root.
+__device__ __forceinline__ float draw_t3(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
+                                         uint32_t seed_lo, uint32_t seed_hi) {
     const U4 w = philox_block(j, worker, t_lo, t_hi, seed_lo, seed_hi);
     float c01, s01;
     const float r2 = radius_sq(w.a);
     circle_point(w.b, c01, s01);
-    if (kind == 1) return __builtin_sqrtf(r2) * c01;
     const float chi2_3 = __builtin_fmaf(r2, s01 * s01, radius_sq(w.c));
     if (chi2_3 == 0.0f) return 0.0f;
     const float ratio = (3.0f * r2) / chi2_3;
@@ -198,14 +214,21 @@ __device__ __forceinline__ Shared4 grad_shared4(const GradSource& s, uint32_t j)
 // key 2^64 - 2, which no iteration uses.
 __device__ __forceinline__ void grad_quad(const GradSource& s, const Shared4& sh, uint32_t worker,
                                           uint32_t j, uint32_t d, float (&out)[4]) {
+    float shift[4] = {0.f, 0.f, 0.f, 0.f}, z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (s.zeta != 0.0f) draw_normal4(j >> 2, worker, 0xfffffffeu, 0xffffffffu, s.seed_lo, s.seed_hi, shift);
+    if (s.kind == 1) {
+        draw_normal4(j >> 2, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi, z);
+    } else if (s.kind == 2) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) z[c] = draw_t3(j + c, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi);
+    }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         float optimum = sh.opt[c];
-        if (s.zeta != 0.0f)
-            optimum = sh.opt[c] + s.zeta * draw_z(j + c, worker, 0xfffffffeu, 0xffffffffu, s.seed_lo, s.seed_hi, 1);
+        if (s.zeta != 0.0f) optimum = sh.opt[c] + s.zeta * shift[c];
         const float mean = sh.lam[c] * (sh.x[c] - optimum);
         float xi = 0.0f;
-        if (s.kind != 0) xi = s.scale * draw_z(j + c, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi, s.kind);
+        if (s.kind != 0) xi = s.scale * z[c];
         out[c] = (j + c < d) ? mean + xi : 0.0f;
     }
 }

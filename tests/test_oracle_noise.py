@@ -62,26 +62,45 @@ def test_unit_circle_matches_libm(oracle_mod):
         assert abs(s - math.sin(ang)) <= 3e-7, hex(w)
 
 
-def test_normal_draw_is_box_muller_of_the_philox_words(oracle_mod):
-    # z = sqrt(-2 ln u1) cos(2 pi u2) with u1, u2 from output words 0 and 1 of the block
-    # whose counter is (j, worker, t_lo, t_hi) and whose key is the seed.
+def test_draws_are_box_muller_of_the_philox_words(oracle_mod):
     seed, t, worker = 0x1234567855AA33CC, (7 << 32) | 9, 3
-    for j in [0, 1, 77, 2 ** 31 + 5]:
-        w = oracle_mod.philox4x32_10([j, worker, t & 0xFFFFFFFF, t >> 32],
-                                     [seed & 0xFFFFFFFF, seed >> 32])
-        u1 = ((int(w[0]) >> 8) + 1) / 2.0 ** 24
-        ang = 2.0 * math.pi * ((int(w[1]) >> 8) + 0.5) / 2.0 ** 24
-        want = math.sqrt(-2.0 * math.log(u1)) * math.cos(ang)
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+
+    def radius_sq(word):
+        return -2.0 * math.log(((int(word) >> 8) + 1) / 2.0 ** 24)
+
+    def angle(word):
+        return 2.0 * math.pi * ((int(word) >> 8) + 0.5) / 2.0 ** 24
+
+    for j in [0, 1, 2, 3, 76, 77, 78, 79, 2 ** 31 + 5, 2 ** 31 + 6]:
+        # normal: the block of counter (j >> 2, worker, t_lo, t_hi) serves four coordinates with
+        # the Box-Muller pairs of its words (0, 1) and (2, 3): z = sqrt(-2 ln u) (cos | sin)(2 pi v)
+        w = oracle_mod.philox4x32_10([j >> 2, worker, t & 0xFFFFFFFF, t >> 32], key)
+        pair = (j >> 1) & 1
+        r, ang = math.sqrt(radius_sq(w[2 * pair])), angle(w[2 * pair + 1])
+        want = r * (math.sin(ang) if j & 1 else math.cos(ang))
         got = oracle_mod.noise_z(seed, t, worker, j, 1)
-        assert abs(got - want) <= 5e-6 * max(1.0, abs(want))
-        # Student-t(3): z0 over the root of a chi-square(3)/3 built from the pair's second
-        # normal and the squared radius -2 ln u3 of the block's third word
-        z1 = math.sqrt(-2.0 * math.log(u1)) * math.sin(ang)
-        u3 = ((int(w[2]) >> 8) + 1) / 2.0 ** 24
-        want_t = want / math.sqrt((z1 * z1 - 2.0 * math.log(u3)) / 3.0)
+        assert abs(got - want) <= 5e-6 * max(1.0, abs(want)), j
+        # Student-t(3): one coordinate to the block of counter (j, worker, t_lo, t_hi): z0 over the
+        # root of a chi-square(3)/3 built from the pair's second normal and the squared radius
+        # -2 ln u3 of the block's third word
+        w = oracle_mod.philox4x32_10([j, worker, t & 0xFFFFFFFF, t >> 32], key)
+        r, ang = math.sqrt(radius_sq(w[0])), angle(w[1])
+        z0, z1 = r * math.cos(ang), r * math.sin(ang)
+        want_t = z0 / math.sqrt((z1 * z1 + radius_sq(w[2])) / 3.0)
         got_t = oracle_mod.noise_z(seed, t, worker, j, 2)
-        assert abs(got_t - want_t) <= 2e-5 * max(1.0, abs(want_t))
+        assert abs(got_t - want_t) <= 2e-5 * max(1.0, abs(want_t)), j
     assert oracle_mod.noise_z(seed, t, worker, 5, 0) == 0.0
+
+
+def test_the_four_normals_of_a_block_are_uncorrelated(oracle_mod):
+    z = oracle_mod.noise_fill(3, 21, 1, 0, 400_000, 1).astype(np.float64).reshape(-1, 4)
+    corr = np.corrcoef(z.T)
+    assert np.abs(corr - np.eye(4)).max() < 1e-2
+    # and so are their squares (cos and sin of one angle are dependent; times an independent
+    # Rayleigh radius they are independent normals)
+    corr2 = np.corrcoef((z * z).T)
+    assert np.abs(corr2 - np.eye(4)).max() < 1e-2
 
 
 def test_normal_distribution(oracle_mod):
