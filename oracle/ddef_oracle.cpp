@@ -133,7 +133,9 @@ void unit_circle_point(uint32_t w, float* cos_out, float* sin_out) {
 //   independent chi-square with 2 degrees of freedom, -2 ln u(w2) (the squared radius of a
 //   second Box-Muller pair, which needs no angle).  With R2 = -2 ln u(w0), z0 = sqrt(R2) cos and
 //   z1^2 = R2 sin^2, the quotient is cos * sqrt(3 R2 / (R2 sin^2 + chi2_2)): one division and
-//   one square root.  w3 is not used.
+//   one square root.  A draw takes three words; the four coordinates 4q .. 4q+3 take the twelve
+//   words of the three blocks with counters (3q, worker, t), (3q+1, ..), (3q+2, ..) in order:
+//   coordinate 4q+c uses words 3c, 3c+1, 3c+2 of that sequence as (radius, angle, chi-square).
 // kind 0: no noise.
 float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) {
     if (kind == 0) return 0.0f;
@@ -148,11 +150,16 @@ float noise_z(uint64_t seed, uint64_t t, uint32_t worker, uint32_t j, int kind) 
         unit_circle_point(w[2 * pair + 1], &c01, &s01);
         return (j & 1u) ? radius * s01 : radius * c01;
     }
-    uint32_t ctr[4] = {j, worker, (uint32_t)t, (uint32_t)(t >> 32)};
-    philox4x32_10(ctr, key, w);
-    float r2 = neg2ln_uniform(w[0]);
-    unit_circle_point(w[1], &c01, &s01);
-    float chi2_2 = neg2ln_uniform(w[2]);
+    uint32_t word[3];
+    for (uint32_t m = 0; m < 3; ++m) {
+        uint32_t at = 3u * (j & 3u) + m;                   // position among the quad's twelve words
+        uint32_t ctr[4] = {3u * (j >> 2) + (at >> 2), worker, (uint32_t)t, (uint32_t)(t >> 32)};
+        philox4x32_10(ctr, key, w);
+        word[m] = w[at & 3u];
+    }
+    float r2 = neg2ln_uniform(word[0]);
+    unit_circle_point(word[1], &c01, &s01);
+    float chi2_2 = neg2ln_uniform(word[2]);
     float chi2_3 = std::fmaf(r2, s01 * s01, chi2_2);
     if (chi2_3 == 0.0f) return 0.0f;
     float ratio = (3.0f * r2) / chi2_3;

@@ -170,20 +170,31 @@ __device__ __forceinline__ void draw_normal4(uint32_t q, uint32_t worker, uint32
     z[3] = radius * si;
 }
 
-// Student-t(3) draw for coordinate j from the block of counter (j, worker, t):
-// z0 / sqrt((z1^2 + chi2_2) / 3) with (z0, z1) = (R cos, R sin) the Box-Muller pair of words
-// (0, 1) and chi2_2 = -2 ln u of the third word, computed as
+// Student-t(3) from three words (radius, angle, chi-square):
+// z0 / sqrt((z1^2 + chi2_2) / 3) with (z0, z1) = (R cos, R sin) the Box-Muller pair of the first
+// two words and chi2_2 = -2 ln u of the third, computed as
 // cos * sqrt(3 R^2 / (R^2 sin^2 + chi2_2)): one division and one square root.
-__device__ __forceinline__ float draw_t3(uint32_t j, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
-                                         uint32_t seed_lo, uint32_t seed_hi) {
-    const U4 w = philox_block(j, worker, t_lo, t_hi, seed_lo, seed_hi);
+__device__ __forceinline__ float t3_of(uint32_t w_radius, uint32_t w_angle, uint32_t w_chi) {
     float c01, s01;
-    const float r2 = radius_sq(w.a);
-    circle_point(w.b, c01, s01);
-    const float chi2_3 = __builtin_fmaf(r2, s01 * s01, radius_sq(w.c));
+    const float r2 = radius_sq(w_radius);
+    circle_point(w_angle, c01, s01);
+    const float chi2_3 = __builtin_fmaf(r2, s01 * s01, radius_sq(w_chi));
     if (chi2_3 == 0.0f) return 0.0f;
     const float ratio = (3.0f * r2) / chi2_3;
     return c01 * __builtin_sqrtf(ratio);
+}
+
+// Student-t(3) draws for the four coordinates 4q .. 4q+3: the twelve words of the blocks with
+// counters (3q, worker, t), (3q+1, ..), (3q+2, ..), three to a coordinate in order.
+__device__ __forceinline__ void draw_t3x4(uint32_t q, uint32_t worker, uint32_t t_lo, uint32_t t_hi,
+                                          uint32_t seed_lo, uint32_t seed_hi, float (&z)[4]) {
+    const U4 a = philox_block(3u * q, worker, t_lo, t_hi, seed_lo, seed_hi);
+    const U4 b = philox_block(3u * q + 1u, worker, t_lo, t_hi, seed_lo, seed_hi);
+    const U4 c = philox_block(3u * q + 2u, worker, t_lo, t_hi, seed_lo, seed_hi);
+    z[0] = t3_of(a.a, a.b, a.c);
+    z[1] = t3_of(a.d, b.a, b.b);
+    z[2] = t3_of(b.c, b.d, c.a);
+    z[3] = t3_of(c.b, c.c, c.d);
 }
 
 // ------------------------------------------------------------------------------------
@@ -219,8 +230,7 @@ __device__ __forceinline__ void grad_quad(const GradSource& s, const Shared4& sh
     if (s.kind == 1) {
         draw_normal4(j >> 2, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi, z);
     } else if (s.kind == 2) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) z[c] = draw_t3(j + c, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi);
+        draw_t3x4(j >> 2, worker, s.t_lo, s.t_hi, s.seed_lo, s.seed_hi, z);
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {

@@ -81,16 +81,28 @@ def test_draws_are_box_muller_of_the_philox_words(oracle_mod):
         want = r * (math.sin(ang) if j & 1 else math.cos(ang))
         got = oracle_mod.noise_z(seed, t, worker, j, 1)
         assert abs(got - want) <= 5e-6 * max(1.0, abs(want)), j
-        # Student-t(3): one coordinate to the block of counter (j, worker, t_lo, t_hi): z0 over the
-        # root of a chi-square(3)/3 built from the pair's second normal and the squared radius
-        # -2 ln u3 of the block's third word
-        w = oracle_mod.philox4x32_10([j, worker, t & 0xFFFFFFFF, t >> 32], key)
+        # Student-t(3): three words to a coordinate, taken in order from the twelve words of the
+        # blocks with counters (3q, ..), (3q+1, ..), (3q+2, ..), q = j >> 2: z0 over the root of a
+        # chi-square(3)/3 built from the pair's second normal and the squared radius -2 ln u of
+        # the third word
+        twelve = []
+        for b in range(3):
+            twelve += list(oracle_mod.philox4x32_10([3 * (j >> 2) + b, worker, t & 0xFFFFFFFF, t >> 32], key))
+        w = twelve[3 * (j & 3):3 * (j & 3) + 3]
         r, ang = math.sqrt(radius_sq(w[0])), angle(w[1])
         z0, z1 = r * math.cos(ang), r * math.sin(ang)
         want_t = z0 / math.sqrt((z1 * z1 + radius_sq(w[2])) / 3.0)
         got_t = oracle_mod.noise_z(seed, t, worker, j, 2)
         assert abs(got_t - want_t) <= 2e-5 * max(1.0, abs(want_t)), j
     assert oracle_mod.noise_z(seed, t, worker, 5, 0) == 0.0
+
+
+def test_the_four_t3_draws_of_a_quad_are_uncorrelated(oracle_mod):
+    z = oracle_mod.noise_fill(4, 22, 0, 0, 400_000, 2).astype(np.float64).reshape(-1, 4)
+    # t(3) has no finite fourth moment: compare ranks (Spearman) of the values and of their magnitudes
+    for cols in (z, np.abs(z)):
+        rho = stats.spearmanr(cols).statistic
+        assert np.abs(rho - np.eye(4)).max() < 1e-2
 
 
 def test_the_four_normals_of_a_block_are_uncorrelated(oracle_mod):
