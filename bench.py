@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 VALU_NOMINAL_TINSTR = 256 * 64 * 2.4e9 / 1e12
 # vector lane-instructions k_grad executes per noise draw, by noise kind: SQ_INSTS_VALU x 64 / draws
 # (profiles/k_grad_C3_valu.txt)
-VALU_PER_DRAW = {2: 171.8}
+VALU_PER_DRAW = {2: 162.2}
 
 # algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
 ALGO_BYTES_PER_ELEM = {
