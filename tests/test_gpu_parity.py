@@ -479,3 +479,40 @@ def test_heterogeneous_objectives(ddef, oracle_mod, fuse):
         g.apply_delayed(w.lr); o.apply_delayed()
         assert_model_equal(g, o, what=("non-iid", fuse, t))
     g.close()
+
+
+# ---- seeded sweep over small shapes ---------------------------------------------------------------
+def test_seeded_sweep_of_small_shapes(ddef, oracle_mod):
+    """Forty seeded configurations with d from 1 to a few thousand (ragged quads, groups, chunks and
+    tiles), every noise kind, both server states, tau and delta changing in mid-run."""
+    rng = np.random.default_rng(20250717)
+    for case in range(40):
+        d = int(rng.choice([1, 2, 3, 5, 63, 64, 255, 256, 257, 1023, 1025, 4095, 4096, 4097, 5000, 9000, 20011]))
+        n = int(rng.integers(1, 6))
+        tau_max = int(rng.integers(0, 4))
+        kind = int(rng.integers(0, 3))
+        queue = bool(rng.integers(0, 2))
+        w = workloads.replace(workloads.get("C1", d=d, n=n), seed=1000 + case, noise_kind=kind,
+                              noise_scale=float(rng.choice([0.0, 0.05, 0.5])) if kind else 0.0)
+        lam, xstar, x0 = workloads.make_problem(w)
+        g = ddef.Context(d, n, tau_max, queue_form=queue)
+        o = oracle_mod.QueueOracle(d, n, tau_max) if queue else oracle_mod.Oracle(d, n, tau_max)
+        for h in (g, o):
+            h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        what = dict(case=case, d=d, n=n, tau_max=tau_max, kind=kind, queue=queue)
+        for t in range(int(rng.integers(3, 9))):
+            tau = int(rng.integers(0, tau_max + 1))
+            delta = float(rng.choice([1e-4, 0.003, 0.01, 0.1, 0.5, 1.0]))
+            lr = float(rng.choice([0.05, 0.3]))
+            g.set_tau(tau); o.set_tau(tau)
+            g.step(delta, lr); o.step(delta, lr)
+            for i in range(n):
+                gi, gv = g.get_message(i)
+                oi, ov = o.get_message(i)
+                assert np.array_equal(gi, oi), (what, t, i)
+                assert np.array_equal(bits(gv), bits(ov)), (what, t, i)
+                assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), (what, t, i)
+            assert np.array_equal(bits(g.get_update()), bits(o.get_update())), (what, t)
+            assert np.array_equal(bits(g.get_model()), bits(o.get_model())), (what, t)
+        g.close()
+        o.close()
