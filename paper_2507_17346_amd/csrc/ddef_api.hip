@@ -688,7 +688,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
     if (use_filter && c->bound_k != k)
         LAUNCH(c, SL_REBOUND, k_rebound, dim3((n + 255u) / 256u), dim3(256), (const SelState*)c->sel, n,
-               (uint32_t)c->bound_k, (uint32_t)k, (uint32_t)kb, bound, zero_at);
+               (uint32_t)c->bound_k, (uint32_t)kb, bound, zero_at);
     const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
     if (c->grad_pending) {
         LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,

@@ -90,7 +90,7 @@ __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt
 __global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
                              uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound, uint32_t* zero_at,
                              uint32_t* cand_count, uint32_t* overflow);
-__global__ void k_rebound(const SelState* sel, uint32_t n, uint32_t k_old, uint32_t k_new, uint32_t kb_new,
+__global__ void k_rebound(const SelState* sel, uint32_t n, uint32_t k_old, uint32_t kb_new,
                           uint32_t* bound, uint32_t* zero_at);
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,

@@ -872,7 +872,7 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
 // of time in this iteration (zero_at = infinity).  As always the bound only decides which search
 // runs.  One thread per worker.
 __global__ __launch_bounds__(256) void k_rebound(const SelState* __restrict__ sel, uint32_t n, uint32_t k_old,
-                                                 uint32_t k_new, uint32_t kb_new,
+                                                 uint32_t kb_new,
                                                  uint32_t* __restrict__ bound, uint32_t* __restrict__ zero_at) {
     const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= n) return;
