@@ -297,8 +297,16 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
     // plain: grid (groups, n).  fused: 1-D grid with the worker index fastest, so that the blocks
     // that need the same lambda / x* / snapshot lines run at about the same time
     if (kFusedGrad) resolve_iteration(src);
-    const uint32_t w = kFusedGrad ? blockIdx.x % n : blockIdx.y;
-    const uint32_t grp = kFusedGrad ? blockIdx.x / n : blockIdx.x;
+    // fused: consecutive block numbers go to different XCDs (round robin over the 8 of them), and the
+    // n blocks of one group read the same lambda / x* / snapshot lines: hand each XCD a contiguous
+    // eighth of the logical blocks, so that those n blocks share one L2
+    uint32_t bid = blockIdx.x;
+    if (kFusedGrad) {
+        const uint32_t per_xcd = gridDim.x >> 3;
+        if (bid < (per_xcd << 3)) bid = (bid & 7u) * per_xcd + (bid >> 3);
+    }
+    const uint32_t w = kFusedGrad ? bid % n : blockIdx.y;
+    const uint32_t grp = kFusedGrad ? bid / n : blockIdx.x;
     const uint32_t lane = threadIdx.x;
     const uint32_t j = grp * 256u + lane * 4u;
     float pv[4] = {0.f, 0.f, 0.f, 0.f};
