@@ -29,8 +29,9 @@
  *   - a context is bound to the HIP device that was current at ddef_init and to one stream;
  *     the four step calls only enqueue work on that stream, the getters and ddef_sync wait
  *     for it.  A context is not thread-safe;
- *   - all arithmetic is IEEE fp32 with every operation rounded separately (no fused
- *     multiply-add), indices are uint32, d < 2^32.
+ *   - all arithmetic of the method is IEEE fp32 with every operation rounded separately (no
+ *     fused multiply-add; the fused steps inside the noise generator are part of its
+ *     definition), indices are uint32, d < 2^32.
  */
 #ifndef DDEF_H
 #define DDEF_H
@@ -90,7 +91,10 @@ int ddef_set_stream(ddef_ctx* ctx, void* hip_stream);
 /* The synthetic objective f(x) = 1/2 sum_j lambda_j (x_j - xstar_j)^2 shared by all workers
  * (IID data) and the start point: copies three host arrays of d floats, sets every snapshot
  * to x0, every error buffer to 0 and t to 0.  Gradient noise xi = noise_scale * z with z a
- * counter-based draw keyed by (seed, t, worker, j): Philox4x32-10, Box-Muller. */
+ * counter-based draw keyed by (seed, t, worker, j): Philox4x32-10 words turned into normals by
+ * Box-Muller (four coordinates to a block) or into Student-t(3) draws (three words each, four
+ * coordinates to three blocks), out of exactly rounded fp32 operations only, so that any
+ * implementation of the same definition reproduces every draw bit for bit. */
 int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_xstar,
                      const float* host_x0, uint64_t seed, int noise_kind, float noise_scale);
 
