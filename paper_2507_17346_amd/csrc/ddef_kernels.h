@@ -13,7 +13,7 @@ constexpr uint32_t kSubs = 256;
 constexpr uint32_t kSubStride = 32;
 // The run table is scanned in spans of this many 256-entry groups (one block each).
 constexpr uint32_t kSpan = 1024;
-constexpr uint32_t kTile = 4096;      // coordinates per block of the dense aggregation
+constexpr uint32_t kTile = 4096;      // coordinates per block of the tile sum
 
 // Per-worker selection state in device memory.
 struct SelState {

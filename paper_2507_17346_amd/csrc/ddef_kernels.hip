@@ -1035,8 +1035,9 @@ __global__ __launch_bounds__(256) void k_msg_offsets(const uint32_t* __restrict_
     off[(uint64_t)w * (ntiles + 1u) + b] = lo;
 }
 
-// With kApply the tile is not stored but used at once: xn = x - tile / n (S5 fused into S4; x and
-// xn may be the same row), so the dense update never goes through HBM.
+// With kApply the tile is not stored but used at once: xn = x - tile / n (S5 fused into S4), so
+// the dense update never goes through HBM.  When x and xn are the same row, only the entries
+// with a non-zero sum are touched.
 template <bool kApply>
 __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
                                                          const uint32_t* __restrict__ idx,
@@ -1049,6 +1050,7 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
     const uint32_t b = blockIdx.x;
     const uint32_t base = b * kTile;
     for (uint32_t q = threadIdx.x; q < kTile; q += 256u) tile[q] = 0.0f;
+    uint32_t entries = 0;                                  // message entries that fall into this tile
     for (uint32_t w0 = 0; w0 < n; w0 += 256u) {
         const uint32_t batch = n - w0 < 256u ? n - w0 : 256u;
         __syncthreads();                                   // tile zeroed / last batch's bounds consumed
@@ -1063,6 +1065,7 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
             const float* rv = val + (uint64_t)(w0 + i) * msg_ld;
             const uint32_t hi = hi_s[i];
             if (lo_s[i] == hi) continue;                   // same for the whole block
+            entries += hi - lo_s[i];
             for (uint32_t m = lo_s[i] + threadIdx.x; m < hi; m += 256u) {
                 const uint32_t at = ri[m] - base;          // < kTile by the choice of lo, hi
                 tile[at] = tile[at] + rv[m];
@@ -1077,6 +1080,17 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
             const uint64_t t = *rows.t_dev;
             x = rows.ring + (t % rows.ring_slots) * rows.ring_ld;
             xn = rows.ring + ((t + 1u) % rows.ring_slots) * rows.ring_ld;
+        }
+        if (x == xn && entries < kTile / 64u) {
+            // one model row updated in place (message-queue form) and few entries: only the
+            // coordinates some message named can change, x - (+0)/n being x itself, so only those
+            // are read and written
+            float* row = xn + (uint64_t)base;
+            for (uint32_t q = threadIdx.x; q < kTile; q += 256u) {
+                const float u = tile[q];
+                if (__float_as_uint(u) != 0u) row[q] = row[q] - u / nf;
+            }
+            return;
         }
         const float4* xin = reinterpret_cast<const float4*>(x + (uint64_t)base);
         float4* xout = reinterpret_cast<float4*>(xn + (uint64_t)base);
