@@ -167,6 +167,17 @@ int ddef_sync(ddef_ctx* ctx);
 int ddef_step_index(ddef_ctx* ctx, uint64_t* t);
 int ddef_get_model(ddef_ctx* ctx, float* host_x);                       /* x_t, d floats  */
 int ddef_set_model(ddef_ctx* ctx, const float* host_x);                 /* overwrite x_t  */
+/* Checkpoint and resume (ring form, between iterations): the state of a run is t, the
+ * snapshots x_{t-age} for age = 0 .. min(t, tau_max) and the error buffers (the problem, tau and
+ * the options are the caller's to set again).  ddef_get_snapshot / ddef_set_snapshot copy one
+ * snapshot (EINVAL when age > tau_max or, for the getter, age > t); ddef_set_step_index sets t.
+ * Restore in this order: ddef_set_problem, ddef_set_step_index, every snapshot, every error
+ * buffer.  A resumed run continues bit for bit like the uninterrupted one (the candidate filter
+ * starts afresh, which only decides which search runs).  The message-queue form keeps state in
+ * its queue that these calls do not cover: ESTATE there. */
+int ddef_get_snapshot(ddef_ctx* ctx, uint32_t age, float* host_x);
+int ddef_set_snapshot(ddef_ctx* ctx, uint32_t age, const float* host_x);
+int ddef_set_step_index(ddef_ctx* ctx, uint64_t t);
 int ddef_get_error(ddef_ctx* ctx, uint32_t worker, float* host_e);
 int ddef_set_error(ddef_ctx* ctx, uint32_t worker, const float* host_e);
 int ddef_get_grad(ddef_ctx* ctx, uint32_t worker, float* host_g);

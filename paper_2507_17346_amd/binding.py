@@ -37,6 +37,9 @@ SIGNATURES = {
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
     "ddef_aggregate": (C.c_int, [_ctx]),
     "ddef_step": (C.c_int, [_ctx, C.c_double, C.c_float]),
+    "ddef_get_snapshot": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_set_snapshot": (C.c_int, [_ctx, C.c_uint32, _f32p]),
+    "ddef_set_step_index": (C.c_int, [_ctx, C.c_uint64]),
     "ddef_device_info": (C.c_int, [_ctx, _u32p, _u32p, _u64p, _u64p, _u32p, _u32p, _u32p, C.c_char_p, C.c_uint32]),
     "ddef_graph_replays": (C.c_int, [_ctx, _u64p]),
     "ddef_apply_delayed": (C.c_int, [_ctx, C.c_float]),
@@ -280,6 +283,18 @@ class Context:
         return {"arch": name.value.decode(), "compute_units": cu.value, "wave_size": wave.value,
                 "lds_bytes_per_cu": lds.value, "memory_bytes": mem.value, "clock_khz": clk.value,
                 "memory_clock_khz": mclk.value, "memory_bus_bits": bus.value}
+
+    def get_snapshot(self, age: int) -> np.ndarray:
+        return self._get(self._lib.ddef_get_snapshot, "ddef_get_snapshot", int(age))
+
+    def set_snapshot(self, age: int, x) -> None:
+        a = np.ascontiguousarray(x, dtype=np.float32)
+        if a.shape != (self.d,):
+            raise ValueError("snapshot must have d entries")
+        self._check(self._lib.ddef_set_snapshot(self._h, int(age), a.ctypes.data_as(_f32p)), "ddef_set_snapshot")
+
+    def set_step_index(self, t: int) -> None:
+        self._check(self._lib.ddef_set_step_index(self._h, int(t)), "ddef_set_step_index")
 
     def graph_replays(self) -> int:
         n = C.c_uint64()

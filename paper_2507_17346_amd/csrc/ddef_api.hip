@@ -889,6 +889,41 @@ int ddef_set_model(ddef_ctx* c, const float* host_x) {
     return copy_row_in(c, c->slot(c->t), host_x);
 }
 
+int ddef_get_snapshot(ddef_ctx* c, uint32_t age, float* host_x) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_x || age > c->tau_max || (uint64_t)age > c->t) return DDEF_EINVAL;
+    if (c->queue_form || c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    return copy_row_out(c, c->slot(c->t - age), host_x);
+}
+
+int ddef_set_snapshot(ddef_ctx* c, uint32_t age, const float* host_x) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_x || age > c->tau_max) return DDEF_EINVAL;
+    if (c->queue_form || c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    rc = drop_prefetch(c);
+    if (rc) return rc;
+    // slots are numbered by iteration modulo the ring size, so ages beyond t wrap harmlessly
+    return copy_row_in(c, c->slot(c->t + (uint64_t)c->ring_slots - age), host_x);
+}
+
+int ddef_set_step_index(ddef_ctx* c, uint64_t t) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!c->problem_set || c->queue_form || c->phase != PH_IDLE) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    rc = drop_prefetch(c);
+    if (rc) return rc;
+    c->t = t;
+    c->have_bound = false;             // the filter bound belonged to another point of the run
+    c->agg_deferred = false;
+    c->k_step = 0;
+    return DDEF_OK;
+}
+
 int ddef_get_error(ddef_ctx* c, uint32_t worker, float* host_e) {
     int rc = check_ctx(c);
     if (rc) return rc;

@@ -516,3 +516,46 @@ def test_seeded_sweep_of_small_shapes(ddef, oracle_mod):
             assert np.array_equal(bits(g.get_model()), bits(o.get_model())), (what, t)
         g.close()
         o.close()
+
+
+# ---- checkpoint and resume -------------------------------------------------------------------------
+@pytest.mark.parametrize("tau,graph", [(0, 0), (3, 0), (2, 1)])
+def test_checkpoint_and_resume_continue_bit_for_bit(ddef, oracle_mod, tau, graph):
+    w = workloads.get("C3", d=120_011, n=3)
+    lam, xstar, x0 = workloads.make_problem(w)
+
+    def fresh():
+        c = ddef.Context(w.d, w.n, tau + 1)
+        c.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        c.set_tau(tau)
+        c.set_option(ddef.OPT_GRAPH, graph)
+        return c
+
+    a = fresh()
+    o = oracle_mod.Oracle(w.d, w.n, tau + 1, threads=3)
+    o.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    o.set_tau(tau)
+    for t in range(9):
+        a.step(0.004, w.lr); o.step(0.004, w.lr)
+    # checkpoint: t, every snapshot still in the ring, every error buffer
+    t_saved = a.t
+    snaps = [a.get_snapshot(age) for age in range(min(t_saved, tau + 1) + 1)]
+    errs = [a.get_error(i) for i in range(w.n)]
+    assert a.raw("get_snapshot", tau + 2, snaps[0].ctypes.data_as(ddef._f32p)) == ddef.EINVAL
+    a.close()
+    # resume in a new context
+    b = fresh()
+    b.set_step_index(t_saved)
+    for age, x in enumerate(snaps):
+        b.set_snapshot(age, x)
+    for i, e in enumerate(errs):
+        b.set_error(i, e)
+    for t in range(7):
+        b.step(0.004, w.lr); o.step(0.004, w.lr)
+        assert_step_state_equal(b, o, w.n, check_grad=False, what=("resumed", tau, t))
+        assert_model_equal(b, o, what=("resumed", tau, t))
+    assert b.t == t_saved + 7
+    b.close()
+    q = ddef.Context(1000, 2, 1, queue_form=True)
+    assert q.raw("set_step_index", 3) == ddef.ESTATE
+    q.close()
