@@ -90,3 +90,27 @@ def test_adaptive_schedule_exercises_ring_and_k(oracle_mod):
     assert len(pairs) == 10
     assert len({p[0] for p in pairs}) >= 4
     assert max(p[1] for p in pairs) / min(p[1] for p in pairs) > 5
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (no C++ in it), and a C program
+    that names every declared function must link against the built library."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = os.path.join(root, "include", "ddef.h")
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header])
+    names = declared_functions()
+    src = tmp_path / "use_all.c"
+    src.write_text('#include "ddef.h"\n#include <stdio.h>\nint main(void) {\n  const void* p[] = {\n'
+                   + "".join(f"    (const void*){n},\n" for n in names)
+                   + "  };\n  printf(\"%d\\n\", (int)(sizeof p / sizeof p[0]));\n  return 0;\n}\n")
+    lib = os.path.join(root, "paper_2507_17346_amd", "libddef.so")
+    if not os.path.exists(lib):
+        pytest.skip("library not built")
+    exe = tmp_path / "use_all"
+    subprocess.check_call([gcc, "-std=gnu99", "-I", os.path.join(root, "include"), str(src), lib, "-o", str(exe),
+                           "-Wl,-rpath," + os.path.dirname(lib), "-Wl,--allow-shlib-undefined"])
