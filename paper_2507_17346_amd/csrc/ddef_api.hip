@@ -21,13 +21,13 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_REBOUND, SL_FILL,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_SAMPLE, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
-    "k_rebound", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
+    "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -66,6 +66,11 @@ struct ddef_ctx {
     uint64_t cap = 0;
     bool have_bound = false;
     uint64_t bound_k = 0;                // the k the bound was placed for
+    uint64_t sel_k = 0;                  // k of the last completed Top-k selection and how many in a row
+    uint32_t sel_run = 0;                //   had it (the threshold trend needs two)
+    float* sample = nullptr;             // [n][sample_ld] strided sample of p (bound_from_sample)
+    uint32_t* sample_total = nullptr;
+    uint64_t sample_ld = 0;
     int compressor = DDEF_COMPRESSOR_TOPK;
     // gradient prefetch: the gradient of iteration t+1 only needs x_{t+1-tau}, which exists as soon
     // as iteration t starts (tau >= 1), so it is generated on a second stream into a second buffer
@@ -378,6 +383,50 @@ int start_prefetch(ddef_ctx* c) {
     return DDEF_OK;
 }
 
+// Places bound[] and zero_at[] for a selection of k (candidate target kb) from every stride-th entry
+// of p = e + lr*g: the radix select of the path, run on the sample for the ranks k/stride and
+// kb/stride.  The stride keeps about 256 sample entries above the bound (count error about 6 %)
+// within a sample of at most kSampleMax entries per worker; with fewer than 8 above the bound
+// sampling says too little, and the iteration goes on with what it had (a whole-row search when
+// there is no bound at all).
+int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr) {
+    constexpr uint64_t kSampleMax = 1u << 20;
+    uint64_t stride = kb / 256u;
+    const uint64_t least = (c->d + kSampleMax - 1u) / kSampleMax;
+    if (stride < least) stride = least;
+    if (stride < 1u) stride = 1u;
+    const uint64_t count = (c->d + stride - 1u) / stride;
+    const uint64_t kb_s = kb / stride, k_s = k / stride > 0u ? k / stride : 1u;
+    if (kb_s < 8u || kb_s > count) return DDEF_OK;
+    const uint32_t n = c->n;
+    if (!c->sample) {
+        c->sample_ld = ((c->d < kSampleMax ? c->d : kSampleMax) + 7u) & ~(uint64_t)3u;
+        HIP_TRY(c, hipMalloc((void**)&c->sample, (size_t)n * c->sample_ld * 4u));
+        HIP_TRY(c, hipMemsetAsync(c->sample, 0, (size_t)n * c->sample_ld * 4u, c->stream));
+        HIP_TRY(c, hipMalloc((void**)&c->sample_total, (size_t)n * 4u));
+        drop_graph(c);
+    }
+    materialize_grad(c);                      // the sample reads g from memory
+    LAUNCH(c, SL_SAMPLE, k_sample_p, dim3((uint32_t)((count + 255u) / 256u), n), dim3(256), (const float*)c->e,
+           (const float*)c->g, c->ld, lr, (uint32_t)stride, (uint32_t)count, c->sample, c->sample_ld);
+    LAUNCH(c, SL_SAMPLE, k_sample_begin, dim3(n), dim3(256), c->sel, n, (uint32_t)k_s, (uint32_t)kb_s,
+           (uint32_t)count, c->sample_total, c->hist);
+    const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sample, (const uint32_t*)nullptr, c->sample_ld,
+                      (const uint32_t*)c->sample_total};
+    const uint32_t gx = blocks_for(c, (count + 1023u) / 1024u, n, 8);
+    for (int level = 0; level < 3; ++level) {
+        uint32_t* h = c->hist + (uint64_t)level * n * 2 * 2048;
+        LAUNCH(c, SL_DIGIT_HIST, k_digit_hist, dim3(gx, n), dim3(256), vs, (const SelState*)c->sel, h, level);
+        LAUNCH(c, SL_DIGIT_PICK, k_digit_pick, dim3(n, 2), dim3(256), c->sel, (const uint32_t*)h, level);
+    }
+    LAUNCH(c, SL_SAMPLE, k_sample_finish, dim3((n + 255u) / 256u), dim3(256), (const SelState*)c->sel, n, c->filt,
+           c->filt + 5 * n);
+    HIP_TRY(c, hipGetLastError());
+    c->have_bound = true;
+    c->bound_k = k;
+    return DDEF_OK;
+}
+
 int check_ctx(ddef_ctx* c) {
     if (!c) return DDEF_EINVAL;
     if (c->sticky != DDEF_OK) return c->sticky;
@@ -503,7 +552,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->bitmap, c->g_next, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -548,6 +597,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     HIP_TRY(c, hipMemset(c->filt, 0, (size_t)6 * c->n * 4));
     HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
     c->have_bound = false;
+    c->sel_k = 0; c->sel_run = 0;
     drop_graph(c);
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
@@ -679,16 +729,21 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
                c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld, (float*)nullptr, (uint64_t)0);
         HIP_TRY(c, hipGetLastError());
         c->have_bound = false;          // a Top-k bound from before no longer describes e
+        c->sel_k = 0; c->sel_run = 0;
         c->k_step = k;
         c->q_k[c->msg_slot] = k;
         c->phase = PH_COMPRESSED;
         return DDEF_OK;
     }
-    // the filter needs a bound from an earlier selection and pays off only for sparse messages
-    const bool use_filter = !c->opt_force_full && c->have_bound && 2 * kb <= c->d;
-    if (use_filter && c->bound_k != k)
-        LAUNCH(c, SL_REBOUND, k_rebound, dim3((n + 255u) / 256u), dim3(256), (const SelState*)c->sel, n,
-               (uint32_t)c->bound_k, (uint32_t)kb, bound, zero_at);
+    // the filter pays off only for sparse messages and needs a bound: the last selection's, or,
+    // where that was placed for another k or there was none, one from a sample of this p
+    // (or the last selections' bound has no trend behind it yet: the first two iterations with a k)
+    const bool can_filter = !c->opt_force_full && 2 * kb <= c->d;
+    if (can_filter && (!c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
+        rc = bound_from_sample(c, k, kb, lr);
+        if (rc) return rc;
+    }
+    const bool use_filter = can_filter && c->have_bound;
     const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
     if (c->grad_pending) {
         LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
@@ -716,6 +771,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     enqueue_select(c, (uint32_t)k, (uint32_t)kb);
     c->have_bound = true;
     c->bound_k = k;
+    if (c->sel_k == k) { if (c->sel_run < 2u) c->sel_run += 1u; } else { c->sel_k = k; c->sel_run = 1u; }
     HIP_TRY(c, hipGetLastError());
     c->k_step = k;
     c->q_k[c->msg_slot] = k;
@@ -794,10 +850,11 @@ int ddef_step(ddef_ctx* c, double delta, float lr) {
     uint32_t lr_bits;
     std::memcpy(&lr_bits, &lr, 4);
     // A steady iteration only: ring form, Top-k, not empty, a filter bound placed for this very k
-    // (so that neither the whole-row start nor k_rebound is part of it), nothing to reallocate,
+    // (so that neither a whole-row start nor the sampling of a new bound is part of it), nothing to reallocate,
     // no per-launch events, no second stream.
     const bool steady = c->opt_graph && !c->queue_form && c->compressor == DDEF_COMPRESSOR_TOPK &&
                         !c->profiling && !c->opt_prefetch && c->t >= c->tau && c->have_bound && c->bound_k == k &&
+                        c->sel_k == k && c->sel_run >= 2u &&
                         k <= c->msg_ld && candidate_capacity(c, k, kb) <= c->cap;
     if (!steady) return step_eager(c, delta, lr);
     DeviceGuard guard(c->device);
@@ -919,6 +976,7 @@ int ddef_set_step_index(ddef_ctx* c, uint64_t t) {
     if (rc) return rc;
     c->t = t;
     c->have_bound = false;             // the filter bound belonged to another point of the run
+    c->sel_k = 0; c->sel_run = 0;
     c->agg_deferred = false;
     c->k_step = 0;
     return DDEF_OK;

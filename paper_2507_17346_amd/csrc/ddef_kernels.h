@@ -26,8 +26,6 @@ struct SelState {
     uint32_t T_prev;      // threshold pattern of the selection before the last one
     uint32_t k_prev;      // its k (0: none)
     uint32_t zero_used;   // candidates at or above this pattern were written to e as +0 ahead of time
-    uint32_t nb_rank;     // rank at which next_bound was measured in the last selection
-    float trend;          // factor by which the last selection moved its bound for the threshold's trend
 };
 
 // Where the selection kernels find a worker's entries: its whole row of e (d entries, the
@@ -90,8 +88,11 @@ __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt
 __global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
                              uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound, uint32_t* zero_at,
                              uint32_t* cand_count, uint32_t* overflow);
-__global__ void k_rebound(const SelState* sel, uint32_t n, uint32_t k_old, uint32_t kb_new,
-                          uint32_t* bound, uint32_t* zero_at);
+__global__ void k_sample_p(const float* e, const float* g, uint64_t ld, float lr, uint32_t stride, uint32_t count,
+                           float* sample, uint64_t sample_ld);
+__global__ void k_sample_begin(SelState* sel, uint32_t n, uint32_t k_s, uint32_t kb_s, uint32_t count,
+                               uint32_t* sample_total, uint32_t* hist);
+__global__ void k_sample_finish(const SelState* sel, uint32_t n, uint32_t* bound, uint32_t* zero_at);
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,
                              float* msg_val, uint64_t msg_ld, uint32_t k);

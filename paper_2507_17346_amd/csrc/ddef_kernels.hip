@@ -850,13 +850,6 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
         const float moved_T = __uint_as_float(T) * ratio;
         if (moved_T > 0.0f && moved_T < 3.0e38f) nz = __float_as_uint(moved_T);
     }
-    // what the last selection measured, for k_rebound: the pattern sel[w].next_bound sits at this rank
-    {
-        const uint32_t view = sel[w].active == 0u ? cand_total[w] : 0xffffffffu;
-        sel[w].nb_rank = kb < view ? kb : view;
-        sel[w].trend = (sel[w].next_bound != 0u && nb != 0u)
-                           ? __uint_as_float(nb) / __uint_as_float(sel[w].next_bound) : 1.0f;
-    }
     sel[w].T_prev = T;
     sel[w].k_prev = k;
     sel[w].seen = cand_total[w];
@@ -865,41 +858,41 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
     overflow[w] = 0u;
 }
 
-// k changed since the last selection (Algorithm 2 re-chooses delta): the bound was placed for
-// the old k.  The magnitudes of e + lr*g are distributed much as in the last iteration,
-// whatever k is, and the last selection measured two points of that distribution's tail: the
-// pattern T at rank k_old and the pattern B at rank rank_B > k_old.
-//   kb_new <= k_old:  the bound goes to the threshold expected for the old k, which catches
-//     about k_old >= kb_new entries (the buffers still have room for the old k's candidates).
-//     Above T the tail cannot be extrapolated: it was cut off when the last message was sent.
-//   k_old < kb_new <= rank_B:  a power law through the two points (ln count linear in
-//     ln magnitude), evaluated between them.
-//   kb_new > rank_B:  the same law continued below B with 0.4 times its exponent (towards the
-//     bulk the tail flattens; measured on the Student-t workload a tenfold k needed about that).
-// The factor the old bound carried for the threshold's trend is kept.  Nothing is cleared ahead
-// of time in this iteration (zero_at = infinity).  As always the bound only decides which search
-// runs.  One thread per worker.
-__global__ __launch_bounds__(256) void k_rebound(const SelState* __restrict__ sel, uint32_t n, uint32_t k_old,
-                                                 uint32_t kb_new,
-                                                 uint32_t* __restrict__ bound, uint32_t* __restrict__ zero_at) {
+// Filter bound from a sample.  Where no bound fits the coming selection (the first iteration, or k
+// changed: Algorithm 2 re-chooses delta), every `stride`-th entry of p = e + lr*g is computed ahead
+// of the accumulate pass, and the radix select of S2 runs on that sample for the ranks
+// k / stride and kb / stride: the patterns found there estimate the threshold and the pattern at
+// the candidate target for the whole row (the count above the bound then misses its target by
+// about 1 / sqrt(kb / stride), far inside the usable window [k, 3 kb]).  As always the bound only
+// decides which search runs; the selection that follows is exact.
+__global__ __launch_bounds__(256) void k_sample_p(const float* __restrict__ e, const float* __restrict__ g,
+                                                  uint64_t ld, float lr, uint32_t stride, uint32_t count,
+                                                  float* __restrict__ sample, uint64_t sample_ld) {
+    const uint32_t w = blockIdx.y;
+    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= count) return;
+    const uint64_t at = (uint64_t)w * ld + (uint64_t)s * stride;           // s * stride < d
+    sample[(uint64_t)w * sample_ld + s] = e[at] + lr * g[at];
+}
+
+// One block per worker: the sample becomes the worker's view and the selection starts.
+__global__ __launch_bounds__(256) void k_sample_begin(SelState* __restrict__ sel, uint32_t n, uint32_t k_s,
+                                                      uint32_t kb_s, uint32_t count,
+                                                      uint32_t* __restrict__ sample_total,
+                                                      uint32_t* __restrict__ hist) {
+    const uint32_t w = blockIdx.x;
+    if (threadIdx.x == 0) { sel[w].active = 0u; sample_total[w] = count; }
+    begin_selection(sel, w, n, k_s, kb_s, count, hist);
+}
+
+// One thread per worker: rank kb_s of the sample places the bound, rank k_s the expected threshold.
+__global__ __launch_bounds__(256) void k_sample_finish(const SelState* __restrict__ sel, uint32_t n,
+                                                       uint32_t* __restrict__ bound,
+                                                       uint32_t* __restrict__ zero_at) {
     const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= n) return;
-    const uint32_t expected_T = zero_at[w];
-    zero_at[w] = 0x7f800000u;
-    if (kb_new <= k_old) {
-        if (expected_T != 0u && expected_T < 0x7f800000u) bound[w] = expected_T;
-        return;
-    }
-    const uint32_t T = sel[w].T, B = sel[w].next_bound, rank_B = sel[w].nb_rank;
-    if (T == 0u || B == 0u || B >= T || T >= 0x7f800000u || rank_B <= k_old) return;
-    const float lt = __logf(__uint_as_float(T)), lb = __logf(__uint_as_float(B));
-    const float slope = (__logf((float)rank_B) - __logf((float)k_old)) / (lt - lb);   // -d ln count / d ln x
-    if (!(slope > 0.05f && slope < 400.0f)) return;
-    float ln_x;
-    if (kb_new <= rank_B) ln_x = lt - (__logf((float)kb_new) - __logf((float)k_old)) / slope;
-    else ln_x = lb - (__logf((float)kb_new) - __logf((float)rank_B)) / (0.4f * slope);
-    const float x = __expf(ln_x) * sel[w].trend;
-    if (x > 0.0f && x < 3.0e38f) bound[w] = __float_as_uint(x);
+    bound[w] = sel[w].next_bound;
+    zero_at[w] = sel[w].T;
 }
 
 // One block of 1024 threads per worker walks the chunk counts in order and turns them into

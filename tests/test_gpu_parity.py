@@ -219,8 +219,8 @@ def test_changing_k_keeps_the_candidate_filter(ddef, oracle_mod):
         g.step(delta, w.lr); o.step(delta, w.lr)
         assert_step_state_equal(g, o, w.n, check_grad=False, what=("k change", t, delta))
         assert_model_equal(g, o, what=("k change", t))
-    # the first two iterations search the rows (no bound, then no trend); the changes of k must not
-    assert g.full_select_count() <= 2 * w.n + w.n, g.full_select_count()
+    # neither the first iterations nor the changes of k need a whole-row search
+    assert g.full_select_count() == 0, g.full_select_count()
     g.close()
 
 
@@ -313,9 +313,9 @@ def test_filter_path_is_used_and_matches_full_search(ddef, oracle_mod):
         assert_step_state_equal(b, o, w.n, what=("full", t))
         assert_model_equal(a, o, what=("filter", t))
     assert b.full_select_count() == steps * w.n
-    # the first step has no bound and the second no trend yet; afterwards the filter should
-    # carry nearly every selection
-    assert a.full_select_count() <= 3 * w.n, a.full_select_count()
+    # the first two bounds come from samples of p, the later ones from the selections before them:
+    # the filter carries every selection
+    assert a.full_select_count() == 0, a.full_select_count()
     a.close(); b.close()
 
 
@@ -339,13 +339,12 @@ def test_filter_bound_too_high_and_too_low_fall_back(ddef, oracle_mod):
         g.aggregate(); o.aggregate(); g.apply_delayed(1.0); o.apply_delayed()
         assert_model_equal(g, o, what=("scale", step))
         fulls.append(g.full_select_count())
-    # step 0: no bound. step 2: magnitudes dropped 1000x -> too few candidates. step 4: rose
-    # 10^6x -> candidate buffer overflows.  Each must have taken the whole-row search.
-    assert fulls[0] == n and fulls[1] == n
-    assert fulls[2] == 2 * n and fulls[3] == 2 * n
-    assert fulls[4] == 3 * n and fulls[5] == 3 * n
-    # step 12: 15 % smaller -> fewer than k candidates, a good part of them above the expected
-    # threshold (already cleared from e by the accumulate pass and put back for the row search)
+    # steps 0 and 1 place their bound from a sample of p and need no row search.  step 2: magnitudes
+    # dropped 1000x -> too few candidates.  step 4: rose 10^6x -> candidate buffer overflows.  Each of
+    # these must have taken the whole-row search, and the step after it must not.
+    assert fulls[0] == 0 and fulls[1] == 0
+    assert fulls[2] == n and fulls[3] == n
+    assert fulls[4] == 2 * n and fulls[5] == 2 * n
     assert fulls[11] == fulls[10] and fulls[12] == fulls[11] + n
     g.close()
 
