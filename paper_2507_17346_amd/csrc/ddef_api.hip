@@ -385,13 +385,13 @@ int start_prefetch(ddef_ctx* c) {
 
 // Places bound[] and zero_at[] for a selection of k (candidate target kb) from every stride-th entry
 // of p = e + lr*g: the radix select of the path, run on the sample for the ranks k/stride and
-// kb/stride.  The stride keeps about 256 sample entries above the bound (count error about 6 %)
-// within a sample of at most kSampleMax entries per worker; with fewer than 8 above the bound
-// sampling says too little, and the iteration goes on with what it had (a whole-row search when
-// there is no bound at all).
-int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr) {
+// kb/stride.  The stride keeps about `above` sample entries above the bound (count error about
+// 1/sqrt(above)) within a sample of at most kSampleMax entries per worker; with fewer than 8 above
+// the bound sampling says too little, and the iteration goes on with what it had (a whole-row
+// search when there is no bound at all).
+int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t above) {
     constexpr uint64_t kSampleMax = 1u << 20;
-    uint64_t stride = kb / 256u;
+    uint64_t stride = kb / above;
     const uint64_t least = (c->d + kSampleMax - 1u) / kSampleMax;
     if (stride < least) stride = least;
     if (stride < 1u) stride = 1u;
@@ -737,10 +737,14 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     // the filter pays off only for sparse messages and needs a bound: the last selection's, or,
     // where that was placed for another k or there was none, one from a sample of this p
-    // (or the last selections' bound has no trend behind it yet: the first two iterations with a k)
+    // (or the last selections' bound has no trend behind it yet: the first two iterations with a k).
+    // Dense messages (k/d > 1/32) sample every time, and more finely: there the entries between the
+    // expected and the true threshold each cost a scattered store in the compaction, many enough
+    // to outweigh the sampling by far, and the trend of noisy thresholds misses by more.
     const bool can_filter = !c->opt_force_full && 2 * kb <= c->d;
-    if (can_filter && (!c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
-        rc = bound_from_sample(c, k, kb, lr);
+    const bool dense = k * 32u > c->d;
+    if (can_filter && (dense || !c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
+        rc = bound_from_sample(c, k, kb, lr, dense ? 4096u : 256u);
         if (rc) return rc;
     }
     const bool use_filter = can_filter && c->have_bound;
@@ -854,7 +858,7 @@ int ddef_step(ddef_ctx* c, double delta, float lr) {
     // no per-launch events, no second stream.
     const bool steady = c->opt_graph && !c->queue_form && c->compressor == DDEF_COMPRESSOR_TOPK &&
                         !c->profiling && !c->opt_prefetch && c->t >= c->tau && c->have_bound && c->bound_k == k &&
-                        c->sel_k == k && c->sel_run >= 2u &&
+                        c->sel_k == k && c->sel_run >= 2u && k * 32u <= c->d &&
                         k <= c->msg_ld && candidate_capacity(c, k, kb) <= c->cap;
     if (!steady) return step_eager(c, delta, lr);
     DeviceGuard guard(c->device);
