@@ -943,6 +943,9 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
                                                     float* __restrict__ msg_val, uint64_t msg_ld,
                                                     uint32_t k) {
     __shared__ uint32_t lds[5];
+    // the entries a round of the block sends are gathered here and leave with contiguous stores
+    __shared__ uint32_t out_idx[1024];
+    __shared__ float out_val[1024];
     const uint32_t w = blockIdx.y;
     const View v = view_of(vs, sel, w);
     const uint32_t nchunks = (v.count + 4095u) >> 12;
@@ -983,19 +986,26 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
                 nsend += take;
             }
             uint32_t send_total;
-            uint32_t pos = out_run + block_excl_scan(nsend, lds, &send_total);
+            uint32_t at = block_excl_scan(nsend, lds, &send_total);   // position inside this round
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const bool cleared = key[m] >= zero_used;          // already +0 in e
                 if (send[m]) {
                     const uint32_t coord = v.map ? v.map[j + m] : j + m;
-                    if (pos < k) { oi[pos] = coord; ov[pos] = vv[m]; }
-                    ++pos;
+                    out_idx[at] = coord;
+                    out_val[at] = vv[m];
+                    ++at;
                     if (!cleared) erow[coord] = 0.0f;
                 } else if (valid[m] && cleared) {
                     erow[v.map[j + m]] = vv[m];
                 }
             }
+            __syncthreads();
+            for (uint32_t q = threadIdx.x; q < send_total; q += blockDim.x) {
+                const uint32_t pos = out_run + q;
+                if (pos < k) { oi[pos] = out_idx[q]; ov[pos] = out_val[q]; }
+            }
+            __syncthreads();
             eq_run += eq_total;
             out_run += send_total;
         }
