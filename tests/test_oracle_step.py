@@ -329,3 +329,29 @@ def test_stepwise_queue_form_non_iid_matches_ring_form(oracle_mod):
     for t in range(T):
         plain.step(delta, lr)
     assert not np.array_equal(bits(plain.get_model()), bits(q.get_model()))
+
+
+def test_ring_form_changing_tau_is_delayed_sgd_at_delta_one(oracle_mod):
+    """Ring form under a changing tau, delta = 1 (every e_i stays zero): iteration t applies
+    lr * g(x_{t - tau_t}) with the noise of iteration t, or nothing while t - tau_t < 0: replayed in
+    numpy from the stored iterates."""
+    w, lam, xstar, x0 = small_problem(seed=63, d=650, n=3)
+    lr = 0.05
+    taus = [0, 1, 1, 3, 2, 0, 3, 3, 1, 2, 0, 1]
+    o = make_oracle(oracle_mod, w, lam, xstar, x0, 0, tau_max=3)
+    xs = [x0.copy()]
+    for t, tau in enumerate(taus):
+        o.set_tau(tau)
+        o.step(1.0, lr)
+        x = xs[-1]
+        upd = np.zeros(w.d, dtype=F32)
+        if t - tau >= 0:
+            stale = xs[t - tau]
+            for i in range(w.n):
+                z = oracle_mod.noise_fill(w.seed, t, i, 0, w.d, w.noise_kind)
+                upd = upd + F32(lr) * (lam * (stale - xstar) + F32(w.noise_scale) * z)
+        xs.append(x - upd / F32(w.n))
+        assert np.array_equal(bits(o.get_update()), bits(upd)), t
+        assert np.array_equal(bits(o.get_model()), bits(xs[-1])), t
+        for i in range(w.n):
+            assert np.all(bits(o.get_error(i)) == 0)
