@@ -32,8 +32,9 @@
 // identity, the Top-k contraction bound, delta=1/tau=0 -> D-SGD, delta=1 -> delayed SGD,
 // the closed form (1-lr*lambda)^t on the noiseless quadratic, ring form == queue form,
 // Philox known answers, the noise transform against libm, DeCo's degenerate values and
-// Theorem 3 against the recurrence.  The trajectory under a *changing* tau has no pin
-// other than the invariants (the paper fixes none): parity unpinned for that case.
+// Theorem 3 against the recurrence.  Under a *changing* tau both forms are pinned at
+// delta = 1 (numpy replays of SGD with a time-varying delay) and by the invariants; with
+// delta < 1 the paper fixes no trajectory: parity unpinned for that case.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
