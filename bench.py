@@ -40,6 +40,42 @@ ALGO_BYTES_PER_ELEM = {
 }
 
 
+class HipEvents:
+    """HIP events on a stream of this process's own, through the HIP runtime's C API: the time the
+    GPU spends between two points of the stream, without the host's waits in it."""
+
+    def __init__(self):
+        import ctypes as C
+        self.C = C
+        self.hip = C.CDLL("libamdhip64.so")
+        self.stream = C.c_void_p()
+        self._ok(self.hip.hipStreamCreateWithFlags(C.byref(self.stream), C.c_uint(1)), "hipStreamCreateWithFlags")  # non-blocking
+        self.events = []
+
+    def _ok(self, rc, what):
+        if rc != 0:
+            raise RuntimeError(f"{what} failed with HIP error {rc}")
+
+    def mark(self):
+        ev = self.C.c_void_p()
+        self._ok(self.hip.hipEventCreate(self.C.byref(ev)), "hipEventCreate")
+        self._ok(self.hip.hipEventRecord(ev, self.stream), "hipEventRecord")
+        self.events.append(ev)
+        return len(self.events) - 1
+
+    def ms(self, a, b):
+        out = self.C.c_float()
+        self._ok(self.hip.hipEventSynchronize(self.events[b]), "hipEventSynchronize")
+        self._ok(self.hip.hipEventElapsedTime(self.C.byref(out), self.events[a], self.events[b]), "hipEventElapsedTime")
+        return float(out.value)
+
+    def close(self):
+        for ev in self.events:
+            self.hip.hipEventDestroy(ev)
+        self.events = []
+        self.hip.hipStreamDestroy(self.stream)
+
+
 def measured_traffic(kernel, workload_name, key="traffic_bytes_per_launch"):
     """HBM bytes from the committed hardware-counter summary (rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE, scaled by the copy yardstick): per launch of `kernel`, or with another key the
@@ -233,6 +269,28 @@ def main():
     phase_ms = {k: 1e3 * v / args.steps for k, v in phase.items()}
     phase_median = {k: sorted(v)[len(v) // 2] for k, v in samples.items()}
     phase_min = {k: min(v) for k, v in samples.items()}
+
+    # ---- and once more with HIP events around each call on the stream, no host wait in between:
+    # the time the GPU needs per call, launch gaps between its kernels included
+    ctx.sync()
+    hev = HipEvents()
+    ctx.set_stream(hev.stream.value)
+    marks = []
+    floor_bytes_sum = 0.0
+    for _ in range(args.steps):
+        delta = begin_iteration()
+        floor_bytes_sum += (12.0 + 24.0 * (w.k(delta) / w.d) + 16.0 / w.n) * w.n * w.d
+        row = [hev.mark()]
+        for call in (ctx.grad, lambda: ctx.ef_compress(delta, w.lr), ctx.aggregate, lambda: ctx.apply_delayed(w.lr)):
+            call()
+            row.append(hev.mark())
+        marks.append(row)
+    ctx.sync()
+    gpu_ms = {name: sum(hev.ms(r[i], r[i + 1]) for r in marks) / args.steps
+              for i, name in enumerate(("grad", "ef_compress", "aggregate", "apply_delayed"))}
+    ctx.set_stream(None)
+    hev.close()
+    log("  per call, GPU time between HIP events (ms): " + ", ".join(f"{k} {v:.3f}" for k, v in gpu_ms.items()))
     full0 = ctx.full_select_count()
     ctx.profile_enable(True)
     for _ in range(args.steps):
@@ -292,9 +350,10 @@ def main():
             grad_info["nominal_valu_T_lane_instr_per_s"] = VALU_NOMINAL_TINSTR
 
     # metric of the path proper (EF + top-k + aggregate + apply), gradient generation aside
-    path_ms = phase_ms["ef_compress"] + phase_ms["aggregate"] + phase_ms["apply_delayed"]
+    path_ms = gpu_ms["ef_compress"] + gpu_ms["aggregate"] + gpu_ms["apply_delayed"]
     floor_bytes = floor_bytes_sum / args.steps
-    path = {"ms": path_ms, "elements_per_s": elems / (path_ms * 1e-3),
+    path = {"ms": path_ms, "ms_with_host_waits": phase_ms["ef_compress"] + phase_ms["aggregate"] + phase_ms["apply_delayed"],
+            "elements_per_s": elems / (path_ms * 1e-3),
             "floor_bytes_per_step": floor_bytes,
             "floor_GBps": floor_bytes / (path_ms * 1e-3) / 1e9,
             "floor_frac_of_peak": floor_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -322,6 +381,7 @@ def main():
         "roofline": roofline,
         "grad": grad_info,
         "ef_topk_aggregate_apply": path,
+        "ms_per_call_gpu_events": gpu_ms,
         "ms_per_call": phase_ms,
         "ms_per_call_median": phase_median,
         "ms_per_call_min": phase_min,
