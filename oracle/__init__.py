@@ -76,6 +76,9 @@ def lib():
         "oracle_randk_permute": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]),
         "oracle_murmur_fmix32": (C.c_uint32, [C.c_uint32]),
         "oracle_set_compressor": (None, [vp, C.c_int]),
+        "oracle_set_composed": (None, [vp, C.c_double]),
+        "oracle_quantize4": (None, [f32p, C.c_uint64, C.POINTER(C.c_uint8), f32p, f32p]),
+        "oracle_get_message_codes": (None, [vp, C.c_uint32, C.POINTER(C.c_uint8), f32p]),
         "oracle_set_heterogeneity": (None, [vp, C.c_float]),
         "oracle_phi_prime": (C.c_double, [C.c_double, C.c_double]),
         "oracle_deco_noniid": (C.c_int, [C.c_double] * 4 + [u32p, C.POINTER(C.c_double)]),
@@ -182,6 +185,18 @@ def randk_permute(seed, t, worker, d, m) -> int:
     return int(lib().oracle_randk_permute(int(seed), int(t), int(worker), int(d), int(m)))
 
 
+def quantize4(values):
+    """4-bit block quantiser of a message: (packed codes, block steps, decoded values)."""
+    v, vp_ = _f32(values)
+    k = v.size
+    codes = np.zeros((k + 1) // 2, dtype=np.uint8)
+    steps = np.zeros((k + 255) // 256, dtype=np.float32)
+    deq = np.zeros(k, dtype=np.float32)
+    lib().oracle_quantize4(vp_, k, codes.ctypes.data_as(C.POINTER(C.c_uint8)),
+                           steps.ctypes.data_as(C.POINTER(C.c_float)), deq.ctypes.data_as(C.POINTER(C.c_float)))
+    return codes, steps, deq
+
+
 def murmur_fmix32(h: int) -> int:
     return int(lib().oracle_murmur_fmix32(C.c_uint32(h)))
 
@@ -282,8 +297,21 @@ class Oracle:
         lib().oracle_set_heterogeneity(self._h, float(zeta))
 
     def set_compressor(self, kind):
-        """0: Top-k (default), 1: Random-k."""
+        """0: Top-k (default), 1: Random-k, 2: composed (Random-k, Top-k inside it, 4-bit codes)."""
         lib().oracle_set_compressor(self._h, int(kind))
+
+    def set_composed(self, rand_ratio):
+        """Share of the coordinates the Random-k stage of the composed compressor keeps."""
+        lib().oracle_set_composed(self._h, float(rand_ratio))
+
+    def get_message_codes(self, w):
+        """Wire form of worker w's last composed message: packed 4-bit codes and block steps."""
+        k = int(lib().oracle_message_size(self._h, int(w)))
+        codes = np.zeros((k + 1) // 2, dtype=np.uint8)
+        steps = np.zeros((k + 255) // 256, dtype=np.float32)
+        lib().oracle_get_message_codes(self._h, int(w), codes.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                       steps.ctypes.data_as(C.POINTER(C.c_float)))
+        return codes, steps
 
     @property
     def t(self):

@@ -16,6 +16,7 @@
 //   EF accumulate     p = e + gamma*g                         Algorithm 1, worker side
 //   compressor        Top-k of p, k = ceil(delta*d)           Section 5.2 "Baselines"; Top-k lemma
 //   other sparsifier  Random-k: k entries chosen at random    Appendix "Experiment Results with other sparsifiers"
+//   composed          Random-k, Top-k inside it, 4-bit codes  Section 5.1 "Baselines" (the strongest static baseline's compressor)
 //   residual          e' = e + gamma*g - Delta                Algorithm 1, worker side
 //   server update     x' = x - (1/n) sum_i Delta_i            Algorithm 1, server side
 //   start-up          Delta_{t-tau} = 0 while t-tau < 0       Section 3.2, boundary convention
@@ -32,7 +33,10 @@
 // identity, the Top-k contraction bound, delta=1/tau=0 -> D-SGD, delta=1 -> delayed SGD,
 // the closed form (1-lr*lambda)^t on the noiseless quadratic, ring form == queue form,
 // Philox known answers, the noise transform against libm, DeCo's degenerate values and
-// Theorem 3 against the recurrence.  Under a *changing* tau both forms are pinned at
+// Theorem 3 against the recurrence.  The composed compressor (tests/test_oracle_composed.py):
+// its selection against a numpy sort of the Random-k subset, its quantiser against a hand-worked
+// block, the nearest-level property by brute force over all 15 levels, the case whose values lie
+// on the 4-bit grid (lossless: equals plain Top-k), conservation and the contraction.  Under a *changing* tau both forms are pinned at
 // delta = 1 (numpy replays of SGD with a time-varying delay) and by the invariants; with
 // delta < 1 the paper fixes no trajectory: parity unpinned for that case.
 #include <algorithm>
@@ -246,6 +250,41 @@ void randk_select(uint64_t seed, uint64_t t, uint32_t worker, uint64_t d, uint64
     std::sort(idx_out, idx_out + k);
 }
 
+// ---------------------------------------------------------------------------------
+// 4-bit quantiser of a message (composed compressor, third stage).  The paper names the stage
+// and nothing else, so this is a reading: the values, in message order (ascending coordinate),
+// are cut into blocks of 256; a block's step is (largest magnitude in the block) / 7, a value's
+// code the integer nearest to value / step (halves to the even one) kept inside [-7, 7], and
+// the receiver's value is code * step.  A block whose step comes out as zero (all values zero,
+// or so tiny that max/7 rounds to zero) sends only zero codes.  Two codes share a byte: the
+// even position in the low nibble, two's complement.
+// codes: (count+1)/2 bytes, steps: (count+255)/256 floats, deq: count floats.
+// ---------------------------------------------------------------------------------
+constexpr uint64_t kQuantBlock = 256;
+
+void quantize4(const float* v, uint64_t count, uint8_t* codes, float* steps, float* deq) {
+    for (uint64_t m = 0; m < (count + 1) / 2; ++m) codes[m] = 0;
+    for (uint64_t b0 = 0; b0 < count; b0 += kQuantBlock) {
+        const uint64_t b1 = std::min(count, b0 + kQuantBlock);
+        float largest = 0.0f;
+        for (uint64_t m = b0; m < b1; ++m) largest = std::max(largest, std::fabs(v[m]));
+        const float step = largest / 7.0f;
+        steps[b0 / kQuantBlock] = step;
+        for (uint64_t m = b0; m < b1; ++m) {
+            int q = 0;
+            if (step > 0.0f) {
+                float ratio = v[m] / step;
+                float nearest = std::nearbyint(ratio);          // default rounding mode: halves to even
+                if (nearest > 7.0f) nearest = 7.0f;
+                if (nearest < -7.0f) nearest = -7.0f;
+                q = (int)nearest;
+            }
+            deq[m] = (float)q * step;
+            codes[m / 2] |= (uint8_t)((q & 0xf) << ((m & 1) * 4));
+        }
+    }
+}
+
 uint64_t k_from_delta(double delta, uint64_t d) {
     double kd = std::ceil(delta * (double)d);
     if (kd < 1.0) kd = 1.0;
@@ -264,7 +303,10 @@ struct Oracle {
     int noise_kind = 0;
     float noise_scale = 0.0f;
     int threads = 1;
-    int compressor = 0;                 // 0: Top-k, 1: Random-k
+    int compressor = 0;                 // 0: Top-k, 1: Random-k, 2: composed (Random-k, Top-k inside, 4-bit)
+    double rand_ratio = 0.2;            // composed: share of the coordinates the Random-k stage keeps
+    std::vector<std::vector<uint8_t>> msg_codes;   // composed: the 4-bit codes and block steps of the last message
+    std::vector<std::vector<float>> msg_steps;
     float zeta = 0.0f;                  // non-IID: worker i's optimum is x* + zeta * u_i
     bool step_is_noop = false;
     std::vector<float> lambda, xstar, U;
@@ -331,6 +373,40 @@ void compress_worker(Oracle* o, uint32_t i, uint64_t k, float lr) {
     for (uint64_t j = 0; j < d; ++j) o->e[i][j] = p[j] - dense[j];
 }
 
+// Composed compressor: Random-k keeps k1 = ceil(rand_ratio * d) coordinates, Top-k keeps the
+// k = ceil(delta * k1) largest of those (same total order; among the kept coordinates a lower
+// coordinate wins a tie), the 4-bit quantiser codes their values.  Delta is what the receiver
+// decodes, so the quantisation error stays in the error buffer with everything not sent.
+void compress_worker_composed(Oracle* o, uint32_t i, double delta, float lr) {
+    const uint64_t d = o->d;
+    std::vector<float> p(d);
+    for (uint64_t j = 0; j < d; ++j) {
+        float scaled = lr * o->g[i][j];
+        p[j] = o->e[i][j] + scaled;
+    }
+    const uint64_t k1 = k_from_delta(o->rand_ratio, d);
+    const uint64_t k = k_from_delta(delta, k1);
+    std::vector<uint32_t> subset(k1);
+    randk_select(o->seed, o->t, i, d, k1, subset.data());          // ascending coordinates
+    std::vector<float> kept(k1);
+    for (uint64_t m = 0; m < k1; ++m) kept[m] = p[subset[m]];
+    std::vector<uint32_t> pos(k);
+    topk_select(kept.data(), k1, k, pos.data(), &o->thr_T[i], &o->thr_r[i]);
+    o->msg_idx[i].assign(k, 0u);
+    o->msg_val[i].assign(k, 0.0f);
+    std::vector<float> chosen(k);
+    for (uint64_t m = 0; m < k; ++m) {
+        o->msg_idx[i][m] = subset[pos[m]];
+        chosen[m] = kept[pos[m]];
+    }
+    o->msg_codes[i].assign((k + 1) / 2, 0);
+    o->msg_steps[i].assign((k + kQuantBlock - 1) / kQuantBlock, 0.0f);
+    quantize4(chosen.data(), k, o->msg_codes[i].data(), o->msg_steps[i].data(), o->msg_val[i].data());
+    std::vector<float> dense(d, 0.0f);
+    for (uint64_t m = 0; m < k; ++m) dense[o->msg_idx[i][m]] = o->msg_val[i][m];
+    for (uint64_t j = 0; j < d; ++j) o->e[i][j] = p[j] - dense[j];
+}
+
 // DeCo's objective and the timing model (double precision, host scalars).
 double phi_value(double delta, double tau) {
     return (1.0 - delta) / (delta * std::pow(1.0 - 0.5 * delta, tau));
@@ -366,6 +442,10 @@ uint64_t oracle_randk_permute(uint64_t seed, uint64_t t, uint32_t worker, uint64
 }
 uint32_t oracle_murmur_fmix32(uint32_t h) { return murmur_fmix32(h); }
 void oracle_set_compressor(void* h, int kind) { ((Oracle*)h)->compressor = kind; }
+void oracle_set_composed(void* h, double rand_ratio) { ((Oracle*)h)->rand_ratio = rand_ratio; }
+void oracle_quantize4(const float* v, uint64_t count, uint8_t* codes, float* steps, float* deq) {
+    quantize4(v, count, codes, steps, deq);
+}
 void oracle_set_heterogeneity(void* h, float zeta) { ((Oracle*)h)->zeta = zeta; }
 
 void* oracle_create(uint64_t d, uint32_t n, uint32_t tau_max) {
@@ -379,6 +459,8 @@ void* oracle_create(uint64_t d, uint32_t n, uint32_t tau_max) {
     o->g.assign(n, std::vector<float>(d, 0.0f));
     o->msg_idx.assign(n, {});
     o->msg_val.assign(n, {});
+    o->msg_codes.assign(n, {});
+    o->msg_steps.assign(n, {});
     o->thr_T.assign(n, 0u);
     o->thr_r.assign(n, 0u);
     return o;
@@ -417,6 +499,10 @@ void oracle_ef_compress(void* h, double delta, float lr) {
     Oracle* o = (Oracle*)h;
     if (o->step_is_noop) {
         for (uint32_t i = 0; i < o->n; ++i) { o->msg_idx[i].clear(); o->msg_val[i].clear(); }
+        return;
+    }
+    if (o->compressor == 2) {
+        for_each_worker(o, [o, delta, lr](uint32_t i) { compress_worker_composed(o, i, delta, lr); });
         return;
     }
     uint64_t k = k_from_delta(delta, o->d);
@@ -478,6 +564,12 @@ void oracle_get_message(void* h, uint32_t w, uint32_t* idx, float* val) {
     Oracle* o = (Oracle*)h;
     std::copy(o->msg_idx[w].begin(), o->msg_idx[w].end(), idx);
     std::copy(o->msg_val[w].begin(), o->msg_val[w].end(), val);
+}
+// composed compressor: the wire form of the last message ((k+1)/2 code bytes, (k+255)/256 steps)
+void oracle_get_message_codes(void* h, uint32_t w, uint8_t* codes, float* steps) {
+    Oracle* o = (Oracle*)h;
+    std::copy(o->msg_codes[w].begin(), o->msg_codes[w].end(), codes);
+    std::copy(o->msg_steps[w].begin(), o->msg_steps[w].end(), steps);
 }
 void oracle_get_update(void* h, float* U) {
     Oracle* o = (Oracle*)h;
