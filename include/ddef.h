@@ -52,6 +52,7 @@ extern "C" {
 
 #define DDEF_COMPRESSOR_TOPK 0  /* keep the k largest magnitudes (default)                  */
 #define DDEF_COMPRESSOR_RANDK 1 /* keep k coordinates drawn at random per worker, iteration */
+#define DDEF_COMPRESSOR_COMPOSED 2 /* Random-k, then Top-k of the kept ones, then 4-bit codes */
 
 #define DDEF_NOISE_NONE 0
 #define DDEF_NOISE_GAUSS 1      /* N(0,1) * noise_scale                                    */
@@ -105,8 +106,23 @@ int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_
  * smallest even-width bit field holding d, round function MurmurHash3's 32-bit finaliser of
  * (half XOR round key), cycle-walked into [0, d), round keys from Philox4x32-10 with counter
  * (0xFFFFFFFF, worker, t).  Messages, error feedback and k = ceil(delta*d) are as for Top-k;
- * ddef_get_threshold reports (0, 0).  Only between iterations. */
+ * ddef_get_threshold reports (0, 0).
+ * Composed is the compressor the paper gives for its strongest static baseline (Section 5.1
+ * "Baselines": Random-k with 20 %, Top-k with 10 %, 4-bit quantisation); the paper describes it no
+ * further, the stages below are this library's reading.  (1) Random-k as above keeps
+ * k1 = ceil(rand_ratio * d) coordinates (ddef_set_composed, default 0.2).  (2) Top-k keeps the
+ * k = ceil(delta * k1) largest of those under the same total order (magnitude descending,
+ * coordinate ascending); delta is ddef_ef_compress's argument, and ddef_get_threshold reports
+ * this selection.  (3) The k values, in ascending coordinate order, are cut into blocks of 256:
+ * step = (largest magnitude in the block) / 7, code = value / step rounded to the nearest integer
+ * (halves to even) inside [-7, 7], all codes 0 where step is 0.  Delta holds what the receiver
+ * decodes, code * step (that is what ddef_get_message returns and the aggregation sums), so
+ * e' = p - Delta keeps the coding error with everything not sent.  Ring form only.
+ * Only between iterations. */
 int ddef_set_compressor(ddef_ctx* ctx, int kind);
+/* Share of the coordinates the Random-k stage of the composed compressor keeps, in (0, 1].
+ * Between iterations. */
+int ddef_set_composed(ddef_ctx* ctx, double rand_ratio);
 
 /* Heterogeneous local objectives (Assumption 3; the paper's non-IID experiments): worker i's
  * quadratic has the optimum xstar + zeta * u_i instead of xstar, u_i a standard normal vector
@@ -186,6 +202,14 @@ int ddef_get_update(ddef_ctx* ctx, float* host_U);   /* U of the last ddef_aggre
  * host_idx / host_val may be NULL to query k only; otherwise they hold at least k items. */
 int ddef_get_message(ddef_ctx* ctx, uint32_t worker, uint32_t* host_idx, float* host_val,
                      uint64_t* k);
+/* Wire form of a worker's last message under the composed compressor (Section 5.1 "Baselines",
+ * 4-bit stage as read in ddef_set_compressor's comment): (k+1)/2 bytes of codes, entry 2m in the
+ * low and entry 2m+1 in the high nibble of byte m, two's complement, a missing last entry 0; and
+ * (k+255)/256 block steps.  Entry m decodes to code * steps[m / 256] at coordinate idx[m] of
+ * ddef_get_message.  host_codes / host_steps may be NULL to query k.  ESTATE under another
+ * compressor. */
+int ddef_get_message_codes(ddef_ctx* ctx, uint32_t worker, uint8_t* host_codes, float* host_steps,
+                           uint64_t* k);
 /* Threshold of the last selection: T = smallest selected magnitude pattern, r = how many
  * selected entries carry exactly T. */
 int ddef_get_threshold(ddef_ctx* ctx, uint32_t worker, uint32_t* T, uint64_t* r);

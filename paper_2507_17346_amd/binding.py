@@ -14,7 +14,7 @@ import numpy as np
 from . import build as _build
 
 OK, EINVAL, ESTATE, ENOMEM, EHIP, ENONFINITE, EINTERNAL = 0, -1, -2, -3, -4, -5, -6
-COMPRESSOR_TOPK, COMPRESSOR_RANDK = 0, 1
+COMPRESSOR_TOPK, COMPRESSOR_RANDK, COMPRESSOR_COMPOSED = 0, 1, 2
 NOISE_NONE, NOISE_GAUSS, NOISE_STUDENT_T3 = 0, 1, 2
 OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16, OPT_PREFETCH_GRAD, OPT_FUSE_GRAD, OPT_GRAPH = 1, 2, 3, 4, 5
 
@@ -29,6 +29,8 @@ SIGNATURES = {
     "ddef_set_problem": (C.c_int, [_ctx, _f32p, _f32p, _f32p, C.c_uint64, C.c_int, C.c_float]),
     "ddef_set_tau": (C.c_int, [_ctx, C.c_uint32]),
     "ddef_set_compressor": (C.c_int, [_ctx, C.c_int]),
+    "ddef_set_composed": (C.c_int, [_ctx, C.c_double]),
+    "ddef_get_message_codes": (C.c_int, [_ctx, C.c_uint32, C.POINTER(C.c_uint8), _f32p, _u64p]),
     "ddef_set_heterogeneity": (C.c_int, [_ctx, C.c_float]),
     "ddef_deco_noniid": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
     "ddef_phi_prime": (C.c_double, [C.c_double, C.c_double]),
@@ -249,6 +251,9 @@ class Context:
     def set_compressor(self, kind: int):
         self._check(self._lib.ddef_set_compressor(self._h, int(kind)), "ddef_set_compressor")
 
+    def set_composed(self, rand_ratio: float):
+        self._check(self._lib.ddef_set_composed(self._h, float(rand_ratio)), "ddef_set_composed")
+
     def set_option(self, option: int, value: int):
         self._check(self._lib.ddef_set_option(self._h, int(option), int(value)), "ddef_set_option")
 
@@ -349,6 +354,20 @@ class Context:
             self._check(self._lib.ddef_get_message(self._h, int(worker), idx.ctypes.data_as(_u32p),
                                                    val.ctypes.data_as(_f32p), C.byref(k)), "ddef_get_message")
         return idx, val
+
+    def get_message_codes(self, worker: int):
+        """(packed 4-bit codes, block steps) of the last message under the composed compressor."""
+        k = C.c_uint64()
+        self._check(self._lib.ddef_get_message_codes(self._h, int(worker), None, None, C.byref(k)),
+                    "ddef_get_message_codes")
+        codes = np.zeros((k.value + 1) // 2, dtype=np.uint8)
+        steps = np.zeros((k.value + 255) // 256, dtype=np.float32)
+        if k.value:
+            self._check(self._lib.ddef_get_message_codes(self._h, int(worker),
+                                                         codes.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                                         steps.ctypes.data_as(_f32p), C.byref(k)),
+                        "ddef_get_message_codes")
+        return codes, steps
 
     def get_threshold(self, worker: int):
         T, r = C.c_uint32(), C.c_uint64()

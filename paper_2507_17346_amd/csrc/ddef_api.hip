@@ -21,12 +21,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
-    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_SAMPLE, SL_FILL,
+    SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_QUANTIZE4, SL_SAMPLE, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
-    "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit",
+    "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_quantize4",
     "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
@@ -87,6 +87,13 @@ struct ddef_ctx {
     uint64_t pf_t = 0;
     uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
+    // composed compressor: share of the coordinates its Random-k stage keeps, and the wire form of
+    // the last message: codes [n][codes_ld] bytes (two entries each), steps [n][codes_ld/128] floats
+    double rand_ratio = 0.2;
+    uint8_t* codes = nullptr;
+    float* steps = nullptr;
+    uint64_t codes_ld = 0;
+    bool codes_valid = false;
     // The messages are summed tile by tile in LDS by ddef_apply_delayed, in the pass that updates
     // the model; ddef_aggregate only locates each tile's entries (agg_off: [n][ld/kTile + 1]
     // message offsets at the tile boundaries).  agg_deferred holds from ddef_aggregate to the next
@@ -239,7 +246,8 @@ uint64_t candidate_target(const ddef_ctx* c, uint64_t k) {
     return kb;
 }
 
-int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
+// Message rows for k entries per worker and `want` candidate slots per worker.
+int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t want) {
     if (k > c->msg_ld) {
         drop_graph(c);
         // longer rows; the messages held so far (queued ones in queue form) move over
@@ -266,7 +274,6 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t kb) {
         if (c->msg_val) (void)hipFree(c->msg_val);
         c->msg_idx = idx; c->msg_val = val; c->msg_ld = len;
     }
-    const uint64_t want = candidate_capacity(c, k, kb);
     if (want > c->cap) {
         drop_graph(c);
         HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -441,7 +448,7 @@ int check_device_flags(ddef_ctx* c) {
     HIP_TRY(c, hipMemcpy(bad.data(), c->filt + 4 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
     for (uint32_t v : bad)
         if (v) { c->sticky = DDEF_ENONFINITE; return DDEF_ENONFINITE; }
-    if (c->compressor != DDEF_COMPRESSOR_RANDK || c->k_step == 0) return DDEF_OK;
+    if (c->compressor == DDEF_COMPRESSOR_TOPK || c->k_step == 0) return DDEF_OK;
     std::vector<SelState> st(c->n);
     HIP_TRY(c, hipMemcpy(st.data(), c->sel, sizeof(SelState) * c->n, hipMemcpyDeviceToHost));
     for (const SelState& s : st)
@@ -553,7 +560,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
                     c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->g_next, c->cand,
-                    c->sorted_idx, c->sorted_val};
+                    c->sorted_idx, c->sorted_val, c->codes, c->steps};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
     delete c;
@@ -610,11 +617,22 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
 int ddef_set_compressor(ddef_ctx* c, int kind) {
     int rc = check_ctx(c);
     if (rc) return rc;
-    if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK) return DDEF_EINVAL;
+    if (kind != DDEF_COMPRESSOR_TOPK && kind != DDEF_COMPRESSOR_RANDK && kind != DDEF_COMPRESSOR_COMPOSED)
+        return DDEF_EINVAL;
     if (c->queue_form && kind != DDEF_COMPRESSOR_TOPK) return DDEF_EINVAL;
     if (c->phase != PH_IDLE) return DDEF_ESTATE;
     drop_graph(c);
     c->compressor = kind;
+    c->codes_valid = false;
+    return DDEF_OK;
+}
+
+int ddef_set_composed(ddef_ctx* c, double rand_ratio) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!(rand_ratio > 0.0) || !(rand_ratio <= 1.0)) return DDEF_EINVAL;
+    if (c->phase != PH_IDLE) return DDEF_ESTATE;
+    c->rand_ratio = rand_ratio;
     return DDEF_OK;
 }
 
@@ -697,10 +715,14 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         c->phase = PH_COMPRESSED;
         return DDEF_OK;
     }
-    const uint64_t k = ddef_k_from_delta(delta, c->d);
+    // composed: Random-k keeps k1 coordinates, Top-k the k = ceil(delta * k1) largest of them
+    const bool composed = c->compressor == DDEF_COMPRESSOR_COMPOSED;
+    const uint64_t k1 = composed ? ddef_k_from_delta(c->rand_ratio, c->d) : 0u;
+    const uint64_t k = composed ? ddef_k_from_delta(delta, k1) : ddef_k_from_delta(delta, c->d);
     c->agg_deferred = false;               // the messages it would read are about to be replaced
     const uint64_t kb = candidate_target(c, k);
-    rc = ensure_capacity(c, k, kb);
+    rc = composed ? ensure_capacity(c, k, candidate_capacity(c, k1, candidate_target(c, k1)))
+                  : ensure_capacity(c, k, candidate_capacity(c, k, kb));
     if (rc) return rc;
     c->msg_slot = (uint32_t)(c->t % c->q_slots);
     c->q_k[c->msg_slot] = 0;               // set again once the launches are enqueued
@@ -708,17 +730,56 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     uint32_t* cand_total = c->filt + 3 * n;
     uint32_t* zero_at = c->filt + 5 * n;
-    if (c->compressor == DDEF_COMPRESSOR_RANDK) {
+    if (c->compressor != DDEF_COMPRESSOR_TOPK) {
         materialize_grad(c);
         const uint64_t bitmap_ld = c->ld / 32u;
         if (!c->bitmap) {
             HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
             HIP_TRY(c, hipMemsetAsync(c->bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream));
         }
+    }
+    if (composed) {
+        if (c->codes_ld != c->msg_ld / 2u) {       // follows the message rows (msg_ld is a multiple of 1024)
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            if (c->codes) (void)hipFree(c->codes);
+            if (c->steps) (void)hipFree(c->steps);
+            c->codes = nullptr; c->steps = nullptr; c->codes_ld = 0;
+            HIP_TRY(c, hipMalloc((void**)&c->codes, (size_t)n * (c->msg_ld / 2u)));
+            HIP_TRY(c, hipMalloc((void**)&c->steps, (size_t)n * (c->msg_ld / 256u) * 4u));
+            c->codes_ld = c->msg_ld / 2u;
+        }
+        const uint64_t bitmap_ld = c->ld / 32u;
+        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k1 + 255u) / 256u, n, 8), n), dim3(256),
+               c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k1, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+        LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
+               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+        LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               c->span_sum, c->nspans);
+        LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
+               (uint32_t)k1, (uint32_t)k, n, c->sel, cand_total, c->hist);
+        LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+               (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
+               c->sorted_idx, c->sorted_val, c->cap, (float*)nullptr, (uint64_t)0);
+        enqueue_select(c, (uint32_t)k, (uint32_t)k);
+        LAUNCH(c, SL_QUANTIZE4, k_quantize4, dim3((uint32_t)((k + 255u) / 256u), n), dim3(256),
+               (const uint32_t*)c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld, (uint32_t)k,
+               (const SelState*)c->sel, c->e, c->ld, c->codes, c->codes_ld, c->steps, c->codes_ld / 128u);
+        HIP_TRY(c, hipGetLastError());
+        c->have_bound = false;          // the filter words now describe this selection, not a Top-k of e
+        c->sel_k = 0; c->sel_run = 0;
+        c->codes_valid = true;
+        c->k_step = k;
+        c->q_k[c->msg_slot] = k;
+        c->phase = PH_COMPRESSED;
+        return DDEF_OK;
+    }
+    if (c->compressor == DDEF_COMPRESSOR_RANDK) {
+        const uint64_t bitmap_ld = c->ld / 32u;
         LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
                c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
                (uint32_t)c->t, (uint32_t)(c->t >> 32));
-        LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr,
+        LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 1,
                c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
@@ -1041,6 +1102,26 @@ int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* ho
                          (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
     HIP_TRY(c, hipMemcpy(host_val, c->slot_val(c->msg_slot) + (uint64_t)worker * c->msg_ld,
                          (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
+    return DDEF_OK;
+}
+
+int ddef_get_message_codes(ddef_ctx* c, uint32_t worker, uint8_t* host_codes, float* host_steps, uint64_t* k) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!k || worker >= c->n) return DDEF_EINVAL;
+    if (c->compressor != DDEF_COMPRESSOR_COMPOSED) return DDEF_ESTATE;
+    if (c->phase != PH_COMPRESSED && c->phase != PH_AGGREGATED && c->phase != PH_IDLE) return DDEF_ESTATE;
+    *k = c->k_step;
+    if (!host_codes || !host_steps || c->k_step == 0) return DDEF_OK;
+    if (!c->codes_valid) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    rc = check_device_flags(c);
+    if (rc) return rc;
+    HIP_TRY(c, hipMemcpy(host_codes, c->codes + (uint64_t)worker * c->codes_ld, (size_t)((c->k_step + 1u) / 2u),
+                         hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(host_steps, c->steps + (uint64_t)worker * (c->codes_ld / 128u),
+                         (size_t)((c->k_step + 255u) / 256u) * 4u, hipMemcpyDeviceToHost));
     return DDEF_OK;
 }
 

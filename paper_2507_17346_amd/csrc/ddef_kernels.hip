@@ -423,9 +423,10 @@ __global__ __launch_bounds__(256) void k_randk_mark(uint32_t* __restrict__ bitma
 
 // grid (ld/256, n), one wave per block, as k_ef_filter.  Eight lanes share one bitmap word;
 // the first of them clears it after the group has read it, so the bitmap is all-zero again
-// when the pass is over.
+// when the pass is over.  zero_marked = 0 leaves the marked entries' values in e (the composed
+// compressor decides later which of them are sent).
 __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const float* __restrict__ g,
-                                                 uint64_t ld, uint32_t d, float lr,
+                                                 uint64_t ld, uint32_t d, float lr, int zero_marked,
                                                  uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
                                                  uint2* __restrict__ cand, uint64_t cap,
                                                  uint32_t* __restrict__ cand_count,
@@ -447,7 +448,7 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
         pv[3] = ev.w + lr * gv.w;
         float res[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) res[c] = ((bitsel >> c) & 1u) ? 0.0f : pv[c];
+        for (int c = 0; c < 4; ++c) res[c] = (zero_marked && ((bitsel >> c) & 1u)) ? 0.0f : pv[c];
         store_stream4(ep, res);
     }
     if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
@@ -592,6 +593,84 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
     const uint32_t w = blockIdx.x;
     if (threadIdx.x == 0) { sel[w].active = 1u; sel[w].zero_used = 0xffffffffu; cand_total[w] = 0u; }
     begin_selection(sel, w, n, k, kb, d, hist);
+}
+
+// ---- composed compressor: Random-k, Top-k inside the kept coordinates, 4-bit codes ---------
+// (Section 5.1 "Baselines": the strongest static baseline's compressor.)  The Random-k pass above
+// records the k1 kept entries as runs and leaves e = p; the radix select of S2/S3 then runs on
+// those entries in coordinate order for rank k, as it does on a filter's candidates, and the
+// message it writes is coded below.
+//
+// One block per worker, after k_tab_sum: span sums -> span offsets; the runs must hold exactly
+// k1 entries (active = 2 flags a slot overflow); starts the selection of the k largest of them.
+__global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restrict__ span_sum, uint32_t nspans,
+                                                             uint32_t* __restrict__ overflow, uint32_t k1,
+                                                             uint32_t k, uint32_t n,
+                                                             SelState* __restrict__ sel,
+                                                             uint32_t* __restrict__ cand_total,
+                                                             uint32_t* __restrict__ hist) {
+    __shared__ uint32_t lds[5];
+    const uint32_t w = blockIdx.x;
+    uint32_t* sw = span_sum + (uint64_t)w * nspans;
+    uint32_t carry = 0;
+    for (uint32_t first = 0; first < nspans; first += 256u) {
+        const uint32_t sp = first + threadIdx.x;
+        const uint32_t v = sp < nspans ? sw[sp] : 0u;
+        uint32_t total;
+        const uint32_t at = carry + block_excl_scan(v, lds, &total);
+        if (sp < nspans) sw[sp] = at;
+        carry += total;
+    }
+    const bool fine = overflow[w] == 0u && carry == k1;
+    if (threadIdx.x == 0) {
+        cand_total[w] = fine ? carry : 0u;
+        sel[w].active = fine ? 0u : 2u;
+        sel[w].zero_used = 0xffffffffu;         // nothing was cleared ahead of time
+        sel[w].seen = carry;
+    }
+    begin_selection(sel, w, n, k, k, fine ? carry : 0u, hist);
+}
+
+// 4-bit stage: the message (values in coordinate order) is cut into blocks of 256 entries, one
+// thread block each.  step = (largest magnitude of the block) / 7; code = value / step rounded to
+// the nearest integer (halves to even) inside [-7, 7]; the message value becomes what the
+// receiver decodes, code * step, and the coding error goes back into e at the entry's coordinate
+// (k_chunk_emit had put +0 there).  A block whose step is zero sends zero codes.  Two codes per
+// byte, even position in the low nibble, two's complement.  grid (ceil(k / 256), n).
+__global__ __launch_bounds__(256) void k_quantize4(const uint32_t* __restrict__ msg_idx,
+                                                   float* __restrict__ msg_val, uint64_t msg_ld, uint32_t k,
+                                                   const SelState* __restrict__ sel,
+                                                   float* __restrict__ e, uint64_t ld,
+                                                   uint8_t* __restrict__ codes, uint64_t codes_ld,
+                                                   float* __restrict__ steps, uint64_t steps_ld) {
+    __shared__ float red[4];
+    const uint32_t w = blockIdx.y, b = blockIdx.x;
+    if (sel[w].active == 2u) return;            // broken invariant: the host reports it, nothing is coded
+    const uint32_t m = b * 256u + threadIdx.x;
+    const bool in = m < k;
+    const float v = in ? msg_val[(uint64_t)w * msg_ld + m] : 0.0f;
+    float big = fabsf(v);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) big = fmaxf(big, __shfl_xor(big, off, 64));
+    if (lane_id() == 0) red[threadIdx.x >> 6] = big;
+    __syncthreads();
+    big = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float step = big / 7.0f;
+    int q = 0;
+    if (step > 0.0f) {
+        float nearest = rintf(v / step);
+        nearest = fminf(fmaxf(nearest, -7.0f), 7.0f);
+        q = (int)nearest;
+    }
+    const float deq = (float)q * step;
+    const uint32_t nib = (uint32_t)q & 0xfu;
+    const uint32_t next_nib = (uint32_t)__shfl_down((int)nib, 1, 64);   // pairs (even, odd) never straddle a wave
+    if (in) {
+        msg_val[(uint64_t)w * msg_ld + m] = deq;
+        e[(uint64_t)w * ld + msg_idx[(uint64_t)w * msg_ld + m]] = v - deq;
+        if ((threadIdx.x & 1u) == 0u) codes[(uint64_t)w * codes_ld + (m >> 1)] = (uint8_t)(nib | (next_nib << 4));
+    }
+    if (threadIdx.x == 0) steps[(uint64_t)w * steps_ld + b] = step;
 }
 
 // Prefixes inside a span, and with them the candidates in coordinate order: group c's run

@@ -1,0 +1,161 @@
+"""GPU parity of the composed compressor (Random-k, Top-k inside the kept coordinates, 4-bit block
+codes; Section 5.1 "Baselines") with the oracle, through the C-ABI: index sets, packed codes and
+block steps byte for byte, decoded values, error buffers, thresholds, update and model bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2507_17346_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+
+
+def bits(a):
+    return np.asarray(a, dtype=F32).view(np.uint32)
+
+
+@pytest.fixture(scope="module")
+def ddef():
+    from paper_2507_17346_amd import binding
+    binding.load()
+    return binding
+
+
+def pair(ddef, oracle_mod, w, tau, rand_ratio, threads=4):
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, max(tau, 1))
+    o = oracle_mod.Oracle(w.d, w.n, max(tau, 1), threads=threads)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(tau)
+        h.set_compressor(2)
+        h.set_composed(rand_ratio)
+    return g, o
+
+
+def assert_same(g, o, n, what, codes=True):
+    for i in range(n):
+        gi, gv = g.get_message(i)
+        oi, ov = o.get_message(i)
+        assert np.array_equal(gi, oi), (what, "indices", i)
+        assert np.array_equal(bits(gv), bits(ov)), (what, "decoded values", i)
+        if codes and len(oi):
+            gc, gs = g.get_message_codes(i)
+            oc, os_ = o.get_message_codes(i)
+            assert np.array_equal(gc, oc), (what, "codes", i)
+            assert np.array_equal(bits(gs), bits(os_)), (what, "steps", i)
+            assert g.get_threshold(i) == o.get_threshold(i), (what, "threshold", i)
+        assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), (what, "error buffer", i)
+    assert np.array_equal(bits(g.get_update()), bits(o.get_update())), what
+    assert np.array_equal(bits(g.get_model()), bits(o.get_model())), what
+
+
+@pytest.mark.parametrize("d,n,tau,rho,delta,steps", [
+    (1, 1, 0, 0.2, 0.1, 3),                 # k1 = k = 1
+    (3, 2, 0, 0.2, 0.1, 4),
+    (33, 3, 1, 0.5, 0.5, 5),                # odd k: the last byte holds one code
+    (4097, 2, 2, 0.2, 0.1, 6),
+    (100_003, 4, 1, 0.2, 0.1, 6),           # k = 2001: eight blocks, a ragged last one
+    (250_000, 8, 1, 0.2, 0.1, 6),           # the paper's ratios and tau = 1
+    (65_536, 2, 0, 1.0, 1.0, 3),            # every coordinate kept and sent: only the codes compress
+    (65_537, 2, 0, 1.0, 0.3, 3),
+    (300_001, 3, 3, 0.03, 0.004, 5),
+])
+def test_composed_trajectories(ddef, oracle_mod, d, n, tau, rho, delta, steps):
+    w = workloads.replace(workloads.get("C3", d=d, n=n), seed=2000 + d)
+    g, o = pair(ddef, oracle_mod, w, tau, rho)
+    k = oracle_mod.k_from_delta(delta, oracle_mod.k_from_delta(rho, d))
+    for t in range(steps):
+        g.grad(); o.grad()
+        g.ef_compress(delta, w.lr); o.ef_compress(delta, w.lr)
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(w.lr); o.apply_delayed()
+        assert_same(g, o, n, (d, t))
+        if t >= tau:
+            assert len(g.get_message(0)[0]) == k
+    g.close()
+
+
+def test_ties_and_zero_blocks(ddef, oracle_mod):
+    # loaded gradients with many equal magnitudes, +-0 and a stretch of zeros long enough to fill
+    # whole blocks of the message: the tie rule and the zero-step rule
+    d, n = 40_000, 2
+    w = workloads.replace(workloads.get("C1", d=d, n=n), seed=77, noise_kind=0, noise_scale=0.0)
+    g, o = pair(ddef, oracle_mod, w, 0, 1.0)
+    rng = np.random.default_rng(8)
+    for t in range(3):
+        for i in range(n):
+            v = rng.choice(np.array([0.0, -0.0, 1.0, -1.0, 2.5, 1e-42], dtype=F32), d, p=[0.6, 0.1, 0.1, 0.1, 0.05, 0.05])
+            g.load_grad(i, v); o.load_grad(i, v)
+        g.ef_compress(0.9, 1.0); o.ef_compress(0.9, 1.0)
+        g.aggregate(); o.aggregate()
+        g.apply_delayed(1.0); o.apply_delayed()
+        assert_same(g, o, n, ("ties", t))
+    g.close()
+
+
+def test_switching_between_the_three_compressors(ddef, oracle_mod):
+    w = workloads.get("C1", d=120_000, n=3)
+    g, o = pair(ddef, oracle_mod, w, 1, 0.2)
+    plan = [0, 0, 0, 2, 2, 0, 0, 1, 2, 0, 0, 0]
+    for t, comp in enumerate(plan):
+        g.set_compressor(comp); o.set_compressor(comp)
+        delta = 0.1 if comp == 2 else 0.01
+        g.step(delta, w.lr); o.step(delta, w.lr)
+        assert_same(g, o, w.n, (t, comp), codes=comp == 2)
+    g.close()
+
+
+def test_growing_message_keeps_codes_in_step(ddef, oracle_mod):
+    # delta changes from iteration to iteration, so the message rows and the code rows are reallocated
+    w = workloads.get("C1", d=200_000, n=2)
+    g, o = pair(ddef, oracle_mod, w, 0, 0.2)
+    for t, delta in enumerate([0.01, 0.1, 0.5, 1.0, 0.02]):
+        g.step(delta, w.lr); o.step(delta, w.lr)
+        assert_same(g, o, w.n, (t, delta))
+    g.close()
+
+
+def test_argument_and_state_checks(ddef):
+    c = ddef.Context(1000, 1, 0)
+    one = np.ones(1000, dtype=F32)
+    c.set_problem(one, one, one, 0, 0, 0.0)
+    assert c.raw("set_composed", 0.0) == ddef.EINVAL
+    assert c.raw("set_composed", 1.5) == ddef.EINVAL
+    assert c.raw("set_composed", float("nan")) == ddef.EINVAL
+    import ctypes as C
+    k = C.c_uint64()
+    assert c.raw("get_message_codes", 0, None, None, C.byref(k)) == ddef.ESTATE      # Top-k is selected
+    c.set_compressor(ddef.COMPRESSOR_COMPOSED)
+    assert c.raw("get_message_codes", 1, None, None, C.byref(k)) == ddef.EINVAL
+    assert c.raw("get_message_codes", 0, None, None, None) == ddef.EINVAL
+    c.grad()
+    assert c.raw("set_composed", 0.5) == ddef.ESTATE
+    c.ef_compress(0.1, 0.05); c.aggregate(); c.apply_delayed(0.05)
+    idx, val = c.get_message(0)
+    assert len(idx) == 20                   # ceil(0.1 * ceil(0.2 * 1000))
+    codes, steps = c.get_message_codes(0)
+    assert len(codes) == 10 and len(steps) == 1
+    c.close()
+    q = ddef.Context(1000, 1, 1, queue_form=True)
+    assert q.raw("set_compressor", ddef.COMPRESSOR_COMPOSED) == ddef.EINVAL
+    q.close()
+
+
+def test_composed_c3_full_size(ddef, oracle_mod):
+    # the paper's setting of this compressor (20 %, 10 %, tau = 1) on the C3 shape
+    w = workloads.get("C3")
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, 1)
+    o = oracle_mod.Oracle(w.d, w.n, 1, threads=w.n)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(1)
+        h.set_compressor(2)
+        h.set_composed(0.2)
+    for t in range(3):
+        g.step(0.1, w.lr)
+        o.step(0.1, w.lr)
+    assert_same(g, o, w.n, "C3 composed")
+    g.close()
