@@ -94,7 +94,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, compressor=0):
+def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, compressor=0, rand_ratio=0.2):
     """The oracle, as it stands, on a bounded sample: one non-empty iteration over the first
     sample_d coordinates of the workload (all n workers, one thread per worker unless capped)."""
     import oracle
@@ -113,6 +113,7 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, com
     o.set_problem(lam[:sample_d], xstar[:sample_d], x0[:sample_d], w.seed, w.noise_kind, w.noise_scale)
     o.set_tau(0)
     o.set_compressor(compressor)
+    o.set_composed(rand_ratio)
     t0 = time.perf_counter()
     o.step(w.deltas[0], w.lr)
     dt = time.perf_counter() - t0
@@ -179,7 +180,9 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="shrink d (debug only; not a valid bench)")
     ap.add_argument("--delta", type=float, default=None,
                     help="fix the compression ratio (study runs only; the default follows the workload)")
-    ap.add_argument("--compressor", choices=["topk", "randk"], default="topk",
+    ap.add_argument("--rand-ratio", type=float, default=0.2,
+                    help="composed compressor: share of the coordinates its Random-k stage keeps")
+    ap.add_argument("--compressor", choices=["topk", "randk", "composed"], default="topk",
                     help="sparsifier: the paper's default Top-k, or its appendix's Random-k")
     ap.add_argument("--prefetch", type=int, default=0,
                     help="1: generate the next iteration's gradient on a second stream meanwhile")
@@ -214,8 +217,17 @@ def main():
     log(f"inputs generated in {time.perf_counter() - t0:.1f} s")
     ctx = binding.Context(w.d, w.n, w.tau_max, queue_form=bool(args.queue_form))
     ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
-    compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK}[args.compressor]
+    compressor = {"topk": binding.COMPRESSOR_TOPK, "randk": binding.COMPRESSOR_RANDK,
+                  "composed": binding.COMPRESSOR_COMPOSED}[args.compressor]
     ctx.set_compressor(compressor)
+    if args.compressor == "composed":
+        ctx.set_composed(args.rand_ratio)
+
+    def sent_ratio(dl):
+        """entries per worker in a message, as a share of d"""
+        if args.compressor == "composed":
+            return binding.k_from_delta(dl, binding.k_from_delta(args.rand_ratio, w.d)) / w.d
+        return w.k(dl) / w.d
     ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
     ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
     ctx.set_option(binding.OPT_GRAPH, 1 if args.graph else 0)
@@ -256,7 +268,7 @@ def main():
     floor_bytes_sum = 0.0
     for _ in range(args.steps):
         delta = begin_iteration()
-        floor_bytes_sum += (12.0 + 24.0 * (w.k(delta) / w.d) + 16.0 / w.n) * w.n * w.d
+        floor_bytes_sum += (12.0 + 24.0 * sent_ratio(delta) + 16.0 / w.n) * w.n * w.d
         for name, call in (("grad", ctx.grad), ("ef_compress", lambda: ctx.ef_compress(delta, w.lr)),
                            ("aggregate", ctx.aggregate), ("apply_delayed", lambda: ctx.apply_delayed(w.lr))):
             ctx.sync()
@@ -279,7 +291,7 @@ def main():
     floor_bytes_sum = 0.0
     for _ in range(args.steps):
         delta = begin_iteration()
-        floor_bytes_sum += (12.0 + 24.0 * (w.k(delta) / w.d) + 16.0 / w.n) * w.n * w.d
+        floor_bytes_sum += (12.0 + 24.0 * sent_ratio(delta) + 16.0 / w.n) * w.n * w.d
         row = [hev.mark()]
         for call in (ctx.grad, lambda: ctx.ef_compress(delta, w.lr), ctx.aggregate, lambda: ctx.apply_delayed(w.lr)):
             call()
@@ -376,7 +388,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
+                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,
@@ -394,13 +406,13 @@ def main():
         sample_d = args.cpu_sample_d or min(w.d, 124_000_000)
         note = ""
         try:
-            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note, compressor=compressor)
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note, compressor=compressor, rand_ratio=args.rand_ratio)
         except MemoryError:
             out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory",
-                                               compressor=compressor)
+                                               compressor=compressor, rand_ratio=args.rand_ratio)
         # the same oracle on one thread, on an eighth of the coordinates to keep the run short
         out["cpu_baseline_single_thread"] = cpu_baseline(w, lam, xstar, x0, max(1, sample_d // 8), "",
-                                                         max_threads=1, compressor=compressor)
+                                                         max_threads=1, compressor=compressor, rand_ratio=args.rand_ratio)
     ctx.close()
     print(json.dumps(out), flush=True)
 

@@ -299,6 +299,13 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                               * only between ddef_grad and ddef_apply_delayed (it regenerates the
                               * values); ddef_load_grad and Random-k fall back to a stored gradient.
                               * Default 0: the pass becomes bound by the generator's arithmetic.      */
+#define DDEF_OPT_RANDK_BUCKET_PERCENT 6 /* Random-k with k >= 2^20 sorts the kept coordinates into
+                              * buckets by coordinate region before it sets their bits; a bucket
+                              * holds its expected fill plus 8 standard deviations (value 0,
+                              * default), and what does not fit is set bit by bit.  A value of
+                              * 1..400 sizes the buckets at that percentage of the expected fill
+                              * instead (tests use it to exercise the overflow path).  Results are
+                              * unchanged.                                                          */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 
 const char* ddef_strerror(int code);

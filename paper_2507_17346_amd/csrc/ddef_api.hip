@@ -20,12 +20,12 @@ namespace {
 enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 
 enum Slot {
-    SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
+    SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_RANDK_BIN, SL_RANDK_FILL, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_QUANTIZE4, SL_SAMPLE, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
-    "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
+    "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_randk_bin", "k_randk_fill", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_quantize4",
     "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
 
@@ -87,6 +87,7 @@ struct ddef_ctx {
     uint64_t pf_t = 0;
     uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
+    uint32_t* region_count = nullptr;    // Random-k, binned marking: [n][2048] bucket fill counts, all-zero between steps
     // composed compressor: share of the coordinates its Random-k stage keeps, and the wire form of
     // the last message: codes [n][codes_ld] bytes (two entries each), steps [n][codes_ld/128] floats
     double rand_ratio = 0.2;
@@ -114,6 +115,7 @@ struct ddef_ctx {
     int sticky = DDEF_OK;
     uint64_t full_selects = 0;
     int64_t opt_force_full = 0, opt_slack_x16 = 40;
+    int64_t opt_bucket_percent = 0;      // Random-k buckets: 0 = expected fill plus slack, else that share of it
     // ddef_step as a captured graph: the launches of one steady iteration, replayed while
     // (k, lr, tau) stay the same.  Inside the graph the iteration number comes from t_dev.
     int64_t opt_graph = 0;
@@ -292,7 +294,7 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t want) {
 }
 
 // Radix select and ordered compaction of every worker through its view (candidates or row).
-void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
+void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, int fix_e = 1) {
     const uint32_t n = c->n;
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *cand_total = c->filt + 3 * n;
     const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sorted_val, c->sorted_idx, c->cap, cand_total};
@@ -311,7 +313,47 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb) {
            k, kb, bound, c->filt + 5 * n, cand_count, overflow);
     LAUNCH(c, SL_CHUNK_EMIT, k_chunk_emit, dim3(gc, n), dim3(256), vs, (const SelState*)c->sel,
            (const uint32_t*)c->cnt_gt, (const uint32_t*)c->cnt_eq, c->nchunks, c->e, c->slot_idx(c->msg_slot),
-           c->slot_val(c->msg_slot), c->msg_ld, k);
+           c->slot_val(c->msg_slot), c->msg_ld, k, fix_e);
+}
+
+// Sets the bits of the k coordinates Random-k keeps for this (iteration, worker) in the bitmap.
+// A few coordinates are set one atomic each; many are first sorted into buckets by coordinate
+// region (the candidate buffer, idle at this point, holds the buckets) and set region by region.
+int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
+    const uint32_t n = c->n;
+    const uint64_t bitmap_ld = c->ld / 32u;
+    if (!c->bitmap) {
+        HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
+        HIP_TRY(c, hipMemsetAsync(c->bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream));
+    }
+    uint32_t bits_d = 1;
+    while (((uint64_t)1 << bits_d) < c->d) ++bits_d;
+    const uint32_t region_bits = bits_d > 29u ? bits_d - 11u : 18u;
+    const uint64_t regions = (c->d + (((uint64_t)1 << region_bits) - 1u)) >> region_bits;     // <= 2048
+    const double expected = (double)k * (double)((uint64_t)1 << region_bits) / (double)c->d;
+    uint64_t bucket_cap = (((uint64_t)(expected + 8.0 * std::sqrt(expected)) + 64u) + 63u) & ~(uint64_t)63u;
+    if (c->opt_bucket_percent) bucket_cap = (uint64_t)(expected * (double)c->opt_bucket_percent / 100.0) + 1u;
+    const bool binned = k >= ((uint64_t)1 << 20) && regions <= 2048u && regions * bucket_cap <= 2u * c->cap &&
+                        bucket_cap < 0xffffffffull;
+    if (!binned) {
+        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
+               c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
+               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+        return DDEF_OK;
+    }
+    if (!c->region_count) {
+        HIP_TRY(c, hipMalloc((void**)&c->region_count, (size_t)n * 2048u * 4u));
+        HIP_TRY(c, hipMemsetAsync(c->region_count, 0, (size_t)n * 2048u * 4u, c->stream));
+    }
+    uint32_t* bucket = reinterpret_cast<uint32_t*>(c->cand);
+    LAUNCH(c, SL_RANDK_BIN, k_randk_bin, dim3(blocks_for(c, (k + 8191u) / 8192u, n, 2), n), dim3(1024), bucket,
+           2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
+           (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)c->t,
+           (uint32_t)(c->t >> 32));
+    LAUNCH(c, SL_RANDK_FILL, k_randk_fill, dim3((uint32_t)regions, n), dim3(1024), (const uint32_t*)bucket,
+           2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
+           (uint32_t)c->d);
+    return DDEF_OK;
 }
 
 // The sum of the messages named by the last ddef_aggregate, written to U (a getter wants it;
@@ -559,7 +601,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->g_next, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->region_count, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val, c->codes, c->steps};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -730,14 +772,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     uint32_t *bound = c->filt, *cand_count = c->cand_count, *overflow = c->filt + n, *stat_full = c->filt + 2 * n;
     uint32_t* cand_total = c->filt + 3 * n;
     uint32_t* zero_at = c->filt + 5 * n;
-    if (c->compressor != DDEF_COMPRESSOR_TOPK) {
-        materialize_grad(c);
-        const uint64_t bitmap_ld = c->ld / 32u;
-        if (!c->bitmap) {
-            HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
-            HIP_TRY(c, hipMemsetAsync(c->bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream));
-        }
-    }
+    if (c->compressor != DDEF_COMPRESSOR_TOPK) materialize_grad(c);
     if (composed) {
         if (c->codes_ld != c->msg_ld / 2u) {       // follows the message rows (msg_ld is a multiple of 1024)
             HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -749,9 +784,8 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
             c->codes_ld = c->msg_ld / 2u;
         }
         const uint64_t bitmap_ld = c->ld / 32u;
-        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k1 + 255u) / 256u, n, 8), n), dim3(256),
-               c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k1, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+        rc = enqueue_randk_mark(c, k1);
+        if (rc) return rc;
         LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
                c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
@@ -761,7 +795,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
                c->sorted_idx, c->sorted_val, c->cap, (float*)nullptr, (uint64_t)0);
-        enqueue_select(c, (uint32_t)k, (uint32_t)k);
+        enqueue_select(c, (uint32_t)k, (uint32_t)k, 0);      // e is completed by the 4-bit stage
         LAUNCH(c, SL_QUANTIZE4, k_quantize4, dim3((uint32_t)((k + 255u) / 256u), n), dim3(256),
                (const uint32_t*)c->slot_idx(c->msg_slot), c->slot_val(c->msg_slot), c->msg_ld, (uint32_t)k,
                (const SelState*)c->sel, c->e, c->ld, c->codes, c->codes_ld, c->steps, c->codes_ld / 128u);
@@ -776,9 +810,8 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     }
     if (c->compressor == DDEF_COMPRESSOR_RANDK) {
         const uint64_t bitmap_ld = c->ld / 32u;
-        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
-               c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+        rc = enqueue_randk_mark(c, k);
+        if (rc) return rc;
         LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 1,
                c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
@@ -1245,6 +1278,10 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
             if (c->opt_fuse) return drop_prefetch(c);
             return DDEF_OK;
         case DDEF_OPT_GRAPH: c->opt_graph = value != 0; return DDEF_OK;
+        case DDEF_OPT_RANDK_BUCKET_PERCENT:
+            if (value < 0 || value > 400) return DDEF_EINVAL;
+            c->opt_bucket_percent = value;
+            return DDEF_OK;
         case DDEF_OPT_CANDIDATE_SLACK_X16:
             if (value < 16 || value > 1024) return DDEF_EINVAL;
             c->opt_slack_x16 = value;

@@ -76,6 +76,11 @@ __global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* 
                             float* sorted_val, uint64_t out_ld, float* e_row, uint64_t e_ld);
 __global__ void k_randk_mark(uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d, uint32_t k, uint32_t seed_lo,
                              uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
+__global__ void k_randk_bin(uint32_t* bucket, uint64_t bucket_ld, uint32_t bucket_cap, uint32_t* gcount,
+                            uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d,
+                            uint32_t k, uint32_t seed_lo, uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
+__global__ void k_randk_fill(const uint32_t* bucket, uint64_t bucket_ld, uint32_t bucket_cap, uint32_t* gcount,
+                             uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d);
 __global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, int zero_marked, uint32_t* bitmap,
                            uint64_t bitmap_ld, uint2* cand, uint64_t cap, uint32_t* cand_count,
                            uint32_t* overflow, uint2* tab, uint32_t ngroups, uint32_t* nonfinite);
@@ -99,7 +104,7 @@ __global__ void k_sample_begin(SelState* sel, uint32_t n, uint32_t k_s, uint32_t
 __global__ void k_sample_finish(const SelState* sel, uint32_t n, uint32_t* bound, uint32_t* zero_at);
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,
-                             float* msg_val, uint64_t msg_ld, uint32_t k);
+                             float* msg_val, uint64_t msg_ld, uint32_t k, int fix_e);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
 __global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off);
 // Where the model update reads x_t and writes x_{t+1}: given rows, or (inside a captured graph)

@@ -395,29 +395,135 @@ __device__ __forceinline__ uint32_t fmix32(uint32_t h) {
     return h;
 }
 
+struct RandkPerm { uint32_t key[4]; uint32_t half, mask, d; };
+
+__device__ __forceinline__ RandkPerm randk_perm(uint32_t w, uint32_t d, uint32_t seed_lo, uint32_t seed_hi,
+                                                uint32_t t_lo, uint32_t t_hi) {
+    RandkPerm p;
+    const U4 rk = philox_block(0xffffffffu, w, t_lo, t_hi, seed_lo, seed_hi);
+    p.key[0] = rk.a; p.key[1] = rk.b; p.key[2] = rk.c; p.key[3] = rk.d;
+    p.half = 1;
+    while (((uint64_t)1 << (2u * p.half)) < (uint64_t)d) ++p.half;
+    p.mask = (uint32_t)(((uint64_t)1 << p.half) - 1u);
+    p.d = d;
+    return p;
+}
+
+__device__ __forceinline__ uint32_t randk_image(const RandkPerm& p, uint64_t m) {
+    uint64_t y = m;
+    do {                                       // walk until the image falls inside [0, d)
+        uint32_t left = (uint32_t)(y >> p.half), right = (uint32_t)y & p.mask;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t nr = left ^ (fmix32(right ^ p.key[r]) & p.mask);
+            left = right;
+            right = nr;
+        }
+        y = ((uint64_t)left << p.half) | right;
+    } while (y >= (uint64_t)p.d);
+    return (uint32_t)y;
+}
+
 __global__ __launch_bounds__(256) void k_randk_mark(uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
                                                     uint32_t d, uint32_t k, uint32_t seed_lo,
                                                     uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
     const uint32_t w = blockIdx.y;
-    const U4 rk = philox_block(0xffffffffu, w, t_lo, t_hi, seed_lo, seed_hi);
-    const uint32_t key[4] = {rk.a, rk.b, rk.c, rk.d};
-    uint32_t half = 1;
-    while (((uint64_t)1 << (2u * half)) < (uint64_t)d) ++half;
-    const uint32_t mask = (uint32_t)(((uint64_t)1 << half) - 1u);
+    const RandkPerm perm = randk_perm(w, d, seed_lo, seed_hi, t_lo, t_hi);
     uint32_t* row = bitmap + (uint64_t)w * bitmap_ld;
     for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
-        uint64_t y = m;
-        do {                                   // walk until the image falls inside [0, d)
-            uint32_t left = (uint32_t)(y >> half), right = (uint32_t)y & mask;
+        const uint32_t y = randk_image(perm, m);
+        atomicOr(&row[y >> 5], 1u << (y & 31u));
+    }
+}
+
+// Marking many coordinates (k a sizeable share of d) bit by bit costs one memory-side atomic on
+// a random line per coordinate.  Instead the images are first sorted coarsely: the coordinate
+// range is cut into `regions` regions of 2^region_bits coordinates, and each image is appended to
+// its region's bucket (bucket_cap entries; gcount[w][region] counts them).  A block takes 8192
+// values of m, counts its images per region in LDS, reserves a run in every bucket it needs
+// with one atomic per region, and writes the images there.  An image that finds its bucket full
+// is set in the bitmap directly.  k_randk_fill then sets a region's bits in LDS and writes the
+// words out.  grid (blocks, n), 1024 threads; regions <= 2048.
+__global__ __launch_bounds__(1024) void k_randk_bin(uint32_t* __restrict__ bucket, uint64_t bucket_ld,
+                                                    uint32_t bucket_cap, uint32_t* __restrict__ gcount,
+                                                    uint32_t region_bits, uint32_t regions,
+                                                    uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
+                                                    uint32_t d, uint32_t k, uint32_t seed_lo,
+                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
+    __shared__ uint32_t cnt[2048];
+    __shared__ uint32_t base[2048];
+    const uint32_t w = blockIdx.y;
+    const RandkPerm perm = randk_perm(w, d, seed_lo, seed_hi, t_lo, t_hi);
+    uint32_t* mine = bucket + (uint64_t)w * bucket_ld;
+    const uint32_t chunks = (uint32_t)(((uint64_t)k + 8191u) >> 13);
+    for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+        for (uint32_t r = threadIdx.x; r < regions; r += blockDim.x) cnt[r] = 0u;
+        __syncthreads();
+        uint32_t y[8], rank[8];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint32_t nr = left ^ (fmix32(right ^ key[r]) & mask);
-                left = right;
-                right = nr;
+        for (int i = 0; i < 8; ++i) {
+            const uint64_t m = ((uint64_t)chunk << 13) + (uint32_t)i * 1024u + threadIdx.x;
+            y[i] = 0u; rank[i] = 0u;
+            if (m < (uint64_t)k) {
+                y[i] = randk_image(perm, m);
+                rank[i] = atomicAdd(&cnt[y[i] >> region_bits], 1u);
             }
-            y = ((uint64_t)left << half) | right;
-        } while (y >= (uint64_t)d);
-        atomicOr(&row[(uint32_t)y >> 5], 1u << ((uint32_t)y & 31u));
+        }
+        __syncthreads();
+        for (uint32_t r = threadIdx.x; r < regions; r += blockDim.x) {
+            const uint32_t c = cnt[r];
+            base[r] = c ? atomicAdd(&gcount[(uint64_t)w * regions + r], c) : 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint64_t m = ((uint64_t)chunk << 13) + (uint32_t)i * 1024u + threadIdx.x;
+            if (m < (uint64_t)k) {
+                const uint32_t r = y[i] >> region_bits;
+                const uint64_t pos = (uint64_t)base[r] + rank[i];
+                if (pos < (uint64_t)bucket_cap) mine[(uint64_t)r * bucket_cap + pos] = y[i];
+                else atomicOr(&bitmap[(uint64_t)w * bitmap_ld + (y[i] >> 5)], 1u << (y[i] & 31u));
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// grid (regions, n), 1024 threads: sets the region's bits tile by tile (2^18 coordinates, 32 KB of
+// LDS) from its bucket and ORs the words into the bitmap (no other block touches these words);
+// leaves gcount at zero for the next iteration.
+__global__ __launch_bounds__(1024) void k_randk_fill(const uint32_t* __restrict__ bucket, uint64_t bucket_ld,
+                                                     uint32_t bucket_cap, uint32_t* __restrict__ gcount,
+                                                     uint32_t region_bits, uint32_t regions,
+                                                     uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
+                                                     uint32_t d) {
+    __shared__ uint32_t bits[8192];
+    const uint32_t w = blockIdx.y, r = blockIdx.x;
+    uint32_t count = gcount[(uint64_t)w * regions + r];
+    if (count > bucket_cap) count = bucket_cap;
+    __syncthreads();
+    if (threadIdx.x == 0) gcount[(uint64_t)w * regions + r] = 0u;
+    if (count == 0u) return;
+    const uint32_t* mine = bucket + (uint64_t)w * bucket_ld + (uint64_t)r * bucket_cap;
+    uint32_t* row = bitmap + (uint64_t)w * bitmap_ld;
+    const uint32_t tiles = 1u << (region_bits - 18u);
+    for (uint32_t s = 0; s < tiles; ++s) {
+        const uint64_t tile_first = ((uint64_t)r << region_bits) + ((uint64_t)s << 18);
+        if (tile_first >= (uint64_t)d) break;
+        const uint32_t tile_id = (uint32_t)(tile_first >> 18);
+        for (uint32_t q = threadIdx.x; q < 8192u; q += blockDim.x) bits[q] = 0u;
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < count; i += blockDim.x) {
+            const uint32_t y = mine[i];
+            if ((y >> 18) == tile_id) atomicOr(&bits[(y & 0x3ffffu) >> 5], 1u << (y & 31u));
+        }
+        __syncthreads();
+        const uint64_t word0 = tile_first >> 5;
+        for (uint32_t q = threadIdx.x; q < 8192u; q += blockDim.x) {
+            const uint32_t v = bits[q];
+            if (v != 0u && word0 + q < bitmap_ld) row[word0 + q] |= v;
+        }
+        __syncthreads();
     }
 }
 
@@ -635,7 +741,7 @@ __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restric
 // thread block each.  step = (largest magnitude of the block) / 7; code = value / step rounded to
 // the nearest integer (halves to even) inside [-7, 7]; the message value becomes what the
 // receiver decodes, code * step, and the coding error goes back into e at the entry's coordinate
-// (k_chunk_emit had put +0 there).  A block whose step is zero sends zero codes.  Two codes per
+// (k_chunk_emit, run with fix_e = 0, left p there).  A block whose step is zero sends zero codes.  Two codes per
 // byte, even position in the low nibble, two's complement.  grid (ceil(k / 256), n).
 __global__ __launch_bounds__(256) void k_quantize4(const uint32_t* __restrict__ msg_idx,
                                                    float* __restrict__ msg_val, uint64_t msg_ld, uint32_t k,
@@ -1013,14 +1119,16 @@ __global__ __launch_bounds__(1024) void k_chunk_scan(SelViews vs, SelState* __re
 // others their value.  In a row view the position is the coordinate and every sent entry is
 // cleared.  In a candidate view map[pos] is the coordinate of entry pos, and the accumulate
 // pass has already cleared the candidates at or above zero_used: only a sent entry below it
-// still has to be cleared, and an unsent one at or above it gets its value back.
+// still has to be cleared, and an unsent one at or above it gets its value back.  fix_e = 0
+// leaves e alone altogether (the composed compressor's 4-bit stage writes the sent entries'
+// residuals itself).
 __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState* __restrict__ sel,
                                                     const uint32_t* __restrict__ out_base,
                                                     const uint32_t* __restrict__ eq_before,
                                                     uint32_t stride, float* __restrict__ e,
                                                     uint32_t* __restrict__ msg_idx,
                                                     float* __restrict__ msg_val, uint64_t msg_ld,
-                                                    uint32_t k) {
+                                                    uint32_t k, int fix_e) {
     __shared__ uint32_t lds[5];
     // the entries a round of the block sends are gathered here and leave with contiguous stores
     __shared__ uint32_t out_idx[1024];
@@ -1074,8 +1182,8 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
                     out_idx[at] = coord;
                     out_val[at] = vv[m];
                     ++at;
-                    if (!cleared) erow[coord] = 0.0f;
-                } else if (valid[m] && cleared) {
+                    if (!cleared && fix_e) erow[coord] = 0.0f;
+                } else if (valid[m] && cleared && fix_e) {
                     erow[v.map[j + m]] = vv[m];
                 }
             }

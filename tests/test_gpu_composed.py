@@ -117,6 +117,22 @@ def test_growing_message_keeps_codes_in_step(ddef, oracle_mod):
     g.close()
 
 
+@pytest.mark.parametrize("compressor,percent", [(2, 0), (2, 60), (1, 0), (1, 95)])
+def test_many_kept_coordinates_are_binned(ddef, oracle_mod, compressor, percent):
+    # k1 >= 2^20 kept coordinates per worker: the bits are set through the region buckets; with
+    # buckets sized below their expected fill a good part of them goes the bit-by-bit way instead
+    d, n = 6_000_000, 2
+    w = workloads.replace(workloads.get("C1", d=d, n=n), seed=91)
+    g, o = pair(ddef, oracle_mod, w, 0, 0.2)
+    g.set_compressor(compressor); o.set_compressor(compressor)
+    g.set_option(ddef.OPT_RANDK_BUCKET_PERCENT, percent)
+    delta = 0.1 if compressor == 2 else 0.2
+    for t in range(3):
+        g.step(delta, w.lr); o.step(delta, w.lr)
+        assert_same(g, o, n, (compressor, percent, t), codes=compressor == 2)
+    g.close()
+
+
 def test_argument_and_state_checks(ddef):
     c = ddef.Context(1000, 1, 0)
     one = np.ones(1000, dtype=F32)
