@@ -240,9 +240,12 @@ uint64_t candidate_capacity(const ddef_ctx* c, uint64_t k, uint64_t kb) {
     return ((want + 4095u) & ~(uint64_t)4095u) + 256u * kSubs;
 }
 
-// candidate target: slack/16 times k for sparse messages (k/d <= 1/32), else 1.5 k
+// candidate target: slack/16 times k for sparse messages (k/d <= 1/32), whose bound follows the
+// trend of the last thresholds; k + k/24 for dense ones, whose bound comes from a fine sample of this
+// very p in every iteration (some 65 000 sample entries above it: the count caught misses the
+// target by about 0.4 %, a tenth of the margin)
 uint64_t candidate_target(const ddef_ctx* c, uint64_t k) {
-    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 2u;
+    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 24u;
     if (kb < k) kb = k;
     if (kb > c->d) kb = c->d;
     return kb;
@@ -838,7 +841,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     const bool can_filter = !c->opt_force_full && 2 * kb <= c->d;
     const bool dense = k * 32u > c->d;
     if (can_filter && (dense || !c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
-        rc = bound_from_sample(c, k, kb, lr, dense ? 4096u : 256u);
+        rc = bound_from_sample(c, k, kb, lr, dense ? 65536u : 256u);
         if (rc) return rc;
     }
     const bool use_filter = can_filter && c->have_bound;
