@@ -77,6 +77,7 @@ def lib():
         "oracle_murmur_fmix32": (C.c_uint32, [C.c_uint32]),
         "oracle_set_compressor": (None, [vp, C.c_int]),
         "oracle_set_composed": (None, [vp, C.c_double]),
+        "oracle_objective": (C.c_double, [vp]),
         "oracle_quantize4": (None, [f32p, C.c_uint64, C.POINTER(C.c_uint8), f32p, f32p]),
         "oracle_get_message_codes": (None, [vp, C.c_uint32, C.POINTER(C.c_uint8), f32p]),
         "oracle_set_heterogeneity": (None, [vp, C.c_float]),
@@ -343,6 +344,10 @@ class Oracle:
 
     def get_model(self):
         return self._get_vec(lib().oracle_get_model)
+
+    def objective(self):
+        """f(x_t) = (1/n) sum_i f_i(x_t) of the synthetic quadratics, in double."""
+        return float(lib().oracle_objective(self._h))
 
     def set_model(self, x):
         _, xp = _f32(x)

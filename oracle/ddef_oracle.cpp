@@ -22,6 +22,7 @@
 //   start-up          Delta_{t-tau} = 0 while t-tau < 0       Section 3.2, boundary convention
 //   DeCo              (tau*, delta*) minimising phi           Algorithm 3, Remark on delta*(tau)
 //   timing            TS/TM/TC recurrence, T_avg closed form  Section 4.1, Theorem 3 and its proof
+//   objective         f(x) = (1/n) sum_i f_i(x)               Section 2.1, problem (1)
 //
 // Two forms of the delay are coded.  The normative one keeps a ring of parameter
 // snapshots and takes the gradient at the old iterate x_{t-tau}; the literal one
@@ -531,6 +532,26 @@ void oracle_step(void* h, double delta, float lr) {
     oracle_ef_compress(h, delta, lr);
     oracle_aggregate(h);
     oracle_apply_delayed(h);
+}
+
+// The objective the method minimises (Section 2.1, problem (1)) at the current iterate:
+// f(x_t) = (1/n) sum_i f_i(x_t) with the synthetic quadratics f_i(x) = 1/2 sum_j lambda_j (x_j - x*_ij)^2,
+// x*_i = x* + zeta u_i as in the gradient.  Evaluated in double from the fp32 state.
+double oracle_objective(void* h) {
+    Oracle* o = (Oracle*)h;
+    const std::vector<float>& x = o->slot(o->t);
+    double total = 0.0;
+    for (uint64_t j = 0; j < o->d; ++j) {
+        double squares = 0.0;
+        for (uint32_t i = 0; i < o->n; ++i) {
+            float optimum = o->xstar[j];
+            if (o->zeta != 0.0f) optimum = o->xstar[j] + o->zeta * noise_z(o->seed, kHeterogeneityKey, i, (uint32_t)j, 1);
+            double diff = (double)x[j] - (double)optimum;
+            squares += diff * diff;
+        }
+        total += (double)o->lambda[j] * (squares / (double)o->n);
+    }
+    return 0.5 * total;
 }
 
 void oracle_get_model(void* h, float* x) {
