@@ -31,6 +31,7 @@ SIGNATURES = {
     "ddef_set_tau": (C.c_int, [_ctx, C.c_uint32]),
     "ddef_set_compressor": (C.c_int, [_ctx, C.c_int]),
     "ddef_set_composed": (C.c_int, [_ctx, C.c_double]),
+    "ddef_objective": (C.c_int, [_ctx, C.POINTER(C.c_double)]),
     "ddef_get_message_codes": (C.c_int, [_ctx, C.c_uint32, C.POINTER(C.c_uint8), _f32p, _u64p]),
     "ddef_set_heterogeneity": (C.c_int, [_ctx, C.c_float]),
     "ddef_deco_noniid": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
@@ -355,6 +356,12 @@ class Context:
             self._check(self._lib.ddef_get_message(self._h, int(worker), idx.ctypes.data_as(_u32p),
                                                    val.ctypes.data_as(_f32p), C.byref(k)), "ddef_get_message")
         return idx, val
+
+    def objective(self) -> float:
+        """f(x_t) = (1/n) sum_i f_i(x_t) of the synthetic quadratics at the current iterate."""
+        f = C.c_double()
+        self._check(self._lib.ddef_objective(self._h, C.byref(f)), "ddef_objective")
+        return float(f.value)
 
     def get_message_codes(self, worker: int):
         """(packed 4-bit codes, block steps) of the last message under the composed compressor."""

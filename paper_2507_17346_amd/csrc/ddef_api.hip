@@ -22,12 +22,12 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_RANDK_BIN, SL_RANDK_FILL, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_QUANTIZE4, SL_SAMPLE, SL_FILL,
-    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_COUNT
+    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_OBJECTIVE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_randk_bin", "k_randk_fill", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_quantize4",
-    "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4"};
+    "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4", "k_objective"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -87,6 +87,7 @@ struct ddef_ctx {
     uint64_t pf_t = 0;
     uint32_t pf_tau = 0;
     uint32_t* bitmap = nullptr;          // Random-k: one bit per coordinate, [n][ld/32], all-zero between steps
+    double* objective_partial = nullptr; // ddef_objective: one partial sum per block
     uint32_t* region_count = nullptr;    // Random-k, binned marking: [n][2048] bucket fill counts, all-zero between steps
     // composed compressor: share of the coordinates its Random-k stage keeps, and the wire form of
     // the last message: codes [n][codes_ld] bytes (two entries each), steps [n][codes_ld/128] floats
@@ -604,7 +605,7 @@ int ddef_destroy(ddef_ctx* c) {
     for (const ProfRecord& r : c->pending) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
-                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->region_count, c->g_next, c->cand,
+                    c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->region_count, c->objective_partial, c->g_next, c->cand,
                     c->sorted_idx, c->sorted_val, c->codes, c->steps};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
@@ -1034,6 +1035,28 @@ int ddef_get_model(ddef_ctx* c, float* host_x) {
     if (!host_x) return DDEF_EINVAL;
     DeviceGuard guard(c->device);
     return copy_row_out(c, c->slot(c->t), host_x);
+}
+
+int ddef_objective(ddef_ctx* c, double* host_f) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!host_f) return DDEF_EINVAL;
+    if (!c->problem_set) return DDEF_ESTATE;
+    DeviceGuard guard(c->device);
+    const uint32_t blocks = blocks_for(c, ((c->d + 3u) / 4u + 255u) / 256u, 1, 8);
+    const uint32_t most = (uint32_t)c->cus * 8u;
+    if (!c->objective_partial) HIP_TRY(c, hipMalloc((void**)&c->objective_partial, (size_t)most * 8u));
+    GradSource src = grad_source(c, 0, c->slot(c->t));
+    src.t_dev = nullptr;                       // the iterate is named by the host's counter
+    LAUNCH(c, SL_OBJECTIVE, k_objective, dim3(blocks), dim3(256), src, (uint32_t)c->d, c->n, c->objective_partial);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::vector<double> partial(blocks);
+    HIP_TRY(c, hipMemcpy(partial.data(), c->objective_partial, (size_t)blocks * 8u, hipMemcpyDeviceToHost));
+    double total = 0.0;
+    for (double v : partial) total += v;
+    *host_f = 0.5 * total;
+    return DDEF_OK;
 }
 
 int ddef_set_model(ddef_ctx* c, const float* host_x) {

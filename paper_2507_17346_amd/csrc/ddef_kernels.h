@@ -60,6 +60,7 @@ struct GradSource {
 };
 
 __global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);
+__global__ void k_objective(GradSource s, uint32_t d, uint32_t n, double* partial);
 template <bool kFusedGrad>
 __global__ void k_ef_filter(float* e, const float* g, GradSource src, uint32_t n, uint64_t ld, uint32_t d,
                             float lr, const uint32_t* bound, const uint32_t* zero_at, int use_filter, uint2* cand, uint64_t cap,

@@ -260,6 +260,42 @@ __global__ __launch_bounds__(256) void k_grad(GradSource s, float* __restrict__ 
     }
 }
 
+// The objective at the iterate x (Section 2.1, problem (1)): f(x) = (1/n) sum_i f_i(x) with
+// f_i(x) = 1/2 sum_j lambda_j (x_j - x*_ij)^2 and x*_i = x* + zeta u_i as in the gradient,
+// accumulated in double.  Each block writes the sum of its coordinates' terms (without the
+// factor 1/2) to partial[blockIdx.x]; the host adds the partials in block order.
+__global__ __launch_bounds__(256) void k_objective(GradSource s, uint32_t d, uint32_t n,
+                                                   double* __restrict__ partial) {
+    __shared__ double red[4];
+    const uint32_t quads = (d + 3u) >> 2;
+    double acc = 0.0;
+    for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += gridDim.x * blockDim.x) {
+        const uint32_t j = q << 2;
+        const Shared4 sh = grad_shared4(s, j);
+        double squares[4] = {0.0, 0.0, 0.0, 0.0};
+        const uint32_t workers = s.zeta != 0.0f ? n : 1u;      // identical optima: one term stands for all
+        for (uint32_t i = 0; i < workers; ++i) {
+            float shift[4] = {0.f, 0.f, 0.f, 0.f};
+            if (s.zeta != 0.0f) draw_normal4(j >> 2, i, 0xfffffffeu, 0xffffffffu, s.seed_lo, s.seed_hi, shift);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float optimum = sh.opt[c];
+                if (s.zeta != 0.0f) optimum = sh.opt[c] + s.zeta * shift[c];
+                const double diff = (double)sh.x[c] - (double)optimum;
+                squares[c] += diff * diff;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (j + c < d) acc += (double)sh.lam[c] * (squares[c] / (double)workers);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane_id() == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 // ------------------------------------------------------------------------------------
 // S1 (+ candidate filter of S2/S3)   p = e + lr * g, written over e   (Algorithm 1, worker side)
 //

@@ -1,0 +1,71 @@
+"""GPU: the objective value against the oracle's, and the paper's central claim on the synthetic
+quadratic: with the timing model of Section 4.1, DeCo's joint choice of staleness and compression
+reaches a target objective sooner than D-SGD, compression alone or delay alone (Section 5.3)."""
+import numpy as np
+import pytest
+
+from paper_2507_17346_amd import time_to_accuracy as tta
+from paper_2507_17346_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def ddef():
+    from paper_2507_17346_amd import binding
+    binding.load()
+    return binding
+
+
+@pytest.mark.parametrize("d,n,zeta", [(1, 1, 0.0), (5, 3, 0.0), (4097, 2, 0.3), (300_001, 4, 0.0), (1_000_003, 3, 0.5)])
+def test_objective_matches_the_oracle(ddef, oracle_mod, d, n, zeta):
+    w = workloads.replace(workloads.get("C1", d=d, n=n), seed=300 + d)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(d, n, 2)
+    o = oracle_mod.Oracle(d, n, 2, threads=4)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(1)
+        h.set_heterogeneity(zeta)
+    for t in range(5):
+        # double sums in different orders: d terms of similar size
+        assert g.objective() == pytest.approx(o.objective(), rel=1e-12 * max(1.0, np.sqrt(d)))
+        g.step(0.1, w.lr); o.step(0.1, w.lr)
+    g.set_model(xstar)
+    if zeta == 0.0:
+        assert g.objective() == 0.0
+    g.close()
+
+
+def test_objective_argument_and_state_checks(ddef):
+    import ctypes as C
+    c = ddef.Context(1000, 2, 1)
+    f = C.c_double()
+    assert c.raw("objective", C.byref(f)) == ddef.ESTATE          # no problem yet
+    one = np.ones(1000, dtype=F32)
+    c.set_problem(one, one, one * F32(3.0), 0, 0, 0.0)
+    assert c.raw("objective", None) == ddef.EINVAL
+    assert c.objective() == pytest.approx(0.5 * 1000 * 4.0)
+    c.close()
+
+
+def test_deco_reaches_the_target_first(ddef):
+    w = workloads.get("C1", d=200_000, n=4)
+    net = tta.Network(32.0 * w.d, 20e6, 0.1, 0.02)        # V_g / a = 0.32 s, b = 0.1 s, T_comp = 0.02 s
+    outcomes = {o.strategy.name: o for o in tta.compare(w, net, target_ratio=0.02, max_iterations=20000,
+                                                        check_every=25, tau_max=16)}
+    for name, o in outcomes.items():
+        assert o.iterations is not None, (name, o.curve[-1])
+        print(f"{name:18s} tau={o.strategy.tau:2d} delta={o.strategy.delta:.4f} T_avg={o.t_avg_s:.4f} s "
+              f"iterations={o.iterations} seconds={o.seconds:.1f}")
+    deco = outcomes["DeCo"]
+    for name in ("D-SGD", "compression only", "delay only"):
+        assert deco.seconds < outcomes[name].seconds, name
+    # compression and delay cost iterations, but far fewer than the time per iteration they save
+    assert deco.iterations >= outcomes["D-SGD"].iterations
+    assert outcomes["D-SGD"].seconds / deco.seconds > 3.0
+    # every curve decreases to its target
+    for o in outcomes.values():
+        assert o.curve[-1][2] <= 0.02 < o.curve[0][2]
