@@ -87,6 +87,42 @@ def run(w, s: Strategy, net: Network, target_ratio: float, max_iterations: int, 
         ctx.close()
 
 
+def run_adaptive(w, nets: List[Network], period: int, adaptive: bool, target_ratio: float,
+                 max_iterations: int, tau_max: int = 16) -> Outcome:
+    """A network that changes every `period` iterations (nets[p % len(nets)] holds during period p).
+    adaptive = True is DeCo-SGD (Algorithm 2): (tau, delta) re-chosen by Algorithm 3 at the start of
+    every period from that period's network.  adaptive = False keeps the choice made for the
+    first period.  Seconds accumulate period by period with each period's iteration time under
+    the (tau, delta) in force; the objective is looked at once per period."""
+    lam, xstar, x0 = workloads.make_problem(w)
+    ctx = binding.Context(w.d, w.n, tau_max)
+    try:
+        ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        f0 = ctx.objective()
+        curve = [(0, 0.0, 1.0)]
+        seconds, t, reached, p = 0.0, 0, None, 0
+        first = None
+        while t < max_iterations and reached is None:
+            net = nets[p % len(nets)]
+            if adaptive or first is None:
+                tau, delta = binding.deco(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
+                first = Strategy("DeCo-SGD" if adaptive else "DeCo, first period's choice kept",
+                                 int(min(tau_max, tau)), float(delta))
+            ctx.set_tau(first.tau)
+            for _ in range(period):
+                ctx.step(first.delta, w.lr)
+            t += period
+            seconds += period * t_avg(net, first, max(period, 2))
+            ratio = ctx.objective() / f0
+            curve.append((t, seconds, ratio))
+            if ratio <= target_ratio:
+                reached = t
+            p += 1
+        return Outcome(first, seconds / max(t, 1), reached, None if reached is None else seconds, curve)
+    finally:
+        ctx.close()
+
+
 def compare(w, net: Network, target_ratio: float = 0.02, max_iterations: int = 20000, check_every: int = 50,
             tau_max: int = 16) -> List[Outcome]:
     return [run(w, s, net, target_ratio, max_iterations, check_every, tau_max) for s in strategies(net, tau_max)]

@@ -69,3 +69,19 @@ def test_deco_reaches_the_target_first(ddef):
     # every curve decreases to its target
     for o in outcomes.values():
         assert o.curve[-1][2] <= 0.02 < o.curve[0][2]
+
+
+def test_adapting_to_a_changing_network_beats_a_fixed_choice(ddef):
+    """Algorithm 2 on a bandwidth that alternates between 200 and 10 Mbit/s every 50 iterations: the
+    choice made for the fast period sends 20 times too much in the slow ones."""
+    w = workloads.get("C1", d=200_000, n=4)
+    v_g = 32.0 * w.d
+    nets = [tta.Network(v_g, 200e6, 0.1, 0.02), tta.Network(v_g, 10e6, 0.1, 0.02)]
+    fixed = tta.run_adaptive(w, nets, 50, False, 0.02, 20000)
+    adaptive = tta.run_adaptive(w, nets, 50, True, 0.02, 20000)
+    assert fixed.iterations is not None and adaptive.iterations is not None
+    print(f"fixed: {fixed.iterations} iterations, {fixed.seconds:.1f} s; adaptive: {adaptive.iterations} iterations, "
+          f"{adaptive.seconds:.1f} s")
+    assert adaptive.seconds < fixed.seconds
+    # the adaptive run pays about T_comp per iteration throughout
+    assert adaptive.seconds / adaptive.iterations == pytest.approx(0.02, rel=0.25)
