@@ -445,18 +445,21 @@ __device__ __forceinline__ RandkPerm randk_perm(uint32_t w, uint32_t d, uint32_t
     return p;
 }
 
+// one pass through the four Feistel rounds (a bijection of [0, 4^half))
+__device__ __forceinline__ uint64_t randk_rounds(const RandkPerm& p, uint64_t y) {
+    uint32_t left = (uint32_t)(y >> p.half), right = (uint32_t)y & p.mask;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t nr = left ^ (fmix32(right ^ p.key[r]) & p.mask);
+        left = right;
+        right = nr;
+    }
+    return ((uint64_t)left << p.half) | right;
+}
+
 __device__ __forceinline__ uint32_t randk_image(const RandkPerm& p, uint64_t m) {
     uint64_t y = m;
-    do {                                       // walk until the image falls inside [0, d)
-        uint32_t left = (uint32_t)(y >> p.half), right = (uint32_t)y & p.mask;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t nr = left ^ (fmix32(right ^ p.key[r]) & p.mask);
-            left = right;
-            right = nr;
-        }
-        y = ((uint64_t)left << p.half) | right;
-    } while (y >= (uint64_t)p.d);
+    do y = randk_rounds(p, y); while (y >= (uint64_t)p.d);   // walk until the image falls inside [0, d)
     return (uint32_t)y;
 }
 
@@ -488,6 +491,7 @@ __global__ __launch_bounds__(1024) void k_randk_bin(uint32_t* __restrict__ bucke
                                                     uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
     __shared__ uint32_t cnt[2048];
     __shared__ uint32_t base[2048];
+    __shared__ uint32_t images[8192];         // images[i * 1024 + thread]: the thread's i-th image
     const uint32_t w = blockIdx.y;
     const RandkPerm perm = randk_perm(w, d, seed_lo, seed_hi, t_lo, t_hi);
     uint32_t* mine = bucket + (uint64_t)w * bucket_ld;
@@ -495,13 +499,34 @@ __global__ __launch_bounds__(1024) void k_randk_bin(uint32_t* __restrict__ bucke
     for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
         for (uint32_t r = threadIdx.x; r < regions; r += blockDim.x) cnt[r] = 0u;
         __syncthreads();
+        // The walk into [0, d) takes a different number of passes for every m (about 4^half / d
+        // on average).  Walking one m after the other, a wave would wait for its slowest lane
+        // eight times over; instead every lane walks through its eight values back to back and
+        // the wave ends when the lane with the most passes in total is done.
+        const uint64_t m0 = ((uint64_t)chunk << 13) + threadIdx.x;
+        uint32_t items = 0;
+        if (m0 < (uint64_t)k) {
+            const uint64_t room = ((uint64_t)k - m0 + 1023u) >> 10;
+            items = room < 8u ? (uint32_t)room : 8u;
+        }
+        uint32_t cur = 0;
+        uint64_t val = m0;
+        while (__any(cur < items)) {
+            if (cur < items) {
+                val = randk_rounds(perm, val);
+                if (val < (uint64_t)d) {
+                    images[cur * 1024u + threadIdx.x] = (uint32_t)val;
+                    ++cur;
+                    val = m0 + (uint64_t)cur * 1024u;
+                }
+            }
+        }
         uint32_t y[8], rank[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const uint64_t m = ((uint64_t)chunk << 13) + (uint32_t)i * 1024u + threadIdx.x;
             y[i] = 0u; rank[i] = 0u;
-            if (m < (uint64_t)k) {
-                y[i] = randk_image(perm, m);
+            if ((uint32_t)i < items) {
+                y[i] = images[(uint32_t)i * 1024u + threadIdx.x];
                 rank[i] = atomicAdd(&cnt[y[i] >> region_bits], 1u);
             }
         }
@@ -513,8 +538,7 @@ __global__ __launch_bounds__(1024) void k_randk_bin(uint32_t* __restrict__ bucke
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const uint64_t m = ((uint64_t)chunk << 13) + (uint32_t)i * 1024u + threadIdx.x;
-            if (m < (uint64_t)k) {
+            if ((uint32_t)i < items) {
                 const uint32_t r = y[i] >> region_bits;
                 const uint64_t pos = (uint64_t)base[r] + rank[i];
                 if (pos < (uint64_t)bucket_cap) mine[(uint64_t)r * bucket_cap + pos] = y[i];
