@@ -133,6 +133,24 @@ def test_many_kept_coordinates_are_binned(ddef, oracle_mod, compressor, percent)
     g.close()
 
 
+@pytest.mark.parametrize("option", ["fuse", "prefetch", "noniid"])
+def test_composed_under_the_library_options(ddef, oracle_mod, option):
+    # the gradient options fall back to a stored gradient under this compressor; heterogeneous
+    # optima only change the gradient: the trajectory must not depend on any of them
+    w = workloads.replace(workloads.get("C3", d=150_001, n=3), seed=404)
+    g, o = pair(ddef, oracle_mod, w, 2, 0.2)
+    if option == "fuse":
+        g.set_option(ddef.OPT_FUSE_GRAD, 1)
+    elif option == "prefetch":
+        g.set_option(ddef.OPT_PREFETCH_GRAD, 1)
+    else:
+        g.set_heterogeneity(0.4); o.set_heterogeneity(0.4)
+    for t in range(7):
+        g.step(0.1, w.lr); o.step(0.1, w.lr)
+        assert_same(g, o, w.n, (option, t))
+    g.close()
+
+
 def test_argument_and_state_checks(ddef):
     c = ddef.Context(1000, 1, 0)
     one = np.ones(1000, dtype=F32)
