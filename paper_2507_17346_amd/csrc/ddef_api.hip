@@ -436,8 +436,8 @@ int start_prefetch(ddef_ctx* c) {
     return DDEF_OK;
 }
 
-// Places bound[] and zero_at[] for a selection of k (candidate target kb) from every stride-th entry
-// of p = e + lr*g: the radix select of the path, run on the sample for the ranks k/stride and
+// Places bound[] and zero_at[] for a selection of k (candidate target kb) from one entry in `stride`
+// of p = e + lr*g (taken eight consecutive coordinates at a time): the radix select of the path, run on the sample for the ranks k/stride and
 // kb/stride.  The stride keeps about `above` sample entries above the bound (count error about
 // 1/sqrt(above)) within a sample of at most kSampleMax entries per worker; with fewer than 8 above
 // the bound sampling says too little, and the iteration goes on with what it had (a whole-row
@@ -448,12 +448,12 @@ int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t a
     const uint64_t least = (c->d + kSampleMax - 1u) / kSampleMax;
     if (stride < least) stride = least;
     if (stride < 1u) stride = 1u;
-    const uint64_t count = (c->d + stride - 1u) / stride;
+    const uint64_t count = 8u * ((c->d + 8u * stride - 1u) / (8u * stride));   // whole octets
     const uint64_t kb_s = kb / stride, k_s = k / stride > 0u ? k / stride : 1u;
     if (kb_s < 8u || kb_s > count) return DDEF_OK;
     const uint32_t n = c->n;
     if (!c->sample) {
-        c->sample_ld = ((c->d < kSampleMax ? c->d : kSampleMax) + 7u) & ~(uint64_t)3u;
+        c->sample_ld = ((c->d < kSampleMax ? c->d : kSampleMax) + 15u) & ~(uint64_t)3u;
         HIP_TRY(c, hipMalloc((void**)&c->sample, (size_t)n * c->sample_ld * 4u));
         HIP_TRY(c, hipMemsetAsync(c->sample, 0, (size_t)n * c->sample_ld * 4u, c->stream));
         HIP_TRY(c, hipMalloc((void**)&c->sample_total, (size_t)n * 4u));
@@ -461,7 +461,8 @@ int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t a
     }
     materialize_grad(c);                      // the sample reads g from memory
     LAUNCH(c, SL_SAMPLE, k_sample_p, dim3((uint32_t)((count + 255u) / 256u), n), dim3(256), (const float*)c->e,
-           (const float*)c->g, c->ld, lr, (uint32_t)stride, (uint32_t)count, c->sample, c->sample_ld);
+           (const float*)c->g, c->ld, (uint32_t)c->d, lr, (uint32_t)stride, (uint32_t)count, c->sample,
+           c->sample_ld);
     LAUNCH(c, SL_SAMPLE, k_sample_begin, dim3(n), dim3(256), c->sel, n, (uint32_t)k_s, (uint32_t)kb_s,
            (uint32_t)count, c->sample_total, c->hist);
     const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sample, (const uint32_t*)nullptr, c->sample_ld,

@@ -1104,20 +1104,28 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
 }
 
 // Filter bound from a sample.  Where no bound fits the coming selection (the first iteration, or k
-// changed: Algorithm 2 re-chooses delta), every `stride`-th entry of p = e + lr*g is computed ahead
-// of the accumulate pass, and the radix select of S2 runs on that sample for the ranks
+// changed: Algorithm 2 re-chooses delta), one entry in `stride` of p = e + lr*g is computed ahead
+// of the accumulate pass -- eight consecutive coordinates out of every 8 * stride, so that a
+// sample point costs an eighth of a 32-byte access per array instead of a whole one -- and the
+// radix select of S2 runs on that sample for the ranks
 // k / stride and kb / stride: the patterns found there estimate the threshold and the pattern at
 // the candidate target for the whole row (the count above the bound then misses its target by
 // about 1 / sqrt(kb / stride), far inside the usable window [k, 3 kb]).  As always the bound only
 // decides which search runs; the selection that follows is exact.
 __global__ __launch_bounds__(256) void k_sample_p(const float* __restrict__ e, const float* __restrict__ g,
-                                                  uint64_t ld, float lr, uint32_t stride, uint32_t count,
-                                                  float* __restrict__ sample, uint64_t sample_ld) {
+                                                  uint64_t ld, uint32_t d, float lr, uint32_t stride,
+                                                  uint32_t count, float* __restrict__ sample,
+                                                  uint64_t sample_ld) {
     const uint32_t w = blockIdx.y;
     const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= count) return;
-    const uint64_t at = (uint64_t)w * ld + (uint64_t)s * stride;           // s * stride < d
-    sample[(uint64_t)w * sample_ld + s] = e[at] + lr * g[at];
+    const uint64_t coord = (uint64_t)(s >> 3) * 8u * stride + (s & 7u);
+    float v = 0.0f;                            // past the end of the row: ranks last
+    if (coord < (uint64_t)d) {
+        const uint64_t at = (uint64_t)w * ld + coord;
+        v = e[at] + lr * g[at];
+    }
+    sample[(uint64_t)w * sample_ld + s] = v;
 }
 
 // One block per worker: the sample becomes the worker's view and the selection starts.
