@@ -298,8 +298,11 @@ def main():
             row.append(hev.mark())
         marks.append(row)
     ctx.sync()
-    gpu_ms = {name: sum(hev.ms(r[i], r[i + 1]) for r in marks) / args.steps
-              for i, name in enumerate(("grad", "ef_compress", "aggregate", "apply_delayed"))}
+    gpu_samples = {name: [hev.ms(r[i], r[i + 1]) for r in marks]
+                   for i, name in enumerate(("grad", "ef_compress", "aggregate", "apply_delayed"))}
+    gpu_ms = {name: sum(v) / args.steps for name, v in gpu_samples.items()}
+    gpu_median = {name: sorted(v)[len(v) // 2] for name, v in gpu_samples.items()}
+    gpu_min = {name: min(v) for name, v in gpu_samples.items()}
     ctx.set_stream(None)
     hev.close()
     log("  per call, GPU time between HIP events (ms): " + ", ".join(f"{k} {v:.3f}" for k, v in gpu_ms.items()))
@@ -394,6 +397,8 @@ def main():
         "grad": grad_info,
         "ef_topk_aggregate_apply": path,
         "ms_per_call_gpu_events": gpu_ms,
+        "ms_per_call_gpu_events_median": gpu_median,
+        "ms_per_call_gpu_events_min": gpu_min,
         "ms_per_call": phase_ms,
         "ms_per_call_median": phase_median,
         "ms_per_call_min": phase_min,
