@@ -185,7 +185,7 @@ int ddef_get_model(ddef_ctx* ctx, float* host_x);                       /* x_t, 
 /* The objective the method minimises, at the current iterate (Section 2.1, problem (1)):
  * f(x_t) = (1/n) sum_i f_i(x_t), f_i(x) = 1/2 sum_j lambda_j (x_j - x*_ij)^2 with worker i's optimum
  * x*_i = xstar + zeta u_i (ddef_set_heterogeneity).  Computed on the device in double from the
- * fp32 state (the order of the additions is fixed for a given d, so the value is reproducible);
+ * fp32 state (the order of the additions is fixed for a given d and device, so the value is reproducible);
  * waits for the stream.  *host_f: host pointer.  ESTATE before ddef_set_problem. */
 int ddef_objective(ddef_ctx* ctx, double* host_f);
 int ddef_set_model(ddef_ctx* ctx, const float* host_x);                 /* overwrite x_t  */
