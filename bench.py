@@ -94,7 +94,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, compressor=0, rand_ratio=0.2):
+def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, compressor=0, rand_ratio=0.2, zeta=0.0):
     """The oracle, as it stands, on a bounded sample: one non-empty iteration over the first
     sample_d coordinates of the workload (all n workers, one thread per worker unless capped)."""
     import oracle
@@ -114,6 +114,7 @@ def cpu_baseline(w, lam, xstar, x0, sample_d, budget_note, max_threads=None, com
     o.set_tau(0)
     o.set_compressor(compressor)
     o.set_composed(rand_ratio)
+    o.set_heterogeneity(zeta)
     t0 = time.perf_counter()
     o.step(w.deltas[0], w.lr)
     dt = time.perf_counter() - t0
@@ -193,6 +194,8 @@ def main():
     ap.add_argument("--queue-form", type=int, default=0,
                     help="1: server state as a message queue (one model, tau_max+1 queued messages) "
                          "instead of the snapshot ring; same iterates for constant tau")
+    ap.add_argument("--zeta", type=float, default=0.0,
+                    help="heterogeneous local objectives: worker i's optimum is x* + zeta u_i (0: IID, the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -222,6 +225,8 @@ def main():
     ctx.set_compressor(compressor)
     if args.compressor == "composed":
         ctx.set_composed(args.rand_ratio)
+    if args.zeta:
+        ctx.set_heterogeneity(args.zeta)
 
     def sent_ratio(dl):
         """entries per worker in a message, as a share of d"""
@@ -391,7 +396,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched),
                    "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
+                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,
@@ -411,13 +416,13 @@ def main():
         sample_d = args.cpu_sample_d or min(w.d, 124_000_000)
         note = ""
         try:
-            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note, compressor=compressor, rand_ratio=args.rand_ratio)
+            out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, sample_d, note, compressor=compressor, rand_ratio=args.rand_ratio, zeta=args.zeta)
         except MemoryError:
             out["cpu_baseline"] = cpu_baseline(w, lam, xstar, x0, w.d // 8, "; reduced: host memory",
-                                               compressor=compressor, rand_ratio=args.rand_ratio)
+                                               compressor=compressor, rand_ratio=args.rand_ratio, zeta=args.zeta)
         # the same oracle on one thread, on an eighth of the coordinates to keep the run short
         out["cpu_baseline_single_thread"] = cpu_baseline(w, lam, xstar, x0, max(1, sample_d // 8), "",
-                                                         max_threads=1, compressor=compressor, rand_ratio=args.rand_ratio)
+                                                         max_threads=1, compressor=compressor, rand_ratio=args.rand_ratio, zeta=args.zeta)
     ctx.close()
     print(json.dumps(out), flush=True)
 
