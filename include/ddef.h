@@ -280,7 +280,8 @@ int ddef_device_info(ddef_ctx* ctx, uint32_t* compute_units, uint32_t* wave_size
  * rewritten by the next ddef_grad anyway. */
 int ddef_copy_probe(ddef_ctx* ctx, uint64_t* bytes_each_way);
 /* How many worker selections so far took the multi-pass path over the whole vector
- * (counted over all workers and iterations since ddef_set_problem). */
+ * (counted over all workers and iterations since ddef_set_problem), plus n for every iteration
+ * of the composed compressor that had to be repeated without its bound. */
 int ddef_full_select_count(ddef_ctx* ctx, uint64_t* count);
 /* Diagnostics of a worker's last selection: the magnitude bound its candidate filter will use
  * next, how many candidates the filter caught this time, and whether the selection had to
@@ -311,6 +312,13 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                               * default), and what does not fit is set bit by bit.  A value of
                               * 1..400 sizes the buckets at that percentage of the expected fill
                               * instead (tests use it to exercise the overflow path).  Results are
+                              * unchanged.                                                          */
+#define DDEF_OPT_COMPOSED_BOUND 7 /* composed compressor: 1 (default) records only the kept entries above a
+                              * bound placed from a sample of e + lr*g, which a few more than k of them
+                              * are expected to pass, and repeats the pass without the bound when fewer
+                              * than k did (ddef_ef_compress then waits for the stream once per
+                              * iteration to learn which); 0 always records every kept entry; 2 places
+                              * the bound too high on purpose (tests of the repeat).  Results are
                               * unchanged.                                                          */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 

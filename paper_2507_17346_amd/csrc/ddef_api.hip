@@ -117,6 +117,8 @@ struct ddef_ctx {
     uint64_t full_selects = 0;
     int64_t opt_force_full = 0, opt_slack_x16 = 40;
     int64_t opt_bucket_percent = 0;      // Random-k buckets: 0 = expected fill plus slack, else that share of it
+    int64_t opt_composed_bound = 1;      // composed compressor: 1 record only the kept entries above a sampled bound
+    uint64_t composed_retries = 0;       //   and how often that had to be repeated without the bound
     // ddef_step as a captured graph: the launches of one steady iteration, replayed while
     // (k, lr, tau) stay the same.  Inside the graph the iteration number comes from t_dev.
     int64_t opt_graph = 0;
@@ -656,6 +658,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->full_selects = 0;
+    c->composed_retries = 0;
     c->u_zero = true;
     c->agg_deferred = false;
     return DDEF_OK;
@@ -789,14 +792,51 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
             c->codes_ld = c->msg_ld / 2u;
         }
         const uint64_t bitmap_ld = c->ld / 32u;
-        rc = enqueue_randk_mark(c, k1);
+        // The k largest of the kept entries lie above the magnitude that about k of the kept ones
+        // exceed, and a random subset has the quantiles of the whole row: a sample of p places a
+        // bound that a few more than k kept entries are expected to pass (margin: a 24th of k, at
+        // least six standard deviations of the count), and only those are recorded.  Should fewer
+        // than k pass after all, the pass runs again over the stored p without a bound.
+        bool bounded = false;
+        const uint64_t margin = std::max<uint64_t>(k / 24u, (uint64_t)(6.0 * std::sqrt((double)k)) + 1u) + 16u;
+        uint64_t kb2 = k + margin;
+        if (c->opt_composed_bound == 2) kb2 = k / 2u;       // test knob: a bound that is too high
+        if (c->opt_composed_bound && !c->opt_force_full && kb2 >= 8u && 2u * kb2 <= k1) {
+            const double scale = (double)c->d / (double)k1;
+            const uint64_t k_row = std::min<uint64_t>(c->d, (uint64_t)std::ceil((double)k * scale));
+            const uint64_t kb_row = std::min<uint64_t>(c->d, (uint64_t)std::ceil((double)kb2 * scale));
+            c->have_bound = false;
+            rc = bound_from_sample(c, k_row, kb_row, lr, 65536u);
+            if (rc) return rc;
+            bounded = c->have_bound;
+        }
+        auto record = [&](bool with_bound, int accumulate) -> int {
+            int rcm = enqueue_randk_mark(c, k1);
+            if (rcm) return rcm;
+            LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
+                   accumulate, with_bound ? (const uint32_t*)bound : (const uint32_t*)nullptr, c->bitmap, bitmap_ld,
+                   c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+            LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+                   c->span_sum, c->nspans);
+            LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
+                   (uint32_t)k1, (uint32_t)k, n, with_bound ? 0 : 1, c->sel, cand_total, cand_count, c->hist);
+            return DDEF_OK;
+        };
+        rc = record(bounded, 1);
         if (rc) return rc;
-        LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
-               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
-        LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
-               c->span_sum, c->nspans);
-        LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
-               (uint32_t)k1, (uint32_t)k, n, c->sel, cand_total, c->hist);
+        if (bounded) {
+            // the device says whether every worker caught enough (one small copy per iteration)
+            std::vector<SelState> st(n);
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            HIP_TRY(c, hipMemcpy(st.data(), c->sel, sizeof(SelState) * n, hipMemcpyDeviceToHost));
+            bool again = false;
+            for (const SelState& q : st) again |= q.active == 3u;
+            if (again) {
+                c->composed_retries += 1;
+                rc = record(false, 0);
+                if (rc) return rc;
+            }
+        }
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
                c->sorted_idx, c->sorted_val, c->cap, (float*)nullptr, (uint64_t)0);
@@ -818,7 +858,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         rc = enqueue_randk_mark(c, k);
         if (rc) return rc;
         LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 1,
-               c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+               1, (const uint32_t*)nullptr, c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_randk, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
@@ -1283,7 +1323,7 @@ int ddef_full_select_count(ddef_ctx* c, uint64_t* count) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     std::vector<uint32_t> fell_back(c->n, 0u);
     HIP_TRY(c, hipMemcpy(fell_back.data(), c->filt + 2 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
-    uint64_t total = c->full_selects;
+    uint64_t total = c->full_selects + c->composed_retries * c->n;
     for (uint32_t v : fell_back) total += v;
     *count = total;
     return DDEF_OK;
@@ -1305,6 +1345,10 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
             if (c->opt_fuse) return drop_prefetch(c);
             return DDEF_OK;
         case DDEF_OPT_GRAPH: c->opt_graph = value != 0; return DDEF_OK;
+        case DDEF_OPT_COMPOSED_BOUND:
+            if (value < 0 || value > 2) return DDEF_EINVAL;
+            c->opt_composed_bound = value;
+            return DDEF_OK;
         case DDEF_OPT_RANDK_BUCKET_PERCENT:
             if (value < 0 || value > 400) return DDEF_EINVAL;
             c->opt_bucket_percent = value;

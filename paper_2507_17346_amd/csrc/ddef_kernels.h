@@ -82,13 +82,15 @@ __global__ void k_randk_bin(uint32_t* bucket, uint64_t bucket_ld, uint32_t bucke
                             uint32_t k, uint32_t seed_lo, uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
 __global__ void k_randk_fill(const uint32_t* bucket, uint64_t bucket_ld, uint32_t bucket_cap, uint32_t* gcount,
                              uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d);
-__global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, int zero_marked, uint32_t* bitmap,
+__global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, int zero_marked, int accumulate,
+                           const uint32_t* bound, uint32_t* bitmap,
                            uint64_t bitmap_ld, uint2* cand, uint64_t cap, uint32_t* cand_count,
                            uint32_t* overflow, uint2* tab, uint32_t ngroups, uint32_t* nonfinite);
 __global__ void k_tab_decide_randk(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k,
                                    SelState* sel, uint32_t* cand_total, uint32_t* cand_count);
 __global__ void k_tab_decide_composed(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k1, uint32_t k,
-                                      uint32_t n, SelState* sel, uint32_t* cand_total, uint32_t* hist);
+                                      uint32_t n, int exact, SelState* sel, uint32_t* cand_total, uint32_t* cand_count,
+                                      uint32_t* hist);
 __global__ void k_quantize4(const uint32_t* msg_idx, float* msg_val, uint64_t msg_ld, uint32_t k, const SelState* sel,
                             float* e, uint64_t ld, uint8_t* codes, uint64_t codes_ld, float* steps, uint64_t steps_ld);
 __global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);

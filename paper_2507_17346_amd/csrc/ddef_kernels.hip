@@ -590,9 +590,13 @@ __global__ __launch_bounds__(1024) void k_randk_fill(const uint32_t* __restrict_
 // grid (ld/256, n), one wave per block, as k_ef_filter.  Eight lanes share one bitmap word;
 // the first of them clears it after the group has read it, so the bitmap is all-zero again
 // when the pass is over.  zero_marked = 0 leaves the marked entries' values in e (the composed
-// compressor decides later which of them are sent).
+// compressor decides later which of them are sent).  With `bound` non-null only the marked entries
+// whose magnitude pattern is >= bound[w] are recorded (the composed compressor needs the largest of
+// the marked entries, not all of them).  accumulate = 0 takes p = e as it stands (a second pass
+// over a row that already holds e + lr*g) and stores nothing.
 __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const float* __restrict__ g,
                                                  uint64_t ld, uint32_t d, float lr, int zero_marked,
+                                                 int accumulate, const uint32_t* __restrict__ bound,
                                                  uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
                                                  uint2* __restrict__ cand, uint64_t cap,
                                                  uint32_t* __restrict__ cand_count,
@@ -607,30 +611,33 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
     if (j < d) {
         float* ep = e + (uint64_t)w * ld + j;
         const float4 ev = load_stream4(ep);
-        const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
-        pv[0] = ev.x + lr * gv.x;
-        pv[1] = ev.y + lr * gv.y;
-        pv[2] = ev.z + lr * gv.z;
-        pv[3] = ev.w + lr * gv.w;
-        float res[4];
+        if (accumulate) {
+            const float4 gv = load_stream4(g + (uint64_t)w * ld + j);
+            pv[0] = ev.x + lr * gv.x;
+            pv[1] = ev.y + lr * gv.y;
+            pv[2] = ev.z + lr * gv.z;
+            pv[3] = ev.w + lr * gv.w;
+            float res[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) res[c] = (zero_marked && ((bitsel >> c) & 1u)) ? 0.0f : pv[c];
-        store_stream4(ep, res);
+            for (int c = 0; c < 4; ++c) res[c] = (zero_marked && ((bitsel >> c) & 1u)) ? 0.0f : pv[c];
+            store_stream4(ep, res);
+        } else {
+            pv[0] = ev.x; pv[1] = ev.y; pv[2] = ev.z; pv[3] = ev.w;
+        }
     }
     if (note_nonfinite(pv) && lane == 0) nonfinite[w] = 1u;
-    const bool any = bitsel != 0u;
-    uint32_t first = 0, total = 0;
-    if (__ballot(any)) {
-        if ((lane & 7u) == 0u) *word = 0u;                   // every lane of the group has read it
-        uint32_t below = 0;
-        bool f[4];
+    const uint32_t L = bound ? bound[w] : 0u;
+    if (__ballot(bitsel != 0u) && (lane & 7u) == 0u) *word = 0u;   // every lane of the group has read it
+    bool f[4];
+    uint32_t first = 0, total = 0, below = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            f[c] = (bitsel >> c) & 1u;
-            const uint64_t m = __ballot(f[c]);
-            below += mask_rank(m);
-            total += (uint32_t)__popcll(m);
-        }
+    for (int c = 0; c < 4; ++c) {
+        f[c] = ((bitsel >> c) & 1u) && mag_key(pv[c]) >= L;
+        const uint64_t m = __ballot(f[c]);
+        below += mask_rank(m);
+        total += (uint32_t)__popcll(m);
+    }
+    if (total != 0u) {                                       // wave-uniform
         const uint32_t sub = grp & (kSubs - 1u);
         const uint32_t sub_cap = (uint32_t)(cap / kSubs);
         uint32_t got = 0;
@@ -638,6 +645,7 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
         got = __shfl(got, 0, 64);
         if (got + total > sub_cap) {
             if (lane == 0) overflow[w] = 1u;
+            total = 0;
         } else {
             first = sub * sub_cap + got;
             uint2* cw = cand + (uint64_t)w * cap;
@@ -767,13 +775,18 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 // those entries in coordinate order for rank k, as it does on a filter's candidates, and the
 // message it writes is coded below.
 //
-// One block per worker, after k_tab_sum: span sums -> span offsets; the runs must hold exactly
-// k1 entries (active = 2 flags a slot overflow); starts the selection of the k largest of them.
+// One block per worker, after k_tab_sum: span sums -> span offsets, then the selection of the k
+// largest recorded entries starts.  exact = 1: every kept coordinate was recorded, the runs must
+// hold exactly k1 entries (active = 2 flags a slot overflow).  exact = 0: only the kept entries
+// above a bound were recorded, which is enough when there are at least k of them; otherwise
+// active = 3 asks the host to run the pass again without the bound.  Leaves the slot counters
+// and the overflow flag cleared.
 __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restrict__ span_sum, uint32_t nspans,
                                                              uint32_t* __restrict__ overflow, uint32_t k1,
-                                                             uint32_t k, uint32_t n,
+                                                             uint32_t k, uint32_t n, int exact,
                                                              SelState* __restrict__ sel,
                                                              uint32_t* __restrict__ cand_total,
+                                                             uint32_t* __restrict__ cand_count,
                                                              uint32_t* __restrict__ hist) {
     __shared__ uint32_t lds[5];
     const uint32_t w = blockIdx.x;
@@ -787,13 +800,16 @@ __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restric
         if (sp < nspans) sw[sp] = at;
         carry += total;
     }
-    const bool fine = overflow[w] == 0u && carry == k1;
+    const bool fine = overflow[w] == 0u && (exact ? carry == k1 : carry >= k);
+    __syncthreads();                            // every thread has read the flag
     if (threadIdx.x == 0) {
         cand_total[w] = fine ? carry : 0u;
-        sel[w].active = fine ? 0u : 2u;
+        sel[w].active = fine ? 0u : (exact ? 2u : 3u);
         sel[w].zero_used = 0xffffffffu;         // nothing was cleared ahead of time
         sel[w].seen = carry;
+        overflow[w] = 0u;
     }
+    for (uint32_t q = threadIdx.x; q < kSubs; q += blockDim.x) cand_count[(w * kSubs + q) * kSubStride] = 0u;
     begin_selection(sel, w, n, k, k, fine ? carry : 0u, hist);
 }
 

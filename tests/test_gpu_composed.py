@@ -151,6 +151,21 @@ def test_composed_under_the_library_options(ddef, oracle_mod, option):
     g.close()
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_bounded_recording_and_its_repeat(ddef, oracle_mod, mode):
+    # 0: every kept entry is recorded; 1: only those above the sampled bound; 2: the bound is placed
+    # too high on purpose, every iteration is repeated without it.  Same results in all three.
+    w = workloads.replace(workloads.get("C3", d=400_003, n=3), seed=515)
+    g, o = pair(ddef, oracle_mod, w, 1, 0.2)
+    g.set_option(ddef.OPT_COMPOSED_BOUND, mode)
+    for t in range(6):
+        g.step(0.1, w.lr); o.step(0.1, w.lr)
+        assert_same(g, o, w.n, (mode, t))
+    repeats = g.full_select_count()
+    assert repeats == (5 * w.n if mode == 2 else 0)          # five non-empty iterations
+    g.close()
+
+
 def test_argument_and_state_checks(ddef):
     c = ddef.Context(1000, 1, 0)
     one = np.ones(1000, dtype=F32)
