@@ -117,7 +117,8 @@ int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_
  * step = (largest magnitude in the block) / 7, code = value / step rounded to the nearest integer
  * (halves to even) inside [-7, 7], all codes 0 where step is 0.  Delta holds what the receiver
  * decodes, code * step (that is what ddef_get_message returns and the aggregation sums), so
- * e' = p - Delta keeps the coding error with everything not sent.  Ring form only.
+ * e' = p - Delta keeps the coding error with everything not sent.  Ring form only.  Under this
+ * compressor ddef_ef_compress waits for the stream once per iteration (DDEF_OPT_COMPOSED_BOUND).
  * Only between iterations. */
 int ddef_set_compressor(ddef_ctx* ctx, int kind);
 /* Share of the coordinates the Random-k stage of the composed compressor keeps, in (0, 1].
