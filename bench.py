@@ -143,7 +143,7 @@ def host_description():
     return {"cpu_model": model, "logical_cpus": os.cpu_count() or 1, "usable_cpus": usable}
 
 
-def describe(w, sched):
+def describe(w, sched, k_of=None):
     noise = {0: "no noise", 1: f"Gaussian noise x{w.noise_scale}", 2: f"Student-t3 noise x{w.noise_scale}"}[w.noise_kind]
     if w.adaptive_period > 0:
         pairs = sorted({sched(t) for t in range(0, w.steps, w.adaptive_period)})
@@ -151,7 +151,7 @@ def describe(w, sched):
     elif len(w.deltas) > 1:
         ratio = f"delta swept over {list(w.deltas)} in segments of {w.steps} iterations, tau={w.tau}"
     else:
-        ratio = f"delta={w.deltas[0]} (k={w.k()}), tau={w.tau}"
+        ratio = f"delta={w.deltas[0]} (k={k_of(w.deltas[0]) if k_of else w.k()}), tau={w.tau}"
     return f"{w.name}: d={w.d} fp32, n={w.n} workers, {ratio}, lr={w.lr}, {noise}, seed {w.seed}"
 
 
@@ -213,7 +213,7 @@ def main():
         w = workloads.replace(w, deltas=(args.delta,), adaptive_period=0, tau=w.tau if w.adaptive_period == 0 else 8)
     sched = make_schedule(w, binding, workloads)
     delta = sched(0)[1]
-    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (k={w.k(delta)}) tau={sched(0)[0]} lr={w.lr} "
+    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (Top-k of the whole row: k={w.k(delta)}) tau={sched(0)[0]} lr={w.lr} "
         f"noise kind {w.noise_kind} scale {w.noise_scale} seed {w.seed}")
     t0 = time.perf_counter()
     lam, xstar, x0 = workloads.make_problem(w)
@@ -394,8 +394,8 @@ def main():
         "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": describe(w, sched),
-                   "d": w.d, "n": w.n, "k": w.k(sched(ctx.t)[1]), "tau": sched(ctx.t)[0],
+        "config": {"workload": describe(w, sched, lambda dl: round(sent_ratio(dl) * w.d)),
+                   "d": w.d, "n": w.n, "k": round(sent_ratio(sched(ctx.t)[1]) * w.d), "tau": sched(ctx.t)[0],
                    "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
