@@ -166,6 +166,36 @@ def test_bounded_recording_and_its_repeat(ddef, oracle_mod, mode):
     g.close()
 
 
+def test_seeded_sweep_of_small_shapes(ddef, oracle_mod):
+    """Forty seeded configurations with d from 1 to a few tens of thousands, the two ratios, tau and
+    the compressor changing in mid-run (Random-k and the composed one share the marking pass)."""
+    rng = np.random.default_rng(20250718)
+    for case in range(40):
+        d = int(rng.choice([1, 2, 5, 63, 64, 255, 257, 1023, 1025, 4096, 4097, 9000, 20011, 70001]))
+        n = int(rng.integers(1, 5))
+        tau_max = int(rng.integers(0, 3))
+        kind = int(rng.integers(0, 3))
+        w = workloads.replace(workloads.get("C1", d=d, n=n), seed=3000 + case, noise_kind=kind,
+                              noise_scale=float(rng.choice([0.05, 0.5])) if kind else 0.0)
+        lam, xstar, x0 = workloads.make_problem(w)
+        g = ddef.Context(d, n, tau_max)
+        o = oracle_mod.Oracle(d, n, tau_max, threads=2)
+        for h in (g, o):
+            h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        what = dict(case=case, d=d, n=n, tau_max=tau_max, kind=kind)
+        for t in range(int(rng.integers(3, 8))):
+            tau = int(rng.integers(0, tau_max + 1))
+            comp = int(rng.choice([2, 2, 2, 1, 0]))
+            rho = float(rng.choice([0.01, 0.2, 0.5, 1.0]))
+            delta = float(rng.choice([0.003, 0.05, 0.1, 0.5, 1.0]))
+            for h in (g, o):
+                h.set_tau(tau); h.set_compressor(comp); h.set_composed(rho)
+            g.step(delta, 0.05); o.step(delta, 0.05)
+            assert_same(g, o, n, (what, t, comp, rho, delta), codes=comp == 2)
+        g.close()
+        o.close()
+
+
 def test_argument_and_state_checks(ddef):
     c = ddef.Context(1000, 1, 0)
     one = np.ones(1000, dtype=F32)
