@@ -243,12 +243,24 @@ uint64_t candidate_capacity(const ddef_ctx* c, uint64_t k, uint64_t kb) {
     return ((want + 4095u) & ~(uint64_t)4095u) + 256u * kSubs;
 }
 
-// candidate target: slack/16 times k for sparse messages (k/d <= 1/32), whose bound follows the
-// trend of the last thresholds; k + k/24 for dense ones, whose bound comes from a fine sample of this
-// very p in every iteration (some 65 000 sample entries above it: the count caught misses the
-// target by about 0.4 %, a tenth of the margin)
+// Whether the filter bound of a selection of k is placed from a fine sample of this very p in every
+// iteration instead of following the trend of the last thresholds.  Sampling costs a fixed tenth
+// of a millisecond or so; a tighter bound saves candidate work in proportion to n * k.  It pays for
+// dense messages (k/d > 1/32) and wherever the workers' messages together hold 2^23 entries or more.
+bool samples_every_iteration(const ddef_ctx* c, uint64_t k) {
+    // (sampling reads the gradient from memory, so with the gradient fused into the accumulate pass
+    // only dense messages, where it is indispensable, get it)
+    return k * 32u > c->d || (!c->opt_fuse && k * (uint64_t)c->n >= ((uint64_t)1 << 23));
+}
+
+// candidate target: slack/16 times k where the bound follows the trend of the last thresholds;
+// where it comes from a fine sample (up to 65 000 sample entries above it, the sample capped at 2^20
+// entries per worker), k + k/24 for dense messages (the count caught misses the target by about
+// 0.5 %) and k + k/16 for sparse ones (fewer sample entries above the bound: about 1 %)
 uint64_t candidate_target(const ddef_ctx* c, uint64_t k) {
-    uint64_t kb = (k * 32u <= c->d) ? k * (uint64_t)c->opt_slack_x16 / 16u : k + k / 24u;
+    uint64_t kb = k * (uint64_t)c->opt_slack_x16 / 16u;
+    if (k * 32u > c->d) kb = k + k / 24u;
+    else if (samples_every_iteration(c, k)) kb = k + k / 16u;
     if (kb < k) kb = k;
     if (kb > c->d) kb = c->d;
     return kb;
@@ -881,7 +893,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     // expected and the true threshold each cost a scattered store in the compaction, many enough
     // to outweigh the sampling by far, and the trend of noisy thresholds misses by more.
     const bool can_filter = !c->opt_force_full && 2 * kb <= c->d;
-    const bool dense = k * 32u > c->d;
+    const bool dense = samples_every_iteration(c, k);
     if (can_filter && (dense || !c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
         rc = bound_from_sample(c, k, kb, lr, dense ? 65536u : 256u);
         if (rc) return rc;
@@ -997,7 +1009,7 @@ int ddef_step(ddef_ctx* c, double delta, float lr) {
     // no per-launch events, no second stream.
     const bool steady = c->opt_graph && !c->queue_form && c->compressor == DDEF_COMPRESSOR_TOPK &&
                         !c->profiling && !c->opt_prefetch && c->t >= c->tau && c->have_bound && c->bound_k == k &&
-                        c->sel_k == k && c->sel_run >= 2u && k * 32u <= c->d &&
+                        c->sel_k == k && c->sel_run >= 2u && !samples_every_iteration(c, k) &&
                         k <= c->msg_ld && candidate_capacity(c, k, kb) <= c->cap;
     if (!steady) return step_eager(c, delta, lr);
     DeviceGuard guard(c->device);
