@@ -227,3 +227,46 @@ def test_coordinates_beyond_2_to_31(ddef, oracle_mod):
         x_cur = c.get_model()
     assert c.full_select_count() < 5          # the candidate filter carried the later selections
     c.close()
+
+
+def test_random_k_marking_beyond_2_to_29(ddef, oracle_mod):
+    """d = 6e8: the kept coordinates of Random-k are sorted into regions of more than one on-chip
+    tile each before their bits are set.  The coordinates sent must be the oracle's subset, the
+    values what was accumulated there; the composed compressor on top must send an ordered part
+    of that subset."""
+    d, n, lr = 600_000_000, 1, 0.05
+    w = workloads.replace(workloads.get("C1", d=d, n=n), seed=77)
+    lam, xstar, x0 = workloads.make_problem(w)
+    c = ddef.Context(d, n, 1)
+    c.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    c.set_tau(0)
+    k1 = oracle_mod.k_from_delta(0.2, d)
+    for comp, delta in ((1, 0.2), (2, 0.1)):
+        c.set_compressor(comp)
+        c.set_composed(0.2)
+        t = c.t
+        e_before = c.get_error(0)
+        c.grad()
+        grad = c.get_grad(0)
+        c.ef_compress(delta, lr)
+        idx, val = c.get_message(0)
+        kept = oracle_mod.randk_indices(w.seed, t, 0, d, k1)
+        if comp == 1:
+            assert np.array_equal(idx, kept)
+            assert np.array_equal(bits(val), bits(e_before[idx] + F32(lr) * grad[idx]))
+            assert np.all(bits(c.get_error(0)[idx]) == 0)
+        else:
+            assert len(idx) == oracle_mod.k_from_delta(delta, k1)
+            assert np.all(np.diff(idx.astype(np.int64)) > 0)
+            assert np.array_equal(kept[np.searchsorted(kept, idx)], idx)
+            p = e_before + F32(lr) * grad
+            T, r = c.get_threshold(0)
+            keys = bits(p[idx]) & np.uint32(0x7FFFFFFF)
+            assert int(keys.min()) == T and int((keys == T).sum()) == r
+            unsent = np.setdiff1d(kept, idx, assume_unique=True)
+            assert int((bits(p[unsent]) & np.uint32(0x7FFFFFFF)).max()) <= T
+        del e_before, grad
+        c.aggregate()
+        c.apply_delayed(lr)
+    assert c.full_select_count() == 0
+    c.close()
