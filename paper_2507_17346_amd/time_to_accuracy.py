@@ -102,12 +102,14 @@ def run(w, s: Strategy, net: Network, target_ratio: float, max_iterations: int, 
 
 
 def run_adaptive(w, nets: List[Network], period: int, adaptive: bool, target_ratio: float,
-                 max_iterations: int, tau_max: int = 16) -> Outcome:
+                 max_iterations: int, tau_max: int = 16, lut: Optional["binding.DecoLut"] = None) -> Outcome:
     """A network that changes every `period` iterations (nets[p % len(nets)] holds during period p).
     adaptive = True is DeCo-SGD (Algorithm 2): (tau, delta) re-chosen by Algorithm 3 at the start of
     every period from that period's network.  adaptive = False keeps the choice made for the
     first period.  Seconds accumulate period by period with each period's iteration time under
-    the (tau, delta) in force; the objective is looked at once per period."""
+    the (tau, delta) in force; the objective is looked at once per period.  With `lut` (the look-up
+    table of Section 4.5, built for one latency) the choice comes from the table entry nearest to the
+    period's bandwidth instead of a run of Algorithm 3."""
     lam, xstar, x0 = workloads.make_problem(w)
     ctx = binding.Context(w.d, w.n, tau_max)
     try:
@@ -119,7 +121,10 @@ def run_adaptive(w, nets: List[Network], period: int, adaptive: bool, target_rat
         while t < max_iterations and reached is None:
             net = nets[p % len(nets)]
             if adaptive or first is None:
-                tau, delta = binding.deco(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
+                if lut is not None:
+                    tau, delta, _ = lut.query(net.a_bps)
+                else:
+                    tau, delta = binding.deco(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
                 first = Strategy("DeCo-SGD" if adaptive else "DeCo, first period's choice kept",
                                  int(min(tau_max, tau)), float(delta))
             ctx.set_tau(first.tau)

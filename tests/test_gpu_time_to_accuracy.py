@@ -85,3 +85,21 @@ def test_adapting_to_a_changing_network_beats_a_fixed_choice(ddef):
     assert adaptive.seconds < fixed.seconds
     # the adaptive run pays about T_comp per iteration throughout
     assert adaptive.seconds / adaptive.iterations == pytest.approx(0.02, rel=0.25)
+
+
+def test_the_lookup_table_serves_the_adaptive_run(ddef):
+    """Section 4.5: (tau, delta) from the nearest of 20 precomputed bandwidths instead of Algorithm 3
+    at run time.  Bandwidths between two sample points get a neighbouring choice; the run stays
+    close to the one that solves Algorithm 3 every period."""
+    w = workloads.get("C1", d=200_000, n=4)
+    v_g = 32.0 * w.d
+    nets = [tta.Network(v_g, a, 0.1, 0.02) for a in (180e6, 12e6, 60e6, 25e6)]
+    lut = ddef.DecoLut(v_g, 10e6, 200e6, 20, 0.1, 0.02)
+    direct = tta.run_adaptive(w, nets, 50, True, 0.02, 20000)
+    table = tta.run_adaptive(w, nets, 50, True, 0.02, 20000, lut=lut)
+    lut.close()
+    assert direct.iterations is not None and table.iterations is not None
+    print(f"Algorithm 3 every period: {direct.iterations} iterations, {direct.seconds:.2f} s; "
+          f"look-up table: {table.iterations} iterations, {table.seconds:.2f} s")
+    assert table.seconds == pytest.approx(direct.seconds, rel=0.25)
+    assert table.seconds / table.iterations < 0.03
