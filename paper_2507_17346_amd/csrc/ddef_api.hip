@@ -248,9 +248,7 @@ uint64_t candidate_capacity(const ddef_ctx* c, uint64_t k, uint64_t kb) {
 // of a millisecond or so; a tighter bound saves candidate work in proportion to n * k.  It pays for
 // dense messages (k/d > 1/32) and wherever the workers' messages together hold 2^23 entries or more.
 bool samples_every_iteration(const ddef_ctx* c, uint64_t k) {
-    // (sampling reads the gradient from memory, so with the gradient fused into the accumulate pass
-    // only dense messages, where it is indispensable, get it)
-    return k * 32u > c->d || (!c->opt_fuse && k * (uint64_t)c->n >= ((uint64_t)1 << 23));
+    return k * 32u > c->d || k * (uint64_t)c->n >= ((uint64_t)1 << 23);
 }
 
 // candidate target: slack/16 times k where the bound follows the trend of the last thresholds;
@@ -473,10 +471,17 @@ int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t a
         HIP_TRY(c, hipMalloc((void**)&c->sample_total, (size_t)n * 4u));
         drop_graph(c);
     }
-    materialize_grad(c);                      // the sample reads g from memory
-    LAUNCH(c, SL_SAMPLE, k_sample_p, dim3((uint32_t)((count + 255u) / 256u), n), dim3(256), (const float*)c->e,
-           (const float*)c->g, c->ld, (uint32_t)c->d, lr, (uint32_t)stride, (uint32_t)count, c->sample,
-           c->sample_ld);
+    // a gradient that lives only in the fused accumulate pass is generated for the sampled coordinates
+    const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
+    if (c->grad_pending) {
+        LAUNCH(c, SL_SAMPLE, k_sample_p<true>, dim3((uint32_t)((count + 255u) / 256u), n), dim3(256),
+               (const float*)c->e, (const float*)c->g, src, c->ld, (uint32_t)c->d, lr, (uint32_t)stride,
+               (uint32_t)count, c->sample, c->sample_ld);
+    } else {
+        LAUNCH(c, SL_SAMPLE, k_sample_p<false>, dim3((uint32_t)((count + 255u) / 256u), n), dim3(256),
+               (const float*)c->e, (const float*)c->g, src, c->ld, (uint32_t)c->d, lr, (uint32_t)stride,
+               (uint32_t)count, c->sample, c->sample_ld);
+    }
     LAUNCH(c, SL_SAMPLE, k_sample_begin, dim3(n), dim3(256), c->sel, n, (uint32_t)k_s, (uint32_t)kb_s,
            (uint32_t)count, c->sample_total, c->hist);
     const SelViews vs{c->e, c->ld, (uint32_t)c->d, c->sample, (const uint32_t*)nullptr, c->sample_ld,

@@ -100,7 +100,9 @@ __global__ void k_chunk_count(SelViews vs, const SelState* sel, uint32_t* cnt_gt
 __global__ void k_chunk_scan(SelViews vs, SelState* sel, uint32_t* cnt_gt, uint32_t* cnt_eq,
                              uint32_t stride, uint32_t k, uint32_t kb, uint32_t* bound, uint32_t* zero_at,
                              uint32_t* cand_count, uint32_t* overflow);
-__global__ void k_sample_p(const float* e, const float* g, uint64_t ld, uint32_t d, float lr, uint32_t stride, uint32_t count,
+template <bool kFusedGrad>
+__global__ void k_sample_p(const float* e, const float* g, GradSource src, uint64_t ld, uint32_t d, float lr, uint32_t stride,
+                           uint32_t count,
                            float* sample, uint64_t sample_ld);
 __global__ void k_sample_begin(SelState* sel, uint32_t n, uint32_t k_s, uint32_t kb_s, uint32_t count,
                                uint32_t* sample_total, uint32_t* hist);

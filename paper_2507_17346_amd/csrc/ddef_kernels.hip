@@ -1128,10 +1128,14 @@ __device__ __forceinline__ void next_bound(SelState* sel, uint32_t w, uint32_t k
 // the candidate target for the whole row (the count above the bound then misses its target by
 // about 1 / sqrt(kb / stride), far inside the usable window [k, 3 kb]).  As always the bound only
 // decides which search runs; the selection that follows is exact.
+// With kFusedGrad the gradient is not read from g but generated for the sampled coordinates (the
+// arithmetic of k_grad), for iterations whose gradient never reaches memory.
+template <bool kFusedGrad>
 __global__ __launch_bounds__(256) void k_sample_p(const float* __restrict__ e, const float* __restrict__ g,
-                                                  uint64_t ld, uint32_t d, float lr, uint32_t stride,
-                                                  uint32_t count, float* __restrict__ sample,
-                                                  uint64_t sample_ld) {
+                                                  GradSource src, uint64_t ld, uint32_t d, float lr,
+                                                  uint32_t stride, uint32_t count,
+                                                  float* __restrict__ sample, uint64_t sample_ld) {
+    if (kFusedGrad) resolve_iteration(src);
     const uint32_t w = blockIdx.y;
     const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= count) return;
@@ -1139,10 +1143,23 @@ __global__ __launch_bounds__(256) void k_sample_p(const float* __restrict__ e, c
     float v = 0.0f;                            // past the end of the row: ranks last
     if (coord < (uint64_t)d) {
         const uint64_t at = (uint64_t)w * ld + coord;
-        v = e[at] + lr * g[at];
+        float gj;
+        if (kFusedGrad) {
+            const uint32_t j = (uint32_t)coord & ~3u;          // the quad the draw is made for
+            float gq[4];
+            grad_quad(src, grad_shared4(src, j), w, j, d, gq);
+            gj = gq[(uint32_t)coord & 3u];
+        } else {
+            gj = g[at];
+        }
+        v = e[at] + lr * gj;
     }
     sample[(uint64_t)w * sample_ld + s] = v;
 }
+template __global__ void k_sample_p<false>(const float*, const float*, GradSource, uint64_t, uint32_t, float,
+                                           uint32_t, uint32_t, float*, uint64_t);
+template __global__ void k_sample_p<true>(const float*, const float*, GradSource, uint64_t, uint32_t, float,
+                                          uint32_t, uint32_t, float*, uint64_t);
 
 // One block per worker: the sample becomes the worker's view and the selection starts.
 __global__ __launch_bounds__(256) void k_sample_begin(SelState* __restrict__ sel, uint32_t n, uint32_t k_s,

@@ -424,7 +424,9 @@ def test_prefetched_gradient_gives_identical_trajectories(ddef, oracle_mod, tau)
 
 # ---- gradient generated inside the accumulate pass: same results --------------------------------
 @pytest.mark.parametrize("name,d,n,tau,delta", [("C3", 200_001, 4, 2, 0.002), ("C1", 50_000, 3, 0, 0.01),
-                                                ("C2", 150_000, 8, 1, 0.01)])
+                                                ("C2", 150_000, 8, 1, 0.01),
+                                                ("C3", 300_001, 3, 1, 0.1),       # sampled bound every iteration
+                                                ("C1", 70_000, 2, 3, 0.4)])
 def test_fused_gradient_gives_identical_trajectories(ddef, oracle_mod, name, d, n, tau, delta):
     w = workloads.get(name, d=d, n=n)
     lam, xstar, x0 = workloads.make_problem(w)
