@@ -114,3 +114,31 @@ def test_header_is_plain_c(tmp_path):
     exe = tmp_path / "use_all"
     subprocess.check_call([gcc, "-std=gnu99", "-I", os.path.join(root, "include"), str(src), lib, "-o", str(exe),
                            "-Wl,-rpath," + os.path.dirname(lib), "-Wl,--allow-shlib-undefined"])
+
+
+def test_product_path_never_reaches_for_the_oracle():
+    """Nothing in the package, nor the bench's timed path, imports the CPU oracle: a missing or
+    unloadable library must surface as an error, not as a silent CPU result."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2507_17346_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert not re.search(r"^\s*(import|from)\s+oracle\b", text, re.M), name
+    # bench.py touches the oracle in one place only: the cpu_baseline leg
+    bench = open(os.path.join(root, "bench.py")).read()
+    uses = [m.start() for m in re.finditer(r"^\s*(import|from)\s+oracle\b", bench, re.M)]
+    assert len(uses) == 1
+    assert bench.rfind("def cpu_baseline", 0, uses[0]) > bench.rfind("\ndef main", 0, uses[0])
+
+
+def test_a_missing_library_is_an_error(tmp_path, monkeypatch):
+    from paper_2507_17346_amd import binding, build
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(build, "LIB", str(tmp_path / "libddef_missing.so"))
+    monkeypatch.setattr(build, "build_library", lambda *a, **k: (_ for _ in ()).throw(RuntimeError("no compiler here")))
+    with pytest.raises((RuntimeError, OSError)):
+        binding.load()
+    with pytest.raises((RuntimeError, OSError)):
+        binding.k_from_delta(0.5, 10)
