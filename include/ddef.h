@@ -71,8 +71,10 @@ int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out);
  * snapshot ring.  The four calls keep their order and meaning, except that in iteration t
  *   ddef_grad            takes the gradient at the current x_t (no iteration is empty) and
  *                        draws the noise keyed by t + tau, the iteration at which the message
- *                        is applied, so that a constant tau gives bit for bit the iterates of
- *                        the ring form;
+ *                        is due, so that a constant tau gives bit for bit the iterates of
+ *                        the ring form.  Keys never repeat: when tau falls and t + tau names an
+ *                        iteration already used, the key is the last one plus one,
+ *                        key_t = max(t + tau_t, key_{t-1} + 1);
  *   ddef_ef_compress     queues the messages Delta_{i,t} (these are what ddef_get_message
  *                        returns);
  *   ddef_aggregate       sums the messages Delta_{i,t-tau} sent tau iterations earlier; U = 0

@@ -335,10 +335,11 @@ void for_each_worker(Oracle* o, F fn) {
 
 constexpr uint64_t kHeterogeneityKey = 0xfffffffffffffffeull;
 
-void grad_worker(Oracle* o, uint32_t i) {
+// Worker i's gradient at the coordinates [j0, j1) (every coordinate is computed on its own).
+void grad_worker(Oracle* o, uint32_t i, uint64_t j0, uint64_t j1) {
     const std::vector<float>& xs = o->slot(o->t - o->tau);
     std::vector<float>& g = o->g[i];
-    for (uint64_t j = 0; j < o->d; ++j) {
+    for (uint64_t j = j0; j < j1; ++j) {
         // heterogeneous local objectives (Assumption 3): f_i has its own optimum, shifted from x*
         // by zeta times a fixed standard normal vector u_i (drawn under a step key no iteration uses)
         float optimum = o->xstar[j];
@@ -488,7 +489,19 @@ void oracle_grad(void* h) {
     Oracle* o = (Oracle*)h;
     o->step_is_noop = o->t < o->tau;
     if (o->step_is_noop) return;
-    for_each_worker(o, [o](uint32_t i) { grad_worker(o, i); });
+    if (o->threads > (int)o->n) {
+        // more threads than workers (one worker of a very long vector): the threads share each
+        // worker's coordinates in contiguous ranges instead
+        const uint64_t nt = (uint64_t)o->threads, per = (o->d + nt - 1) / nt;
+        for (uint32_t i = 0; i < o->n; ++i) {
+            std::vector<std::thread> pool;
+            for (uint64_t j0 = 0; j0 < o->d; j0 += per)
+                pool.emplace_back([=]() { grad_worker(o, i, j0, std::min(o->d, j0 + per)); });
+            for (auto& th : pool) th.join();
+        }
+        return;
+    }
+    for_each_worker(o, [o](uint32_t i) { grad_worker(o, i, 0, o->d); });
 }
 // Replace worker i's gradient by a given vector (unit tests); marks the step as real.
 void oracle_load_grad(void* h, uint32_t worker, const float* g) {
@@ -650,6 +663,11 @@ void oracle_queue_run(uint64_t d, uint32_t n, uint32_t tau, uint64_t T, double d
 // inspected: state = x_u, e_i (already advanced to time u), and the messages sent so far.
 struct QueueOracle {
     uint64_t d = 0, u = 0, seed = 0;
+    // Noise key of the gradient taken at iteration u: the iteration u + tau_u at which its message
+    // is due, moved up where needed so that the keys increase strictly (a falling tau would
+    // otherwise name the same iteration twice and draw the same noise twice):
+    // key_u = max(u + tau_u, key_{u-1} + 1).  For a constant tau this is u + tau.
+    uint64_t next_key_floor = 0;
     uint32_t n = 0, tau = 0;
     int noise_kind = 0;
     float noise_scale = 0.0f;
@@ -680,11 +698,14 @@ void oracle_queue_set_problem(void* h, const float* lambda, const float* xstar, 
     for (auto& e : q->e) std::fill(e.begin(), e.end(), 0.0f);
     q->sent_idx.clear(); q->sent_val.clear();
     q->seed = seed; q->noise_kind = noise_kind; q->noise_scale = noise_scale; q->u = 0;
+    q->next_key_floor = 0;
 }
 void oracle_queue_step(void* h, double delta, float lr) {
     QueueOracle* q = (QueueOracle*)h;
     const uint64_t d = q->d, k = k_from_delta(delta, d), u = q->u;
     q->sent_idx.emplace_back(q->n); q->sent_val.emplace_back(q->n);
+    const uint64_t key = std::max(u + q->tau, q->next_key_floor);
+    q->next_key_floor = key + 1;
     std::vector<float> p(d), dense(d);
     for (uint32_t i = 0; i < q->n; ++i) {                          // worker side, at the current x_u
         for (uint64_t j = 0; j < d; ++j) {
@@ -692,7 +713,7 @@ void oracle_queue_step(void* h, double delta, float lr) {
             if (q->zeta != 0.0f) optimum = q->xstar[j] + q->zeta * noise_z(q->seed, kHeterogeneityKey, i, (uint32_t)j, 1);
             float diff = q->x[j] - optimum;
             float mean = q->lambda[j] * diff;
-            float xi = q->noise_scale * noise_z(q->seed, u + q->tau, i, (uint32_t)j, q->noise_kind);
+            float xi = q->noise_scale * noise_z(q->seed, key, i, (uint32_t)j, q->noise_kind);
             float g = mean + xi;
             float scaled = lr * g;
             p[j] = q->e[i][j] + scaled;

@@ -140,9 +140,12 @@ struct ddef_ctx {
     uint32_t* slot_idx(uint32_t s) const { return msg_idx + (uint64_t)s * n * msg_ld; }
     float* slot_val(uint32_t s) const { return msg_val + (uint64_t)s * n * msg_ld; }
     // The gradient of the iteration in progress: ring form takes it at the snapshot x_{t-tau} with
-    // the noise of iteration t; queue form at the current x_t with the noise of the iteration at
-    // which its message will be applied, so that both forms draw the same noise for the same update.
-    uint64_t grad_key() const { return queue_form ? t + tau : t; }
+    // the noise of iteration t; queue form at the current x_t with the noise of the iteration
+    // t + tau at which its message is due, so that both forms draw the same noise for the same
+    // update under a constant tau.  A falling tau would name the same iteration twice, so the queue
+    // form's keys are kept strictly increasing: q_key = max(t + tau, last key + 1), fixed by ddef_grad.
+    uint64_t q_key = 0, q_key_floor = 0;
+    uint64_t grad_key() const { return queue_form ? q_key : t; }
     const float* grad_snapshot() const { return queue_form ? ring : slot(t - tau); }
 };
 
@@ -674,6 +677,7 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     drop_graph(c);
     c->seed = seed; c->noise_kind = noise_kind; c->noise_scale = noise_scale;
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
+    c->q_key = 0; c->q_key_floor = 0;
     c->full_selects = 0;
     c->composed_retries = 0;
     c->u_zero = true;
@@ -732,6 +736,10 @@ int ddef_grad(ddef_ctx* c) {
     if (!c->problem_set || c->phase != PH_IDLE) return DDEF_ESTATE;
     DeviceGuard guard(c->device);
     c->step_empty = !c->queue_form && c->t < c->tau;
+    if (c->queue_form) {
+        c->q_key = std::max(c->t + c->tau, c->q_key_floor);
+        c->q_key_floor = c->q_key + 1u;
+    }
     c->grad_pending = false;
     c->grad_stored = false;
     c->grad_live = !c->step_empty;
@@ -1379,3 +1387,4 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
 }
 
 }  // extern "C"
+

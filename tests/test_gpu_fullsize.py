@@ -1,11 +1,16 @@
 """GPU parity at the workloads' full sizes, in the launch configuration bench.py times.
 
 C2 and C3 are compared with the oracle element by element for every worker (the oracle needs a
-few seconds per iteration with one thread per worker).  C4 (d = 1.3e9, n*d > 2^32) is too large
-for the oracle to run whole: its selection is checked through properties that hold at any size
-(count, order, threshold dominance, tie rule, EF identity) and its gradients and error-feedback
-values on sampled coordinates that the oracle computes one by one.
+few seconds per iteration with one thread per worker).  C4 (d = 1.3e9, n*d > 2^32): the oracle's
+step runs whole for one worker (about a minute per iteration; all four would take four times the
+memory and no less time) over one iteration per delta of the sweep, and its message, threshold
+and error buffer are compared element by element; on top of that every watched worker's selection
+is checked through properties that hold at any size (count, order, threshold dominance, tie rule,
+EF identity) and gradients and error-feedback values on sampled coordinates that the oracle
+computes one by one.
 """
+import functools
+
 import numpy as np
 import pytest
 
@@ -114,14 +119,57 @@ def test_c5_full_size_across_a_change_of_tau_and_delta(ddef, oracle_mod):
     o.close()
 
 
-def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
+@functools.lru_cache(maxsize=1)
+def c4_problem():
     w = workloads.get("C4")
-    lam, xstar, x0 = workloads.make_problem(w)
+    return (w,) + tuple(workloads.make_problem(w))
+
+
+def test_c4_full_size_one_worker_against_the_oracle(ddef, oracle_mod):
+    """C4 at its real shape on the GPU (d = 1.3e9, n = 4, tau = 4) against the oracle's step for
+    worker 0, one iteration per delta of the sweep (0.01, 0.1, 0.001).  The oracle runs with one
+    worker: a worker's messages and error buffer depend on the others only through the snapshot its
+    gradient is taken at, and iterations tau .. 2 tau all take theirs at x_0 (the first update lands
+    in x_{tau+1}), whatever the number of workers.  So the oracle, given only the seeded inputs,
+    produces what worker 0 of the four must produce."""
+    w, lam, xstar, x0 = c4_problem()
+    g = ddef.Context(w.d, w.n, w.tau_max)
+    o = oracle_mod.Oracle(w.d, 1, w.tau_max, threads=16)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(w.tau)
+    schedule = {w.tau: 0.01, w.tau + 1: 0.1, w.tau + 2: 0.001}
+    for t in range(w.tau + 3):
+        delta = schedule.get(t, 0.01)
+        print(f"C4 vs oracle: iteration {t} delta {delta}", flush=True)
+        g.step(delta, w.lr)
+        o.step(delta, w.lr)
+        if t < w.tau:
+            continue
+        gi, gv = g.get_message(0)
+        oi, ov = o.get_message(0)
+        assert len(gi) == w.k(delta)
+        assert np.array_equal(gi, oi), ("C4 indices", t)
+        assert np.array_equal(bits(gv), bits(ov)), ("C4 values", t)
+        assert g.get_threshold(0) == o.get_threshold(0), ("C4 threshold", t)
+        del gi, gv, oi, ov
+        ge = g.get_error(0)
+        oe = o.get_error(0)
+        assert np.array_equal(bits(ge), bits(oe)), ("C4 error buffer", t)
+        del ge, oe
+    assert np.array_equal(bits(g.get_grad(0)), bits(o.get_grad(0)))
+    assert g.full_select_count() == 0          # every selection went through the sampled filter
+    g.close()
+    o.close()
+
+
+def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
+    w, lam, xstar, x0 = c4_problem()
     g = ddef.Context(w.d, w.n, w.tau_max)
     g.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
     g.set_tau(w.tau)
     # the workload sweeps delta; iterations tau .. 2*tau all take their gradient at x0
-    schedule = {w.tau: 0.001, w.tau + 1: 0.001, w.tau + 2: 0.001, w.tau + 3: 0.1, w.tau + 4: 0.1}
+    schedule = {w.tau: 0.001, w.tau + 1: 0.001, w.tau + 2: 0.001, w.tau + 3: 0.01, w.tau + 4: 0.1}
     rng = np.random.default_rng(17)
     sample = np.unique(np.concatenate([rng.integers(0, w.d, size=4000),
                                        [0, 1, w.d - 1, w.d - 2, 2 ** 30, 2 ** 30 + 1]]))
@@ -180,6 +228,7 @@ def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
     # both searches ran at this size: the whole-row one in the first real iteration only
     assert g.full_select_count() == w.n
     g.close()
+    c4_problem.cache_clear()
 
 
 def test_coordinates_beyond_2_to_31(ddef, oracle_mod):

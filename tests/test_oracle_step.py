@@ -282,6 +282,112 @@ def test_stepwise_queue_form(oracle_mod, tau, delta):
             assert np.array_equal(bits(q2.get_error(i)), bits(ring2.get_error(i)))
 
 
+def queue_noise_keys(taus):
+    """Noise key of the gradient taken at iteration u in the message-queue form: the iteration
+    u + tau_u at which its message is due, pushed up so that the keys never repeat."""
+    keys, floor = [], 0
+    for u, tau in enumerate(taus):
+        keys.append(max(u + tau, floor))
+        floor = keys[-1] + 1
+    return keys
+
+
+def topk_dense(p, k):
+    """Top-k of p as a dense vector, by a full stable sort: |v| descending on the bit pattern with
+    the sign cleared, lower index first among equals."""
+    keys = bits(p) & np.uint32(0x7FFFFFFF)
+    order = np.lexsort((np.arange(len(p)), -keys.astype(np.int64)))
+    comp = np.zeros(len(p), dtype=F32)
+    comp[order[:k]] = p[order[:k]]
+    return comp, np.sort(order[:k]).astype(np.uint32)
+
+
+# (tau_t, delta_t) re-chosen as Algorithm 2 does every E iterations, here every 3: tau rises, falls
+# and returns, delta changes with it
+CHANGING = [(2, 0.05)] * 3 + [(0, 0.2)] * 3 + [(4, 0.02)] * 3 + [(1, 0.1)] * 3 + [(3, 0.05)] * 3 + \
+           [(3, 0.3)] * 2 + [(0, 0.01)] * 2 + [(4, 0.2)] * 3
+
+
+def test_ring_form_changing_tau_and_delta_numpy_replay(oracle_mod):
+    """Algorithm 2 re-chooses (tau, delta) while Algorithm 1 runs.  In the snapshot-ring form
+    iteration t takes every worker's gradient at x_{t - tau_t} with the noise of iteration t, runs
+    error feedback and Top-k with k_t = ceil(delta_t d), and applies the sum at once; while
+    t - tau_t < 0 nothing arrives (Section 3.2's convention): x and every e_i stay.  Replayed here
+    in numpy from a list of all iterates; messages, error buffers, update and model bit for bit."""
+    w, lam, xstar, x0 = small_problem(seed=71, d=900, n=3)
+    lr = 0.05
+    o = make_oracle(oracle_mod, w, lam, xstar, x0, 0, tau_max=4)
+    xs = [x0.copy()]
+    e = [np.zeros(w.d, dtype=F32) for _ in range(w.n)]
+    real = 0
+    for t, (tau, delta) in enumerate(CHANGING):
+        k = int(np.ceil(delta * w.d))
+        o.set_tau(tau)
+        o.step(delta, lr)
+        upd = np.zeros(w.d, dtype=F32)
+        if t - tau >= 0:
+            real += 1
+            stale = xs[t - tau]
+            for i in range(w.n):
+                z = oracle_mod.noise_fill(w.seed, t, i, 0, w.d, w.noise_kind)
+                g = lam * (stale - xstar) + F32(w.noise_scale) * z
+                p = e[i] + F32(lr) * g
+                comp, chosen = topk_dense(p, k)
+                e[i] = p - comp
+                upd = upd + comp
+                idx, val = o.get_message(i)
+                assert np.array_equal(idx, chosen), (t, i)
+                assert np.array_equal(bits(val), bits(p[chosen])), (t, i)
+        else:
+            assert all(len(o.get_message(i)[0]) == 0 for i in range(w.n))
+        xs.append(xs[-1] - upd / F32(w.n))
+        assert np.array_equal(bits(o.get_update()), bits(upd)), t
+        assert np.array_equal(bits(o.get_model()), bits(xs[-1])), t
+        for i in range(w.n):
+            assert np.array_equal(bits(o.get_error(i)), bits(e[i])), (t, i)
+    assert real == len(CHANGING) - 2                               # the first two were empty
+
+
+def test_stepwise_queue_form_changing_tau_and_delta_numpy_replay(oracle_mod):
+    """Algorithm 1 as printed under a changing (tau, delta): every iteration u each worker takes its
+    gradient at the current x_u, compresses e + lr*g with k_u = ceil(delta_u d) and sends; the
+    server applies what was sent tau_u iterations before u (possibly a message a second time, or
+    never), nothing while u - tau_u < 0."""
+    w, lam, xstar, x0 = small_problem(seed=72, d=800, n=3)
+    lr = 0.05
+    taus = [tau for tau, _ in CHANGING]
+    keys = queue_noise_keys(taus)
+    assert len(set(keys)) == len(keys)
+    q = oracle_mod.QueueOracle(w.d, w.n, 0)
+    q.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    x = x0.copy()
+    e = [np.zeros(w.d, dtype=F32) for _ in range(w.n)]
+    sent = []
+    for u, (tau, delta) in enumerate(CHANGING):
+        k = int(np.ceil(delta * w.d))
+        q.set_tau(tau)
+        q.step(delta, lr)
+        msgs = []
+        for i in range(w.n):
+            z = oracle_mod.noise_fill(w.seed, keys[u], i, 0, w.d, w.noise_kind)
+            g = lam * (x - xstar) + F32(w.noise_scale) * z
+            p = e[i] + F32(lr) * g
+            comp, chosen = topk_dense(p, k)
+            e[i] = p - comp
+            msgs.append(comp)
+            idx, val = q.get_message(i)
+            assert np.array_equal(idx, chosen) and np.array_equal(bits(val), bits(p[chosen])), (u, i)
+            assert np.array_equal(bits(q.get_error(i)), bits(e[i])), (u, i)
+        sent.append(msgs)
+        upd = np.zeros(w.d, dtype=F32)
+        if u - tau >= 0:
+            for i in range(w.n):
+                upd = upd + sent[u - tau][i]
+        x = x - upd / F32(w.n)
+        assert np.array_equal(bits(q.get_update()), bits(upd)), u
+        assert np.array_equal(bits(q.get_model()), bits(x)), u
+
+
 def test_stepwise_queue_form_changing_tau_is_delayed_sgd_at_delta_one(oracle_mod):
     """delta = 1 keeps every e_i at zero, so the message of iteration u is lr * g_u and the server's
     rule is x_{t+1} = x_t - (1/n) sum_i lr * g_{i, t - tau_t}: replayed here in numpy."""
@@ -292,12 +398,14 @@ def test_stepwise_queue_form_changing_tau_is_delayed_sgd_at_delta_one(oracle_mod
     q.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
     x = x0.copy()
     sent = []
+    keys = queue_noise_keys(taus)
+    assert len(set(keys)) == len(keys) and keys[:4] == [0, 1, 4, 5]
     for t, tau in enumerate(taus):
         q.set_tau(tau)
         q.step(1.0, lr)
         msgs = []
         for i in range(w.n):
-            z = oracle_mod.noise_fill(w.seed, t + tau, i, 0, w.d, w.noise_kind)
+            z = oracle_mod.noise_fill(w.seed, keys[t], i, 0, w.d, w.noise_kind)
             msgs.append(F32(lr) * (lam * (x - xstar) + F32(w.noise_scale) * z))
             assert np.all(bits(q.get_error(i)) == 0)
             idx, val = q.get_message(i)
