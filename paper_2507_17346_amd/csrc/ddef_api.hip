@@ -155,6 +155,7 @@ int hip_fail(ddef_ctx* c, hipError_t err) {
     if (err == hipSuccess) return DDEF_OK;
     int code = (err == hipErrorOutOfMemory) ? DDEF_ENOMEM : DDEF_EHIP;
     if (c && code == DDEF_EHIP) c->sticky = DDEF_EHIP;
+    (void)hipGetLastError();                 // reported here; not left for a later call to find
     return code;
 }
 
@@ -342,8 +343,11 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
     const uint32_t n = c->n;
     const uint64_t bitmap_ld = c->ld / 32u;
     if (!c->bitmap) {
-        HIP_TRY(c, hipMalloc((void**)&c->bitmap, (size_t)n * bitmap_ld * 4u));
-        HIP_TRY(c, hipMemsetAsync(c->bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream));
+        uint32_t* bitmap = nullptr;
+        hipError_t err = hipMalloc((void**)&bitmap, (size_t)n * bitmap_ld * 4u);
+        if (err == hipSuccess) err = hipMemsetAsync(bitmap, 0, (size_t)n * bitmap_ld * 4u, c->stream);
+        if (err != hipSuccess) { if (bitmap) (void)hipFree(bitmap); (void)hipGetLastError(); return hip_fail(c, err); }
+        c->bitmap = bitmap;
     }
     uint32_t bits_d = 1;
     while (((uint64_t)1 << bits_d) < c->d) ++bits_d;
@@ -361,8 +365,11 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
         return DDEF_OK;
     }
     if (!c->region_count) {
-        HIP_TRY(c, hipMalloc((void**)&c->region_count, (size_t)n * 2048u * 4u));
-        HIP_TRY(c, hipMemsetAsync(c->region_count, 0, (size_t)n * 2048u * 4u, c->stream));
+        uint32_t* counts = nullptr;
+        hipError_t err = hipMalloc((void**)&counts, (size_t)n * 2048u * 4u);
+        if (err == hipSuccess) err = hipMemsetAsync(counts, 0, (size_t)n * 2048u * 4u, c->stream);
+        if (err != hipSuccess) { if (counts) (void)hipFree(counts); (void)hipGetLastError(); return hip_fail(c, err); }
+        c->region_count = counts;
     }
     uint32_t* bucket = reinterpret_cast<uint32_t*>(c->cand);
     LAUNCH(c, SL_RANDK_BIN, k_randk_bin, dim3(blocks_for(c, (k + 8191u) / 8192u, n, 2), n), dim3(1024), bucket,
@@ -436,12 +443,29 @@ int start_prefetch(ddef_ctx* c) {
     // (queue form takes the next gradient at x_{t+1}, which does not exist yet)
     if (!c->opt_prefetch || c->opt_fuse || c->queue_form || c->tau == 0 || c->t + 1 < c->tau) return DDEF_OK;
     if (!c->side) {
-        HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_applied, hipEventDisableTiming));
-        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_prefetched, hipEventDisableTiming));
-        HIP_TRY(c, hipMalloc((void**)&c->g_next, (size_t)c->ld * 4u * c->n));
-        HIP_TRY(c, hipMemsetAsync(c->g_next, 0, (size_t)c->ld * 4u * c->n, c->side));
+        // second stream, its two events and the second gradient buffer: all of them or none, so
+        // that a failed set-up can simply be tried again
+        const size_t bytes = (size_t)c->ld * 4u * c->n;
+        hipStream_t side = nullptr;
+        hipEvent_t applied = nullptr, prefetched = nullptr;
+        float* next = nullptr;
+        hipError_t err = hipStreamCreateWithFlags(&side, hipStreamNonBlocking);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&applied, hipEventDisableTiming);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&prefetched, hipEventDisableTiming);
+        if (err == hipSuccess) err = hipMalloc((void**)&next, bytes);
+        if (err == hipSuccess) err = hipMemsetAsync(next, 0, bytes, side);
+        if (err != hipSuccess) {
+            if (side) (void)hipStreamSynchronize(side);
+            if (next) (void)hipFree(next);
+            if (prefetched) (void)hipEventDestroy(prefetched);
+            if (applied) (void)hipEventDestroy(applied);
+            if (side) (void)hipStreamDestroy(side);
+            (void)hipGetLastError();
+            return hip_fail(c, err);
+        }
+        c->side = side; c->ev_applied = applied; c->ev_prefetched = prefetched; c->g_next = next;
     }
+    if (!c->g_next || !c->ev_applied || !c->ev_prefetched) return DDEF_EINTERNAL;
     HIP_TRY(c, hipEventRecord(c->ev_applied, c->stream));        // everything up to here on the main stream
     HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_applied, 0));
     // fewer resident blocks than the stand-alone launch: the two kernels share the CUs' wave slots
@@ -468,10 +492,20 @@ int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t a
     if (kb_s < 8u || kb_s > count) return DDEF_OK;
     const uint32_t n = c->n;
     if (!c->sample) {
-        c->sample_ld = ((c->d < kSampleMax ? c->d : kSampleMax) + 15u) & ~(uint64_t)3u;
-        HIP_TRY(c, hipMalloc((void**)&c->sample, (size_t)n * c->sample_ld * 4u));
-        HIP_TRY(c, hipMemsetAsync(c->sample, 0, (size_t)n * c->sample_ld * 4u, c->stream));
-        HIP_TRY(c, hipMalloc((void**)&c->sample_total, (size_t)n * 4u));
+        // the sample rows and their length words: both or neither
+        const uint64_t sample_ld = ((c->d < kSampleMax ? c->d : kSampleMax) + 15u) & ~(uint64_t)3u;
+        float* sample = nullptr;
+        uint32_t* total = nullptr;
+        hipError_t err = hipMalloc((void**)&sample, (size_t)n * sample_ld * 4u);
+        if (err == hipSuccess) err = hipMalloc((void**)&total, (size_t)n * 4u);
+        if (err == hipSuccess) err = hipMemsetAsync(sample, 0, (size_t)n * sample_ld * 4u, c->stream);
+        if (err != hipSuccess) {
+            if (total) (void)hipFree(total);
+            if (sample) (void)hipFree(sample);
+            (void)hipGetLastError();
+            return hip_fail(c, err);
+        }
+        c->sample = sample; c->sample_total = total; c->sample_ld = sample_ld;
         drop_graph(c);
     }
     // a gradient that lives only in the fused accumulate pass is generated for the sampled coordinates
@@ -568,7 +602,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
     if (d == 0 || d >= 0xFFFFE000ull || n == 0 || n > 65535u || tau_max > 4096u) return DDEF_EINVAL;
     ddef_ctx* c = new (std::nothrow) ddef_ctx;
     if (!c) return DDEF_ENOMEM;
-    auto fail = [&](int code) { ddef_destroy(c); return code; };
+    auto fail = [&](int code) { ddef_destroy(c); (void)hipGetLastError(); return code; };
     hipError_t err = hipGetDevice(&c->device);
     if (err != hipSuccess) return fail(DDEF_EHIP);
     hipDeviceProp_t prop;
