@@ -325,6 +325,31 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                               * unchanged.                                                          */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The work of ddef_ef_compress (Top-k compressor) on
+ * buffers the caller owns, with no allocation of any kind and no context: for each of the n
+ * workers, p = e + lr*g is written over e, the k = ceil(delta*d) entries first in the total order
+ * become the message (ascending coordinate) and are cleared in e.  Same results, bit for bit, as
+ * ddef_ef_compress on the same e and g.
+ *   dev_e, dev_g     device pointers, n rows of ld floats each, 16-byte aligned; ld >= d and a
+ *                    multiple of 4; entries [d, ld) of a row are read and rewritten but never
+ *                    selected.  Finite values are required (nothing reports Inf/NaN here).
+ *   dev_msg_idx/val  device pointers, n rows of msg_ld >= k entries; row w receives worker w's
+ *                    message, entries beyond k are left alone.
+ *   hip_stream       hipStream_t (as void*) of the current device; NULL is the null stream.  The
+ *                    call only enqueues kernels (eleven launches, no memset or copy nodes), so it
+ *                    may be recorded into a HIP graph.
+ * The selection always searches the whole rows (no candidate filter: that needs buffers sized by
+ * k).  Its work memory -- selection state, histograms, per-chunk counts -- is a fixed array of
+ * about 21 MiB in the library's device image, one copy per GPU for the life of the process,
+ * which bounds the size: n <= 64 and n * ceil(d/4096) <= 2^21 (8 workers of 10^9 coordinates,
+ * 64 of 1.3*10^8), else EINVAL.  Every call on a GPU shares that array: calls that overlap on
+ * one GPU (two streams, two threads) race; calls on one stream are safe back to back.
+ * EINVAL also for null or misaligned pointers, delta outside (0, 1], d = 0, msg_ld < k. */
+int ddef_ef_compress_static(float* dev_e, const float* dev_g, uint64_t ld, uint64_t d, uint32_t n,
+                            double delta, float lr, uint32_t* dev_msg_idx, float* dev_msg_val,
+                            uint64_t msg_ld, void* hip_stream);
+
 const char* ddef_strerror(int code);
 
 #ifdef __cplusplus

@@ -75,6 +75,8 @@ SIGNATURES = {
     "ddef_full_select_count":  (C.c_int, [_ctx, _u64p]),
     "ddef_set_option": (C.c_int, [_ctx, C.c_int, C.c_int64]),
     "ddef_get_filter_state": (C.c_int, [_ctx, C.c_uint32, _u32p, _u32p, _u32p]),
+    "ddef_ef_compress_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32, C.c_double,
+                                          C.c_float, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "ddef_strerror": (C.c_char_p, [C.c_int]),
 }
 
@@ -135,6 +137,15 @@ def deco_noniid(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float) -> O
     if rc != OK:
         raise DdefError(rc, "ddef_deco_noniid")
     return int(tau.value), float(delta.value)
+
+
+def ef_compress_static(dev_e: int, dev_g: int, ld: int, d: int, n: int, delta: float, lr: float,
+                       dev_msg_idx: int, dev_msg_val: int, msg_ld: int, hip_stream: int = 0) -> int:
+    """ddef_ef_compress_static on device addresses given as integers; returns the library's code."""
+    return int(load().ddef_ef_compress_static(C.c_void_p(int(dev_e)), C.c_void_p(int(dev_g)), int(ld), int(d), int(n),
+                                              float(delta), float(lr), C.c_void_p(int(dev_msg_idx)),
+                                              C.c_void_p(int(dev_msg_val)), int(msg_ld),
+                                              C.c_void_p(int(hip_stream)) if hip_stream else None))
 
 
 def phi_prime(delta: float, tau: float) -> float:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1422,3 +1423,120 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
 
 }  // extern "C"
 
+// ---- error feedback + Top-k on the caller's buffers, without any allocation -----------------
+// Work memory of ddef_ef_compress_static: selection state, digit histograms, flag words, slot
+// counters and the per-chunk counts of the compaction, for at most kStaticWorkers workers and
+// kStaticChunks 4096-coordinate chunks over all workers together.  One copy per GPU, for the life
+// of the process.
+namespace {
+
+constexpr uint32_t kStaticWorkers = 64;
+constexpr uint64_t kStaticChunks = (uint64_t)1 << 21;
+constexpr size_t kStaticSelOff = 0;
+constexpr size_t kStaticSelBytes = (sizeof(SelState) * kStaticWorkers + 255u) & ~(size_t)255u;
+constexpr size_t kStaticFiltOff = kStaticSelOff + kStaticSelBytes;
+constexpr size_t kStaticFiltBytes = ((size_t)6 * kStaticWorkers * 4u + 255u) & ~(size_t)255u;
+constexpr size_t kStaticHistOff = kStaticFiltOff + kStaticFiltBytes;
+constexpr size_t kStaticHistBytes = (size_t)3 * kStaticWorkers * 2u * 2048u * 4u;
+constexpr size_t kStaticCountersOff = kStaticHistOff + kStaticHistBytes;
+constexpr size_t kStaticCountersBytes = (size_t)kStaticWorkers * kSubs * kSubStride * 4u;
+constexpr size_t kStaticGtOff = kStaticCountersOff + kStaticCountersBytes;
+constexpr size_t kStaticEqOff = kStaticGtOff + kStaticChunks * 4u;
+constexpr size_t kStaticBytes = kStaticEqOff + kStaticChunks * 4u;
+
+constexpr int kStaticDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_ptr[kStaticDevices] = {};     // device address of `scratch` on each GPU
+int g_static_cus[kStaticDevices] = {};
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+// Device address of this GPU's copy of `scratch` (looked up once per device, with that device
+// current) and its compute-unit count.
+int static_scratch(int device, unsigned char** ptr, int* cus) {
+    if (device < 0 || device >= kStaticDevices) return DDEF_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[device]) {
+        void* at = nullptr;
+        hipError_t err = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || at == nullptr) { (void)hipGetLastError(); return DDEF_EHIP; }
+        int count = 0;
+        err = hipDeviceGetAttribute(&count, hipDeviceAttributeMultiprocessorCount, device);
+        if (err != hipSuccess || count <= 0) { (void)hipGetLastError(); count = 256; }
+        g_static_cus[device] = count;
+        g_static_ptr[device] = static_cast<unsigned char*>(at);
+    }
+    *ptr = g_static_ptr[device];
+    *cus = g_static_cus[device];
+    return DDEF_OK;
+}
+
+}  // namespace
+
+extern "C" int ddef_ef_compress_static(float* dev_e, const float* dev_g, uint64_t ld, uint64_t d, uint32_t n,
+                                       double delta, float lr, uint32_t* dev_msg_idx, float* dev_msg_val,
+                                       uint64_t msg_ld, void* hip_stream) {
+    if (!dev_e || !dev_g || !dev_msg_idx || !dev_msg_val) return DDEF_EINVAL;
+    if (d == 0 || d >= 0xFFFFE000ull || n == 0 || n > kStaticWorkers) return DDEF_EINVAL;
+    if (!(delta > 0.0) || !(delta <= 1.0) || !std::isfinite(lr)) return DDEF_EINVAL;
+    if (ld < d || (ld & 3u) != 0u) return DDEF_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(dev_e) & 15u) != 0u || (reinterpret_cast<uintptr_t>(dev_g) & 15u) != 0u)
+        return DDEF_EINVAL;
+    const uint64_t nchunks = (d + 4095u) / 4096u;
+    if (nchunks * n > kStaticChunks) return DDEF_EINVAL;          // beyond what the work memory holds
+    const uint64_t k = ddef_k_from_delta(delta, d);
+    if (msg_ld < k) return DDEF_EINVAL;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return DDEF_EHIP; }
+    unsigned char* base = nullptr;
+    int cus = 256;
+    int rc = static_scratch(device, &base, &cus);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    SelState* sel = reinterpret_cast<SelState*>(base + kStaticSelOff);
+    uint32_t* filt = reinterpret_cast<uint32_t*>(base + kStaticFiltOff);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(base + kStaticHistOff);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(base + kStaticCountersOff);
+    uint32_t* cnt_gt = reinterpret_cast<uint32_t*>(base + kStaticGtOff);
+    uint32_t* cnt_eq = reinterpret_cast<uint32_t*>(base + kStaticEqOff);
+    uint32_t *bound = filt, *overflow = filt + n, *cand_total = filt + 3 * n, *nonfinite = filt + 4 * n,
+             *zero_at = filt + 5 * n;
+    auto blocks = [&](uint64_t row_blocks, uint32_t per_cu) {
+        uint64_t budget = (uint64_t)cus * per_cu / n;
+        if (budget < 1) budget = 1;
+        const uint64_t b = row_blocks < budget ? row_blocks : budget;
+        return (uint32_t)(b < 1 ? 1 : b);
+    };
+    // p = e + lr*g over e; every state word the later kernels read is written by a kernel of this
+    // call first (k_sel_begin_rows: selection state and histograms; k_chunk_count: the counts), so
+    // what an earlier call left in the work memory does not matter
+    const uint32_t groups = (uint32_t)((d + 255u) / 256u);
+    const GradSource none{};
+    hipLaunchKernelGGL(k_ef_filter<false>, dim3(groups, n), dim3(64), 0, stream, dev_e, dev_g, none, n, ld,
+                       (uint32_t)d, lr, (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint2*)nullptr,
+                       (uint64_t)0, (uint32_t*)nullptr, (uint32_t*)nullptr, (uint2*)nullptr, groups, nonfinite);
+    hipLaunchKernelGGL(k_sel_begin_rows, dim3(n), dim3(256), 0, stream, sel, n, (uint32_t)k, (uint32_t)k,
+                       (uint32_t)d, cand_total, hist);
+    const SelViews vs{dev_e, ld, (uint32_t)d, (const float*)nullptr, (const uint32_t*)nullptr, (uint64_t)0,
+                      (const uint32_t*)cand_total};
+    const uint32_t gx = blocks((d + 1023u) / 1024u, 8);
+    for (int level = 0; level < 3; ++level) {
+        uint32_t* h = hist + (uint64_t)level * n * 2 * 2048;
+        hipLaunchKernelGGL(k_digit_hist, dim3(gx, n), dim3(256), 0, stream, vs, (const SelState*)sel, h, level);
+        hipLaunchKernelGGL(k_digit_pick, dim3(n, 2), dim3(256), 0, stream, sel, (const uint32_t*)h, level);
+    }
+    const uint32_t gc = blocks(nchunks, 8);
+    hipLaunchKernelGGL(k_chunk_count, dim3(gc, n), dim3(256), 0, stream, vs, (const SelState*)sel, cnt_gt, cnt_eq,
+                       (uint32_t)nchunks);
+    hipLaunchKernelGGL(k_chunk_scan, dim3(n), dim3(1024), 0, stream, vs, sel, cnt_gt, cnt_eq, (uint32_t)nchunks,
+                       (uint32_t)k, (uint32_t)k, bound, zero_at, counters, overflow);
+    hipLaunchKernelGGL(k_chunk_emit, dim3(gc, n), dim3(256), 0, stream, vs, (const SelState*)sel,
+                       (const uint32_t*)cnt_gt, (const uint32_t*)cnt_eq, (uint32_t)nchunks, dev_e, dev_msg_idx,
+                       dev_msg_val, msg_ld, (uint32_t)k, 1);
+    if (hipGetLastError() != hipSuccess) return DDEF_EHIP;
+    return DDEF_OK;
+}

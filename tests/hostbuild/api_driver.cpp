@@ -5,6 +5,7 @@
 // about results; exit status 0 and a clean sanitizer report are the test.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
 #include <cstdio>
 #include <initializer_list>
 #include <vector>
@@ -304,8 +305,31 @@ static void deco_calls() {
           ddef_k_from_delta(1e-12, 5) == 1 && ddef_k_from_delta(0.5, 0) == 0 && ddef_k_from_delta(2.0, 5) == 0);
 }
 
+// the allocation-free entry point: what it accepts, what it refuses, and that it never allocates
+static void static_entry_point() {
+    const uint64_t d = 10001, ld = 10004;
+    std::vector<float> e(2 * ld + 4, 0.5f), g(2 * ld + 4, 1.0f), val(2 * 200);
+    std::vector<uint32_t> idx(2 * 200);
+    float* ep = e.data() + ((16 - (reinterpret_cast<uintptr_t>(e.data()) & 15u)) & 15u) / 4;     // 16-byte aligned
+    float* gp = g.data() + ((16 - (reinterpret_cast<uintptr_t>(g.data()) & 15u)) & 15u) / 4;
+    const long mallocs_before = fake_hip::state().mallocs;
+    CHECK(ddef_ef_compress_static(ep, gp, ld, d, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_OK);
+    CHECK(ddef_ef_compress_static(ep, gp, ld, d, 1, 0.001, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_OK);
+    CHECK(fake_hip::state().mallocs == mallocs_before);
+    CHECK(ddef_ef_compress_static(ep, gp, ld, d, 65, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, 4000000000ull, 3999999999ull, 3, 0.01, 0.05f, idx.data(), val.data(), 1ull << 30, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, ld - 4, d, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, ld + 1, d, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep + 1, gp, ld, d, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, ld, d, 2, 0.01, 0.05f, idx.data(), val.data(), 100, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, ld, d, 2, 0.0, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(nullptr, gp, ld, d, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+    CHECK(ddef_ef_compress_static(ep, gp, ld, 0, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
+}
+
 int main() {
     deco_calls();
+    static_entry_point();
     plain_runs();
     call_order_and_arguments();
     init_failures();
