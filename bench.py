@@ -33,6 +33,7 @@ VALU_PER_DRAW = {2: 162.2}
 # algorithmic bytes per (worker, element) of each streaming kernel, per launch over n*d
 ALGO_BYTES_PER_ELEM = {
     "k_ef_filter": 12.0,       # read e, read g, write p (the candidate filter rides along)
+    "k_ef_filter_split": 12.0,  # the same pass for dense messages (sure / band split of the candidates)
     "k_ef_filter_fused": 8.0,  # read e, write p; the gradient is generated in registers
     "k_ef_randk": 12.0,        # same pass for Random-k (+ 1/8 byte of bitmap)
     "k_grad": 4.0,             # write g (+ 12/n shared reads, not counted)
@@ -196,6 +197,9 @@ def main():
                          "instead of the snapshot ring; same iterates for constant tau")
     ap.add_argument("--zeta", type=float, default=0.0,
                     help="heterogeneous local objectives: worker i's optimum is x* + zeta u_i (0: IID, the default)")
+    ap.add_argument("--dense-split", type=int, default=1,
+                    help="0: dense messages go through the selection whole (study runs; default 1: candidates "
+                         "sure to be sent bypass it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -236,6 +240,7 @@ def main():
     ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
     ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
     ctx.set_option(binding.OPT_GRAPH, 1 if args.graph else 0)
+    ctx.set_option(binding.OPT_DENSE_SPLIT, 1 if args.dense_split else 0)
 
     state = {"tau": None}
 
@@ -396,7 +401,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched, lambda dl: round(sent_ratio(dl) * w.d)),
                    "d": w.d, "n": w.n, "k": round(sent_ratio(sched(ctx.t)[1]) * w.d), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph),
+                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph), "dense_split": bool(args.dense_split),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,

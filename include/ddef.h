@@ -323,6 +323,17 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                               * iteration to learn which); 0 always records every kept entry; 2 places
                               * the bound too high on purpose (tests of the repeat).  Results are
                               * unchanged.                                                          */
+#define DDEF_OPT_DENSE_SPLIT 8 /* 1 (default): where messages are dense (k/d > 1/32; ring form, Top-k; the filter
+                              * bound is then placed from a sample of e + lr*g in every iteration), the
+                              * candidates a margin above the expected threshold count as
+                              * sure to be sent: they are recorded once, in runs, and go to the aggregation as
+                              * they are, and only the band around the threshold is ordered, searched and
+                              * compacted.  A worker's message then lies in device memory in two parts;
+                              * ddef_get_message puts them together.  0: one part, every candidate searched.
+                              * 2, 3, 4 (tests): the line between sure and band is put just above the expected
+                              * threshold (about every other selection then counts k or more sure entries and
+                              * falls back to its row), at infinity (nothing is sure), or below the expected
+                              * threshold (always too many sure entries).  Results are unchanged.           */
 int ddef_set_option(ddef_ctx* ctx, int option, int64_t value);
 
 /* For callers that cannot allocate device memory: code under HIP graph capture, tight serving

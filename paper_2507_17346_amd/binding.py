@@ -19,6 +19,7 @@ NOISE_NONE, NOISE_GAUSS, NOISE_STUDENT_T3 = 0, 1, 2
 OPT_FORCE_FULL_SELECT, OPT_CANDIDATE_SLACK_X16, OPT_PREFETCH_GRAD, OPT_FUSE_GRAD, OPT_GRAPH = 1, 2, 3, 4, 5
 OPT_RANDK_BUCKET_PERCENT = 6
 OPT_COMPOSED_BOUND = 7
+OPT_DENSE_SPLIT = 8
 
 _u32p, _f32p, _u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
 _ctx = C.c_void_p

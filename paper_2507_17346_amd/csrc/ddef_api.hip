@@ -23,12 +23,14 @@ enum Phase { PH_IDLE = 0, PH_GRAD = 1, PH_COMPRESSED = 2, PH_AGGREGATED = 3 };
 enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_RANDK_BIN, SL_RANDK_FILL, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_QUANTIZE4, SL_SAMPLE, SL_FILL,
-    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_OBJECTIVE, SL_COUNT
+    SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_OBJECTIVE,
+    SL_EF_FILTER_SPLIT, SL_RESTORE_SURE, SL_MESSAGE_MERGE, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_randk_bin", "k_randk_fill", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_quantize4",
-    "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4", "k_objective"};
+    "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4", "k_objective",
+    "k_ef_filter_split", "k_restore_sure", "k_message_merge"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -53,7 +55,8 @@ struct ddef_ctx {
     std::vector<uint64_t> q_k;
     SelState* sel = nullptr;
     uint32_t *hist = nullptr, *cnt_gt = nullptr, *cnt_eq = nullptr;
-    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite | zero_at], slot
+    // candidate filter: per-worker words [bound | overflow | stat_full | cand_total | nonfinite | zero_at |
+    // sure_at | sure_total | msg_count] (the last three serve the sure / band split of dense messages), slot
     // counters [n][kSubs], the run table per 256-entry group with its prefixes, and the
     // candidate buffers of `cap` entries per worker
     uint32_t* filt = nullptr;
@@ -65,6 +68,21 @@ struct ddef_ctx {
     uint32_t* sorted_idx = nullptr;
     float* sorted_val = nullptr;
     uint64_t cap = 0;
+    // Dense messages whose bound comes from a sample of this very p are split: candidates sure to be
+    // sent are recorded as runs in `sure` (run table `stab`, slot counters `sure_count`) and go to
+    // the aggregation as they are; only the band around the expected threshold is ordered, searched
+    // and compacted into the message row.  msg_split: the last messages have that two-part form;
+    // agg_split: so have the ones named by the last ddef_aggregate.  canon_*: one worker's message
+    // in its canonical form, put together when ddef_get_message asks for it.
+    uint2* sure = nullptr;
+    uint2* stab = nullptr;
+    uint32_t* sure_count = nullptr;
+    uint64_t sure_cap = 0;
+    bool msg_split = false, agg_split = false;
+    uint32_t* canon_idx = nullptr;
+    float* canon_val = nullptr;
+    uint64_t canon_ld = 0;
+    int64_t opt_split = 1;
     bool have_bound = false;
     uint64_t bound_k = 0;                // the k the bound was placed for
     uint64_t sel_k = 0;                  // k of the last completed Top-k selection and how many in a row
@@ -307,10 +325,44 @@ int ensure_capacity(ddef_ctx* c, uint64_t k, uint64_t want) {
         HIP_TRY(c, hipMalloc((void**)&c->cand, (size_t)c->n * want * 8u));
         HIP_TRY(c, hipMalloc((void**)&c->sorted_idx, (size_t)c->n * want * 4u));
         HIP_TRY(c, hipMalloc((void**)&c->sorted_val, (size_t)c->n * want * 4u));
-        HIP_TRY(c, hipMemset(c->sorted_idx, 0, (size_t)c->n * want * 4u));
-        HIP_TRY(c, hipMemset(c->sorted_val, 0, (size_t)c->n * want * 4u));
+        HIP_TRY(c, hipMemsetAsync(c->sorted_idx, 0, (size_t)c->n * want * 4u, c->stream));
+        HIP_TRY(c, hipMemsetAsync(c->sorted_val, 0, (size_t)c->n * want * 4u, c->stream));
         c->cap = want;
     }
+    return DDEF_OK;
+}
+
+SureView sure_view(const ddef_ctx* c, bool split) {
+    if (!split) return SureView{nullptr, 0u, nullptr, 0u, nullptr};
+    return SureView{c->sure, c->sure_cap, c->stab, c->nwc, c->filt + 7 * c->n};
+}
+
+// Buffers of the sure / band split for a selection of k: records for k entries per worker plus a
+// quarter (the slots are handed out in kSubs parts that fill unevenly), the run table and the slot
+// counters.  All of them or none.
+int ensure_split_buffers(ddef_ctx* c, uint64_t k) {
+    uint64_t want = k + k / 4u + 256u * kSubs;
+    if (want > c->ld + 256u * kSubs) want = c->ld + 256u * kSubs;
+    want = (want + 4095u) & ~(uint64_t)4095u;
+    if (c->stab && want <= c->sure_cap) return DDEF_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    uint2 *sure = nullptr, *stab = c->stab;
+    uint32_t* counters = c->sure_count;
+    hipError_t err = hipMalloc((void**)&sure, (size_t)c->n * want * 8u);
+    if (err == hipSuccess && !stab) err = hipMalloc((void**)&stab, (size_t)c->n * c->nwc * 8u);
+    if (err == hipSuccess && !counters) {
+        err = hipMalloc((void**)&counters, (size_t)c->n * kSubs * kSubStride * 4u);
+        // on the context's stream: a fill on the null stream is not ordered against this stream's kernels
+        if (err == hipSuccess) err = hipMemsetAsync(counters, 0, (size_t)c->n * kSubs * kSubStride * 4u, c->stream);
+    }
+    if (err != hipSuccess) {
+        if (sure) (void)hipFree(sure);
+        if (stab && stab != c->stab) (void)hipFree(stab);
+        if (counters && counters != c->sure_count) (void)hipFree(counters);
+        return hip_fail(c, err);
+    }
+    if (c->sure) (void)hipFree(c->sure);
+    c->sure = sure; c->stab = stab; c->sure_count = counters; c->sure_cap = want;
     return DDEF_OK;
 }
 
@@ -389,7 +441,8 @@ void materialize_update(ddef_ctx* c) {
     if (!c->agg_deferred || c->agg_in_U) return;
     LAUNCH(c, SL_AGGREGATE_TILES, k_aggregate_tiles<false>, dim3(c->ntiles), dim3(256), c->U,
            (const uint32_t*)c->slot_idx(c->agg_slot), (const float*)c->slot_val(c->agg_slot), c->msg_ld,
-           (const uint32_t*)c->agg_off, c->ntiles, c->n, ModelRows{nullptr, nullptr, nullptr, nullptr, 1u, 0u}, 1.0f);
+           (const uint32_t*)c->agg_off, c->ntiles, c->n, ModelRows{nullptr, nullptr, nullptr, nullptr, 1u, 0u}, 1.0f,
+           sure_view(c, c->agg_split));
     c->u_zero = false;
     c->agg_in_U = true;
 }
@@ -482,8 +535,9 @@ int start_prefetch(ddef_ctx* c) {
 // 1/sqrt(above)) within a sample of at most kSampleMax entries per worker; with fewer than 8 above
 // the bound sampling says too little, and the iteration goes on with what it had (a whole-row
 // search when there is no bound at all).
-int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t above) {
+int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t above, bool* placed = nullptr) {
     constexpr uint64_t kSampleMax = 1u << 20;
+    if (placed) *placed = false;
     uint64_t stride = kb / above;
     const uint64_t least = (c->d + kSampleMax - 1u) / kSampleMax;
     if (stride < least) stride = least;
@@ -531,10 +585,11 @@ int bound_from_sample(ddef_ctx* c, uint64_t k, uint64_t kb, float lr, uint64_t a
         LAUNCH(c, SL_DIGIT_PICK, k_digit_pick, dim3(n, 2), dim3(256), c->sel, (const uint32_t*)h, level);
     }
     LAUNCH(c, SL_SAMPLE, k_sample_finish, dim3((n + 255u) / 256u), dim3(256), (const SelState*)c->sel, n, c->filt,
-           c->filt + 5 * n);
+           c->filt + 5 * n, c->filt + 6 * n, (int)c->opt_split - 1);
     HIP_TRY(c, hipGetLastError());
     c->have_bound = true;
     c->bound_k = k;
+    if (placed) *placed = true;
     return DDEF_OK;
 }
 
@@ -628,7 +683,7 @@ static int init_ctx(uint64_t d, uint32_t n, uint32_t tau_max, bool queue_form, d
         {(void**)&c->ring, row * c->ring_slots}, {(void**)&c->e, row * n}, {(void**)&c->g, row * n},
         {(void**)&c->sel, sizeof(SelState) * n}, {(void**)&c->hist, (size_t)3 * n * 2 * 2048 * 4},
         {(void**)&c->cnt_gt, (size_t)n * c->nchunks * 4}, {(void**)&c->cnt_eq, (size_t)n * c->nchunks * 4},
-        {(void**)&c->filt, (size_t)6 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
+        {(void**)&c->filt, (size_t)9 * n * 4}, {(void**)&c->cand_count, (size_t)n * kSubs * kSubStride * 4}, {(void**)&c->tab, (size_t)n * c->nwc * 8},
         {(void**)&c->span_sum, (size_t)n * c->nspans * 4},
         {(void**)&c->agg_off, (size_t)n * (c->ntiles + 1u) * 4},
         {(void**)&c->t_dev, 8},
@@ -664,7 +719,8 @@ int ddef_destroy(ddef_ctx* c) {
     for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
     void* bufs[] = {c->lambda, c->xstar, c->U, c->ring, c->e, c->g, c->sel, c->hist, c->cnt_gt,
                     c->cnt_eq, c->msg_idx, c->msg_val, c->filt, c->cand_count, c->tab, c->span_sum, c->agg_off, c->t_dev, c->sample, c->sample_total, c->bitmap, c->region_count, c->objective_partial, c->g_next, c->cand,
-                    c->sorted_idx, c->sorted_val, c->codes, c->steps};
+                    c->sorted_idx, c->sorted_val, c->codes, c->steps, c->sure, c->stab, c->sure_count, c->canon_idx,
+                    c->canon_val};
     for (void* b : bufs) if (b) (void)hipFree(b);
     if (c->own_stream) (void)hipStreamDestroy(c->own_stream);
     delete c;
@@ -702,11 +758,16 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     for (uint32_t s = 0; s < c->ring_slots; ++s)
         HIP_TRY(c, hipMemcpy(c->ring + (uint64_t)s * c->ld, host_x0, bytes, hipMemcpyHostToDevice));
     std::fill(c->q_k.begin(), c->q_k.end(), (uint64_t)0);
-    HIP_TRY(c, hipMemset(c->e, 0, (size_t)c->ld * 4u * c->n));
-    HIP_TRY(c, hipMemset(c->U, 0, (size_t)c->ld * 4u));
-    HIP_TRY(c, hipMemset(c->sel, 0, sizeof(SelState) * c->n));
-    HIP_TRY(c, hipMemset(c->filt, 0, (size_t)6 * c->n * 4));
-    HIP_TRY(c, hipMemset(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4));
+    // fills go on the context's stream, where the kernels that read these buffers run (a fill on the
+    // null stream is not ordered against a non-blocking stream)
+    HIP_TRY(c, hipMemsetAsync(c->e, 0, (size_t)c->ld * 4u * c->n, c->stream));
+    HIP_TRY(c, hipMemsetAsync(c->U, 0, (size_t)c->ld * 4u, c->stream));
+    HIP_TRY(c, hipMemsetAsync(c->sel, 0, sizeof(SelState) * c->n, c->stream));
+    HIP_TRY(c, hipMemsetAsync(c->filt, 0, (size_t)9 * c->n * 4, c->stream));
+    c->msg_split = false; c->agg_split = false;
+    HIP_TRY(c, hipMemsetAsync(c->cand_count, 0, (size_t)c->n * kSubs * kSubStride * 4, c->stream));
+    if (c->sure_count) HIP_TRY(c, hipMemsetAsync(c->sure_count, 0, (size_t)c->n * kSubs * kSubStride * 4, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->have_bound = false;
     c->sel_k = 0; c->sel_run = 0;
     drop_graph(c);
@@ -830,6 +891,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     const uint64_t k1 = composed ? ddef_k_from_delta(c->rand_ratio, c->d) : 0u;
     const uint64_t k = composed ? ddef_k_from_delta(delta, k1) : ddef_k_from_delta(delta, c->d);
     c->agg_deferred = false;               // the messages it would read are about to be replaced
+    c->msg_split = false;
     const uint64_t kb = candidate_target(c, k);
     rc = composed ? ensure_capacity(c, k, candidate_capacity(c, k1, candidate_target(c, k1)))
                   : ensure_capacity(c, k, candidate_capacity(c, k, kb));
@@ -942,27 +1004,52 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     // to outweigh the sampling by far, and the trend of noisy thresholds misses by more.
     const bool can_filter = !c->opt_force_full && 2 * kb <= c->d;
     const bool dense = samples_every_iteration(c, k);
+    bool sampled = false;
     if (can_filter && (dense || !c->have_bound || c->bound_k != k || c->sel_k != k || c->sel_run < 2u)) {
-        rc = bound_from_sample(c, k, kb, lr, dense ? 65536u : 256u);
+        rc = bound_from_sample(c, k, kb, lr, dense ? 65536u : 256u, &sampled);
         if (rc) return rc;
     }
     const bool use_filter = can_filter && c->have_bound;
-    const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
-    if (c->grad_pending) {
-        LAUNCH(c, SL_EF_FILTER_FUSED, k_ef_filter<true>, dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
-               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
-               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
-    } else {
-        LAUNCH(c, SL_EF_FILTER, k_ef_filter<false>, dim3(c->nwc, n), dim3(64), c->e, (const float*)c->g, src, n,
-               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
-               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+    // dense messages (k/d > 1/32) with a bound and an expected threshold fresh from this p: sure / band
+    // split.  (Measured on d = 1.3e9, n = 4: 20.6 -> 15.5 ms per iteration at delta = 0.1; at
+    // delta = 0.01 the runs are two or three entries long and reading them costs the aggregation more
+    // than the selection saves, 12.4 -> 12.9 ms, so sparser messages keep the one-part form.)  The
+    // queue form keeps whole messages in its slots and stays with the one-part form, too.
+    const bool split = use_filter && sampled && k * 32u > c->d && !c->queue_form && c->opt_split;
+    if (split) {
+        rc = ensure_split_buffers(c, k);
+        if (rc) return rc;
     }
+    const SureRuns sp{c->filt + 6 * n, c->sure, c->sure_cap, c->sure_count, c->stab};
+    const GradSource src = grad_source(c, c->grad_key(), c->grad_snapshot());
+    if (c->grad_pending && split) {
+        LAUNCH(c, SL_EF_FILTER_FUSED, (k_ef_filter<true, true>), dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
+               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, 1,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, sp);
+    } else if (c->grad_pending) {
+        LAUNCH(c, SL_EF_FILTER_FUSED, (k_ef_filter<true, false>), dim3(c->nwc * n), dim3(64), c->e, (const float*)c->g, src,
+               n, c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, sp);
+    } else if (split) {
+        LAUNCH(c, SL_EF_FILTER_SPLIT, (k_ef_filter<false, true>), dim3(c->nwc, n), dim3(64), c->e, (const float*)c->g, src, n,
+               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, 1,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, sp);
+    } else {
+        LAUNCH(c, SL_EF_FILTER, (k_ef_filter<false, false>), dim3(c->nwc, n), dim3(64), c->e, (const float*)c->g, src, n,
+               c->ld, (uint32_t)c->d, lr, (const uint32_t*)bound, (const uint32_t*)zero_at, use_filter ? 1 : 0,
+               c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, sp);
+    }
+    c->msg_split = split;
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                c->span_sum, c->nspans);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide, dim3(n), dim3(256), c->span_sum, c->nspans,
                (const uint32_t*)overflow, (uint32_t)k, (uint32_t)kb, (uint32_t)c->d, n, c->sel, cand_total,
-               stat_full, (const uint32_t*)zero_at, c->hist);
+               stat_full, (const uint32_t*)zero_at, c->hist, split ? c->sure_count : (uint32_t*)nullptr,
+               split ? c->filt + 7 * n : (uint32_t*)nullptr, split ? c->filt + 8 * n : (uint32_t*)nullptr);
+        if (split)
+            LAUNCH(c, SL_RESTORE_SURE, k_restore_sure, dim3((c->nwc + 255u) / 256u, n), dim3(256),
+                   (const SelState*)c->sel, sp, c->nwc, c->e, c->ld);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
                c->sorted_idx, c->sorted_val, c->cap, c->e, c->ld);
@@ -996,8 +1083,10 @@ int ddef_aggregate(ddef_ctx* c) {
         ka = c->t >= c->tau ? c->q_k[src] : 0;
     }
     if (ka) {
+        c->agg_split = c->msg_split && !c->queue_form;
         LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, c->n), dim3(256),
-               (const uint32_t*)c->slot_idx(src), c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off);
+               (const uint32_t*)c->slot_idx(src), c->msg_ld, (uint32_t)ka, c->ntiles, c->agg_off,
+               c->agg_split ? (const uint32_t*)(c->filt + 8 * c->n) : (const uint32_t*)nullptr);
         c->agg_deferred = true;
         c->agg_in_U = false;
         c->agg_slot = src;
@@ -1023,7 +1112,7 @@ int ddef_apply_delayed(ddef_ctx* c, float lr) {
                (const uint32_t*)c->agg_off, c->ntiles, c->n,
                ModelRows{c->slot(c->t), c->slot(c->t + 1), c->capturing ? c->t_dev : nullptr, c->ring,
                          c->ring_slots, c->ld},
-               (float)c->n);
+               (float)c->n, sure_view(c, c->agg_split));
     } else {
         LAUNCH(c, SL_APPLY, k_apply, dim3((uint32_t)((quads + 63) / 64)), dim3(64), c->slot(c->t),
                c->U, c->slot(c->t + 1), (uint32_t)c->d, (float)c->n);
@@ -1247,6 +1336,47 @@ int ddef_get_update(ddef_ctx* c, float* host_U) {
     return copy_row_out(c, c->U, host_U);
 }
 
+// A worker's split message (sure runs + band part of its row) as one list in ascending coordinate
+// order, written to the canon buffers.  *merged stays false where the row already holds the whole
+// message (no split, a worker that fell back to its row, or no sure entries).
+static int canonical_message(ddef_ctx* c, uint32_t worker, bool* merged) {
+    *merged = false;
+    if (!c->msg_split) return DDEF_OK;
+    const uint32_t n = c->n;
+    uint32_t sure_total = 0;
+    HIP_TRY(c, hipMemcpy(&sure_total, c->filt + 7 * n + worker, 4u, hipMemcpyDeviceToHost));
+    if (sure_total == 0u) return DDEF_OK;
+    if (c->canon_ld < c->k_step) {
+        const uint64_t len = (c->k_step + 1023u) & ~(uint64_t)1023u;
+        uint32_t* idx = nullptr;
+        float* val = nullptr;
+        hipError_t err = hipMalloc((void**)&idx, (size_t)len * 4u);
+        if (err == hipSuccess) err = hipMalloc((void**)&val, (size_t)len * 4u);
+        if (err != hipSuccess) { if (idx) (void)hipFree(idx); return hip_fail(c, err); }
+        if (c->canon_idx) (void)hipFree(c->canon_idx);
+        if (c->canon_val) (void)hipFree(c->canon_val);
+        c->canon_idx = idx; c->canon_val = val; c->canon_ld = len;
+    }
+    const SureView sv = sure_view(c, true);
+    // where each tile's band entries start in the rows (what ddef_aggregate computes, too), how many
+    // sure entries precede each tile (the compaction's chunk counters are idle between selections and
+    // have one word per tile), then the merge
+    LAUNCH(c, SL_MSG_OFFSETS, k_msg_offsets, dim3((c->ntiles + 1u + 255u) / 256u, n), dim3(256),
+           (const uint32_t*)c->slot_idx(c->msg_slot), c->msg_ld, (uint32_t)c->k_step, c->ntiles, c->agg_off,
+           (const uint32_t*)(c->filt + 8 * n));
+    LAUNCH(c, SL_MESSAGE_MERGE, k_tile_sure_count, dim3((c->ntiles + 255u) / 256u), dim3(256), sv, worker, c->ntiles,
+           c->cnt_gt);
+    LAUNCH(c, SL_MESSAGE_MERGE, k_tile_scan, dim3(1), dim3(1024), c->cnt_gt, c->ntiles);
+    LAUNCH(c, SL_MESSAGE_MERGE, k_message_merge, dim3(c->ntiles), dim3(256), sv, worker,
+           (const uint32_t*)c->slot_idx(c->msg_slot), (const float*)c->slot_val(c->msg_slot), c->msg_ld,
+           (const uint32_t*)c->agg_off, c->ntiles, (const uint32_t*)c->cnt_gt, c->canon_idx, c->canon_val,
+           (uint32_t)c->k_step);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    *merged = true;
+    return DDEF_OK;
+}
+
 int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* host_val, uint64_t* k) {
     int rc = check_ctx(c);
     if (rc) return rc;
@@ -1258,10 +1388,13 @@ int ddef_get_message(ddef_ctx* c, uint32_t worker, uint32_t* host_idx, float* ho
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     rc = check_device_flags(c);
     if (rc) return rc;
-    HIP_TRY(c, hipMemcpy(host_idx, c->slot_idx(c->msg_slot) + (uint64_t)worker * c->msg_ld,
-                         (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
-    HIP_TRY(c, hipMemcpy(host_val, c->slot_val(c->msg_slot) + (uint64_t)worker * c->msg_ld,
-                         (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
+    bool merged = false;
+    rc = canonical_message(c, worker, &merged);
+    if (rc) return rc;
+    const uint32_t* src_idx = merged ? c->canon_idx : c->slot_idx(c->msg_slot) + (uint64_t)worker * c->msg_ld;
+    const float* src_val = merged ? c->canon_val : c->slot_val(c->msg_slot) + (uint64_t)worker * c->msg_ld;
+    HIP_TRY(c, hipMemcpy(host_idx, src_idx, (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemcpy(host_val, src_val, (size_t)c->k_step * 4u, hipMemcpyDeviceToHost));
     return DDEF_OK;
 }
 
@@ -1405,6 +1538,10 @@ int ddef_set_option(ddef_ctx* c, int option, int64_t value) {
             if (c->opt_fuse) return drop_prefetch(c);
             return DDEF_OK;
         case DDEF_OPT_GRAPH: c->opt_graph = value != 0; return DDEF_OK;
+        case DDEF_OPT_DENSE_SPLIT:
+            if (value < 0 || value > 4) return DDEF_EINVAL;
+            c->opt_split = value;
+            return DDEF_OK;
         case DDEF_OPT_COMPOSED_BOUND:
             if (value < 0 || value > 2) return DDEF_EINVAL;
             c->opt_composed_bound = value;
@@ -1516,9 +1653,10 @@ extern "C" int ddef_ef_compress_static(float* dev_e, const float* dev_g, uint64_
     // what an earlier call left in the work memory does not matter
     const uint32_t groups = (uint32_t)((d + 255u) / 256u);
     const GradSource none{};
-    hipLaunchKernelGGL(k_ef_filter<false>, dim3(groups, n), dim3(64), 0, stream, dev_e, dev_g, none, n, ld,
+    hipLaunchKernelGGL((k_ef_filter<false, false>), dim3(groups, n), dim3(64), 0, stream, dev_e, dev_g, none, n, ld,
                        (uint32_t)d, lr, (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint2*)nullptr,
-                       (uint64_t)0, (uint32_t*)nullptr, (uint32_t*)nullptr, (uint2*)nullptr, groups, nonfinite);
+                       (uint64_t)0, (uint32_t*)nullptr, (uint32_t*)nullptr, (uint2*)nullptr, groups, nonfinite,
+                       SureRuns{});
     hipLaunchKernelGGL(k_sel_begin_rows, dim3(n), dim3(256), 0, stream, sel, n, (uint32_t)k, (uint32_t)k,
                        (uint32_t)d, cand_total, hist);
     const SelViews vs{dev_e, ld, (uint32_t)d, (const float*)nullptr, (const uint32_t*)nullptr, (uint64_t)0,

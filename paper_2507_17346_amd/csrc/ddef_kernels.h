@@ -59,17 +59,37 @@ struct GradSource {
     uint64_t ring_ld;
 };
 
+// Dense messages, sure / band split: where the accumulate pass records the candidates that are sure
+// to be sent (runs of (index, value) per 256-coordinate group, like the candidate buffer), and the
+// same buffers as the aggregation reads them.
+struct SureRuns {
+    const uint32_t* sure_at;     // per worker: magnitude pattern from which a candidate counts as sure
+    uint2* sure;                 // [n][cap] records
+    uint64_t cap;
+    uint32_t* count;             // [n][kSubs * kSubStride] slot counters
+    uint2* stab;                 // [n][ngroups] run table (first slot, count)
+};
+struct SureView {
+    const uint2* sure;           // null: messages are not split
+    uint64_t cap;
+    const uint2* stab;
+    uint32_t ngroups;
+    const uint32_t* total;       // per worker: sure entries that belong to its message (0: none)
+};
+
 __global__ void k_grad(GradSource s, float* g, uint64_t ld, uint32_t d, uint32_t n);
 __global__ void k_objective(GradSource s, uint32_t d, uint32_t n, double* partial);
-template <bool kFusedGrad>
+template <bool kFusedGrad, bool kSplit>
 __global__ void k_ef_filter(float* e, const float* g, GradSource src, uint32_t n, uint64_t ld, uint32_t d,
                             float lr, const uint32_t* bound, const uint32_t* zero_at, int use_filter, uint2* cand, uint64_t cap,
                             uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups,
-                            uint32_t* nonfinite);
+                            uint32_t* nonfinite, SureRuns sp);
 __global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
 __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
                              uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,
-                             uint32_t* stat_full, const uint32_t* zero_at, uint32_t* hist);
+                             uint32_t* stat_full, const uint32_t* zero_at, uint32_t* hist, uint32_t* sure_count,
+                             uint32_t* sure_total, uint32_t* msg_count);
+__global__ void k_restore_sure(const SelState* sel, SureRuns sp, uint32_t ngroups, float* e, uint64_t ld);
 __global__ void k_sel_begin_rows(SelState* sel, uint32_t n, uint32_t k, uint32_t kb, uint32_t d,
                                  uint32_t* cand_total, uint32_t* hist);
 __global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* span_off, uint32_t nspans,
@@ -106,12 +126,14 @@ __global__ void k_sample_p(const float* e, const float* g, GradSource src, uint6
                            float* sample, uint64_t sample_ld);
 __global__ void k_sample_begin(SelState* sel, uint32_t n, uint32_t k_s, uint32_t kb_s, uint32_t count,
                                uint32_t* sample_total, uint32_t* hist);
-__global__ void k_sample_finish(const SelState* sel, uint32_t n, uint32_t* bound, uint32_t* zero_at);
+__global__ void k_sample_finish(const SelState* sel, uint32_t n, uint32_t* bound, uint32_t* zero_at,
+                                uint32_t* sure_at, int sure_mode);
 __global__ void k_chunk_emit(SelViews vs, const SelState* sel, const uint32_t* out_base,
                              const uint32_t* eq_before, uint32_t stride, float* e, uint32_t* msg_idx,
                              float* msg_val, uint64_t msg_ld, uint32_t k, int fix_e);
 __global__ void k_apply(const float* x, const float* U, float* xn, uint32_t d, float nf);
-__global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off);
+__global__ void k_msg_offsets(const uint32_t* idx, uint64_t msg_ld, uint32_t k, uint32_t ntiles, uint32_t* off,
+                              const uint32_t* count);
 // Where the model update reads x_t and writes x_{t+1}: given rows, or (inside a captured graph)
 // slots t and t+1 of the ring with t read from device memory.
 struct ModelRows {
@@ -124,7 +146,13 @@ struct ModelRows {
 };
 template <bool kApply>
 __global__ void k_aggregate_tiles(float* U, const uint32_t* idx, const float* val, uint64_t msg_ld,
-                                  const uint32_t* off, uint32_t ntiles, uint32_t n, ModelRows rows, float nf);
+                                  const uint32_t* off, uint32_t ntiles, uint32_t n, ModelRows rows, float nf,
+                                  SureView sv);
+__global__ void k_tile_sure_count(SureView sv, uint32_t w, uint32_t ntiles, uint32_t* tile_count);
+__global__ void k_tile_scan(uint32_t* tile_count, uint32_t ntiles);
+__global__ void k_message_merge(SureView sv, uint32_t w, const uint32_t* idx, const float* val, uint64_t msg_ld,
+                                const uint32_t* off, uint32_t ntiles, const uint32_t* sure_before, uint32_t* out_idx,
+                                float* out_val, uint32_t k);
 __global__ void k_advance(uint64_t* t_dev);
 __global__ void k_fill_f4(float* p, uint64_t quads);
 __global__ void k_copy_f4(const float* src, float* dst, uint64_t quads);

@@ -319,7 +319,16 @@ __global__ __launch_bounds__(256) void k_objective(GradSource s, uint32_t d, uin
 // the truth need a scattered store (k_chunk_emit), instead of all k sent ones.  A group that
 // gets no slots keeps all its entries in e and records an empty run.
 // ------------------------------------------------------------------------------------
-template <bool kFusedGrad>
+//
+// kSplit (dense messages, bound placed from a sample of this very p): the candidates fall into two
+// classes.  Those at or above sure_at[w] -- a pattern as far above the expected threshold as the
+// bound lies below it -- are *sure* to be sent: they are recorded as runs in a buffer of their own
+// (sp.sure, run table sp.stab, slot counters sp.count) and never looked at again by the selection;
+// the aggregation reads them straight from their runs.  Only the narrow *band* between bound[w] and
+// sure_at[w] goes through the candidate buffer, the ordering, the radix select and the compaction,
+// for the rank k minus the number of sure entries.  Should the guess be wrong (more sure entries
+// than k, or fewer than k candidates in all), the worker falls back to its whole row as always.
+template <bool kFusedGrad, bool kSplit>
 __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const float* __restrict__ g,
                                                   GradSource src, uint32_t n,
                                                   uint64_t ld, uint32_t d, float lr,
@@ -329,7 +338,7 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
                                                   uint32_t* __restrict__ cand_count,
                                                   uint32_t* __restrict__ overflow,
                                                   uint2* __restrict__ tab, uint32_t ngroups,
-                                                  uint32_t* __restrict__ nonfinite) {
+                                                  uint32_t* __restrict__ nonfinite, SureRuns sp) {
     // plain: grid (groups, n).  fused: 1-D grid with the worker index fastest, so that the blocks
     // that need the same lambda / x* / snapshot lines run at about the same time
     if (kFusedGrad) resolve_iteration(src);
@@ -367,54 +376,98 @@ __global__ __launch_bounds__(64) void k_ef_filter(float* __restrict__ e, const f
         return;
     }
     const uint32_t L = bound[w], H = zero_at[w];
-    bool f[4];
-    bool any = false;
+    const uint32_t S = kSplit ? sp.sure_at[w] : 0xffffffffu;       // split: [L, S) is the band, [S, ..) is sure
+    bool f[4], sure[4];
+    bool any = false, any_sure = false;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) { f[c] = (j + c < d) && mag_key(pv[c]) >= L; any |= f[c]; }
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t key = mag_key(pv[c]);
+        const bool in = j + c < d;
+        f[c] = in && key >= L && key < S;
+        sure[c] = kSplit && in && key >= S;
+        any |= f[c];
+        any_sure |= sure[c];
+    }
     // the dense store goes out first, already with +0 at the candidates expected to be sent
     // (a group that then gets no slots stores its values once more, below)
     if (j < d) {
         float ov[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) ov[c] = (f[c] && mag_key(pv[c]) >= H) ? 0.0f : pv[c];
+        for (int c = 0; c < 4; ++c) ov[c] = ((f[c] || sure[c]) && mag_key(pv[c]) >= H) ? 0.0f : pv[c];
         store_stream4(ep, ov);
     }
-    uint32_t first = 0, total = 0;
-    if (__ballot(any)) {                       // most groups hold no candidate at all
-        uint32_t below = 0;
+    const uint32_t sub = grp & (kSubs - 1u);
+    bool keep_all = false;                     // a class got no slots: the group's entries stay in e
+    uint32_t first = 0, total = 0, sfirst = 0, stotal = 0;
+    if (__ballot(any || any_sure)) {           // most groups of a sparse selection hold no candidate at all
+        uint32_t below = 0, sbelow = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint64_t m = __ballot(f[c]);
             below += mask_rank(m);
             total += (uint32_t)__popcll(m);
+            if (kSplit) {
+                const uint64_t ms = __ballot(sure[c]);
+                sbelow += mask_rank(ms);
+                stotal += (uint32_t)__popcll(ms);
+            }
         }
-        const uint32_t sub = grp & (kSubs - 1u);
-        const uint32_t sub_cap = (uint32_t)(cap / kSubs);
+        // slots for both classes in one go: lane 0 reserves the band's, lane 1 the sure entries', so
+        // that the two reservations are in flight together
         uint32_t got = 0;
-        if (lane == 0) got = atomicAdd(&cand_count[(w * kSubs + sub) * kSubStride], total);
-        got = __shfl(got, 0, 64);
-        if (got + total > sub_cap) {
-            if (lane == 0) overflow[w] = 1u;
-            total = 0;                         // nothing recorded for this group:
-            if (j < d) store_stream4(ep, pv);  // all its entries stay in e (same lane, same address: in order)
-        } else {
-            first = sub * sub_cap + got;
-            uint2* cw = cand + (uint64_t)w * cap;
-            uint32_t pos = first + below;
+        if (lane == 0 && total != 0u) got = atomicAdd(&cand_count[(w * kSubs + sub) * kSubStride], total);
+        if (kSplit && lane == 1 && stotal != 0u) got = atomicAdd(&sp.count[(w * kSubs + sub) * kSubStride], stotal);
+        const uint32_t got_band = __shfl(got, 0, 64);
+        if (total != 0u) {
+            const uint32_t sub_cap = (uint32_t)(cap / kSubs);
+            if (got_band + total > sub_cap) {
+                if (lane == 0) overflow[w] = 1u;
+                total = 0;                     // nothing recorded for this group
+                keep_all = true;
+            } else {
+                first = sub * sub_cap + got_band;
+                uint2* cw = cand + (uint64_t)w * cap;
+                uint32_t pos = first + below;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
+                for (int c = 0; c < 4; ++c)
+                    if (f[c]) { cw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
+            }
+        }
+        if (kSplit && stotal != 0u) {
+            const uint32_t got_sure = __shfl(got, 1, 64);
+            const uint32_t sub_cap = (uint32_t)(sp.cap / kSubs);
+            if (got_sure + stotal > sub_cap) {
+                if (lane == 0) overflow[w] = 1u;
+                stotal = 0;
+                keep_all = true;
+            } else {
+                sfirst = sub * sub_cap + got_sure;
+                uint2* sw = sp.sure + (uint64_t)w * sp.cap;
+                uint32_t pos = sfirst + sbelow;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (sure[c]) { sw[pos] = make_uint2(j + c, __float_as_uint(pv[c])); ++pos; }
+            }
         }
     }
-    if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
+    if (lane == 0) {
+        tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
+        if (kSplit) sp.stab[(uint64_t)w * ngroups + grp] = make_uint2(sfirst, stotal);
+    }
+    // (same lane, same address as the store above: the two stay in order.  The worker falls back to
+    // its row, and the entries that were recorded are written back there with the same values.)
+    if (keep_all && j < d) store_stream4(ep, pv);
 }
 
-template __global__ void k_ef_filter<false>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
-                                            const uint32_t*, const uint32_t*, int, uint2*, uint64_t, uint32_t*,
-                                            uint32_t*, uint2*, uint32_t, uint32_t*);
-template __global__ void k_ef_filter<true>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, float,
-                                           const uint32_t*, const uint32_t*, int, uint2*, uint64_t, uint32_t*,
-                                           uint32_t*, uint2*, uint32_t, uint32_t*);
+#define DDEF_EF_FILTER_INSTANCE(fused, split)                                                                  \
+    template __global__ void k_ef_filter<fused, split>(float*, const float*, GradSource, uint32_t, uint64_t, uint32_t, \
+                                                       float, const uint32_t*, const uint32_t*, int, uint2*, uint64_t,  \
+                                                       uint32_t*, uint32_t*, uint2*, uint32_t, uint32_t*, SureRuns);
+DDEF_EF_FILTER_INSTANCE(false, false)
+DDEF_EF_FILTER_INSTANCE(false, true)
+DDEF_EF_FILTER_INSTANCE(true, false)
+DDEF_EF_FILTER_INSTANCE(true, true)
+#undef DDEF_EF_FILTER_INSTANCE
 
 // ------------------------------------------------------------------------------------
 // Random-k sparsifier (the paper's appendix on other sparsifiers): worker w keeps the k
@@ -728,6 +781,11 @@ __device__ __forceinline__ void begin_selection(SelState* sel, uint32_t w, uint3
 // least k entries: then the top-k is among the candidates, because every entry outside the
 // candidate set is smaller than every entry inside.  Otherwise sel[w].active = 1 sends the
 // worker's selection over its whole row.
+// With the sure / band split (sure_count non-null: the worker's kSubs slot counters of the sure
+// buffer, cleared here) the candidates are the band only: usable when nothing overflowed, fewer
+// than k entries are sure (S < k) and sure plus band hold at least k; the selection then looks for
+// rank k - S inside the band.  sure_total[w] = S (0 when the worker falls back), msg_count[w] =
+// how many entries the compaction will write to the worker's message row (k - S, or k).
 __global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_sum, uint32_t nspans,
                                                     const uint32_t* __restrict__ overflow, uint32_t k,
                                                     uint32_t kb, uint32_t d, uint32_t n,
@@ -735,7 +793,10 @@ __global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_
                                                     uint32_t* __restrict__ cand_total,
                                                     uint32_t* __restrict__ stat_full,
                                                     const uint32_t* __restrict__ zero_at,
-                                                    uint32_t* __restrict__ hist) {
+                                                    uint32_t* __restrict__ hist,
+                                                    uint32_t* __restrict__ sure_count,
+                                                    uint32_t* __restrict__ sure_total,
+                                                    uint32_t* __restrict__ msg_count) {
     __shared__ uint32_t lds[5];
     const uint32_t w = blockIdx.x;
     uint32_t* sw = span_sum + (uint64_t)w * nspans;
@@ -749,14 +810,43 @@ __global__ __launch_bounds__(256) void k_tab_decide(uint32_t* __restrict__ span_
         carry += total;
     }
     const uint32_t M = carry;
-    const bool usable = overflow[w] == 0u && M >= k;
+    uint32_t S = 0;
+    const bool split = sure_count != nullptr;
+    if (split) {                                 // blockDim.x == kSubs: one slot counter per thread
+        uint32_t* mine = &sure_count[(w * kSubs + threadIdx.x) * kSubStride];
+        const uint32_t v = *mine;
+        *mine = 0u;
+        (void)block_excl_scan(v, lds, &S);
+    }
+    const bool usable = overflow[w] == 0u && (split ? (S < k && M >= k - S) : M >= k);
+    const uint32_t rank = usable ? k - S : k;
     if (threadIdx.x == 0) {
         cand_total[w] = M;
         sel[w].active = usable ? 0u : 1u;
         sel[w].zero_used = zero_at[w];          // what the accumulate pass zeroed ahead of time
         if (!usable) stat_full[w] += 1u;
+        if (sure_total) sure_total[w] = (split && usable) ? S : 0u;
+        if (msg_count) msg_count[w] = rank;
     }
-    begin_selection(sel, w, n, k, kb, usable ? M : d, hist);
+    begin_selection(sel, w, n, rank, (split && usable) ? rank : kb, usable ? M : d, hist);
+}
+
+// A worker that falls back to its whole row although sure entries were recorded (and written to e
+// as +0 ahead of time) gets them back: one thread per 256-coordinate group walks the group's run.
+// grid (ceil(ngroups / 256), n); nothing to do for workers whose selection uses the candidates.
+__global__ __launch_bounds__(256) void k_restore_sure(const SelState* __restrict__ sel, SureRuns sp,
+                                                      uint32_t ngroups, float* __restrict__ e, uint64_t ld) {
+    const uint32_t w = blockIdx.y;
+    if (sel[w].active != 1u) return;
+    const uint32_t grp = blockIdx.x * blockDim.x + threadIdx.x;
+    if (grp >= ngroups) return;
+    const uint2 run = sp.stab[(uint64_t)w * ngroups + grp];
+    const uint2* sw = sp.sure + (uint64_t)w * sp.cap;
+    float* row = e + (uint64_t)w * ld;
+    for (uint32_t q = 0; q < run.y; ++q) {
+        const uint2 item = sw[run.x + q];
+        row[item.x] = __uint_as_float(item.y);
+    }
 }
 
 // No filter in this iteration: every worker searches its whole row.
@@ -1172,13 +1262,30 @@ __global__ __launch_bounds__(256) void k_sample_begin(SelState* __restrict__ sel
 }
 
 // One thread per worker: rank kb_s of the sample places the bound, rank k_s the expected threshold.
+// sure_at (may be null): the pattern from which a candidate counts as sure to be sent, as far above the
+// expected threshold as the bound lies below it (in pattern units, which follow the logarithm of the
+// magnitude closely enough over a few per cent): 2 T - L, at least T + 1, at most the largest finite pattern.
 __global__ __launch_bounds__(256) void k_sample_finish(const SelState* __restrict__ sel, uint32_t n,
                                                        uint32_t* __restrict__ bound,
-                                                       uint32_t* __restrict__ zero_at) {
+                                                       uint32_t* __restrict__ zero_at,
+                                                       uint32_t* __restrict__ sure_at, int sure_mode) {
     const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= n) return;
-    bound[w] = sel[w].next_bound;
-    zero_at[w] = sel[w].T;
+    const uint32_t L = sel[w].next_bound, T = sel[w].T;
+    bound[w] = L;
+    zero_at[w] = T;
+    if (sure_at) {
+        const uint64_t above = (uint64_t)T + (T > L ? T - L : 1u);
+        uint32_t at = above > 0x7f7fffffull ? 0x7f7fffffu : (uint32_t)above;
+        // test knobs: the line just above the expected threshold (k or more sure entries about every
+        // other time: the selection falls back to the row), at infinity (nothing is sure), below the
+        // expected threshold (always too many sure entries).  Fewer than k sure entries means the k-th
+        // largest lies below the line, so every sure entry is sent: the count alone decides.
+        if (sure_mode == 1) at = T + 1u;
+        if (sure_mode == 2) at = 0x7f800000u;
+        if (sure_mode == 3) at = T > L ? T - (T - L) / 2u : T + 1u;
+        sure_at[w] = at;
+    }
 }
 
 // One block of 1024 threads per worker walks the chunk counts in order and turns them into
@@ -1310,15 +1417,17 @@ __global__ __launch_bounds__(256) void k_chunk_emit(SelViews vs, const SelState*
 // inside one message are distinct, so the adds of one worker never collide), and writes the
 // tile out with coalesced stores.  U is overwritten as a whole: no clearing before or after,
 // and no scattered read-modify-write in HBM.
+// count (may be null) gives the length of each worker's row where it is not k for all of them.
 __global__ __launch_bounds__(256) void k_msg_offsets(const uint32_t* __restrict__ idx, uint64_t msg_ld,
                                                      uint32_t k, uint32_t ntiles,
-                                                     uint32_t* __restrict__ off) {
+                                                     uint32_t* __restrict__ off,
+                                                     const uint32_t* __restrict__ count) {
     const uint32_t w = blockIdx.y;
     const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b > ntiles) return;
     const uint32_t* row = idx + (uint64_t)w * msg_ld;
     const uint64_t edge = (uint64_t)b * kTile;             // may exceed 2^32 at the last boundary
-    uint32_t lo = 0, hi = k;                               // first position with row[pos] >= edge
+    uint32_t lo = 0, hi = count ? count[w] : k;            // first position with row[pos] >= edge
     while (lo < hi) {
         const uint32_t mid = lo + ((hi - lo) >> 1);
         if ((uint64_t)row[mid] < edge) lo = mid + 1u; else hi = mid;
@@ -1329,15 +1438,22 @@ __global__ __launch_bounds__(256) void k_msg_offsets(const uint32_t* __restrict_
 // With kApply the tile is not stored but used at once: xn = x - tile / n (S5 fused into S4), so
 // the dense update never goes through HBM.  When x and xn are the same row, only the entries
 // with a non-zero sum are touched.
+// With the sure / band split (sv.sure non-null) a worker's message has two parts: the row idx / val
+// holds what the compaction sent out of the band, and its sure entries lie in runs, one per
+// 256-coordinate group, named by the run table sv.stab (kTile / 256 runs per tile).  Both are added
+// in the worker's turn; the indices of one worker are distinct over both parts.
 template <bool kApply>
 __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
                                                          const uint32_t* __restrict__ idx,
                                                          const float* __restrict__ val, uint64_t msg_ld,
                                                          const uint32_t* __restrict__ off,
                                                          uint32_t ntiles, uint32_t n, ModelRows rows,
-                                                         float nf) {
+                                                         float nf, SureView sv) {
     __shared__ __attribute__((aligned(16))) float tile[kTile];
     __shared__ uint32_t lo_s[256], hi_s[256];
+    constexpr uint32_t kRuns = kTile / 256u;               // 16 runs per tile and worker
+    constexpr uint32_t kHoist = 256u / kRuns;              // workers whose runs one round of loads covers
+    __shared__ uint32_t run_first[256], run_at[kHoist * (kRuns + 1u)];
     const uint32_t b = blockIdx.x;
     const uint32_t base = b * kTile;
     for (uint32_t q = threadIdx.x; q < kTile; q += 256u) tile[q] = 0.0f;
@@ -1351,17 +1467,60 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
             hi_s[threadIdx.x] = o[1];
         }
         __syncthreads();
-        for (uint32_t i = 0; i < batch; ++i) {
-            const uint32_t* ri = idx + (uint64_t)(w0 + i) * msg_ld;
-            const float* rv = val + (uint64_t)(w0 + i) * msg_ld;
-            const uint32_t hi = hi_s[i];
-            if (lo_s[i] == hi) continue;                   // same for the whole block
-            entries += hi - lo_s[i];
-            for (uint32_t m = lo_s[i] + threadIdx.x; m < hi; m += 256u) {
-                const uint32_t at = ri[m] - base;          // < kTile by the choice of lo, hi
-                tile[at] = tile[at] + rv[m];
+        for (uint32_t i0 = 0; i0 < batch; i0 += kHoist) {
+            if (sv.sure != nullptr) {
+                // the run descriptors of the next kHoist workers in one round of loads: thread t takes
+                // run t % 16 of worker i0 + t / 16; prefix of the lengths inside each group of 16 lanes
+                const uint32_t wi = i0 + (threadIdx.x / kRuns), r = threadIdx.x % kRuns;
+                uint2 run = make_uint2(0u, 0u);
+                if (wi < batch && sv.total[w0 + wi] != 0u)
+                    run = sv.stab[(uint64_t)(w0 + wi) * sv.ngroups + (uint64_t)b * kRuns + r];
+                uint32_t incl = run.y;
+#pragma unroll
+                for (uint32_t step = 1; step < kRuns; step <<= 1) {
+                    const uint32_t up = __shfl_up(incl, step, kRuns);
+                    if (r >= step) incl += up;
+                }
+                run_first[threadIdx.x] = run.x;
+                run_at[(threadIdx.x / kRuns) * (kRuns + 1u) + r] = incl - run.y;
+                if (r == kRuns - 1u) run_at[(threadIdx.x / kRuns) * (kRuns + 1u) + kRuns] = incl;
+                __syncthreads();
             }
-            __syncthreads();
+            const uint32_t i1 = i0 + kHoist < batch ? i0 + kHoist : batch;
+            for (uint32_t i = i0; i < i1; ++i) {
+                bool added = false;                        // same for the whole block
+                if (sv.sure != nullptr) {
+                    const uint32_t* at_of = run_at + (i - i0) * (kRuns + 1u);
+                    const uint32_t* first_of = run_first + (i - i0) * kRuns;
+                    const uint32_t total = at_of[kRuns];
+                    entries += total;
+                    added |= total != 0u;
+                    const uint2* sw = sv.sure + (uint64_t)(w0 + i) * sv.cap;
+                    for (uint32_t q = threadIdx.x; q < total; q += 256u) {
+                        uint32_t r = 0;
+#pragma unroll
+                        for (uint32_t s = 1; s < kRuns; ++s) r += at_of[s] <= q;   // run holding entry q
+                        const uint2 item = sw[first_of[r] + (q - at_of[r])];
+                        const uint32_t at = item.x - base;
+                        tile[at] = tile[at] + __uint_as_float(item.y);
+                    }
+                }
+                const uint32_t lo = lo_s[i], hi = hi_s[i];
+                if (lo != hi) {
+                    const uint32_t* ri = idx + (uint64_t)(w0 + i) * msg_ld;
+                    const float* rv = val + (uint64_t)(w0 + i) * msg_ld;
+                    entries += hi - lo;
+                    added = true;
+                    for (uint32_t m = lo + threadIdx.x; m < hi; m += 256u) {
+                        const uint32_t at = ri[m] - base;  // < kTile by the choice of lo, hi
+                        tile[at] = tile[at] + rv[m];
+                    }
+                }
+                // the next worker's additions come after this one's (a worker's own entries, sure and
+                // band alike, name distinct coordinates and need no order among themselves)
+                if (added) __syncthreads();
+            }
+            if (sv.sure != nullptr) __syncthreads();       // the descriptors are overwritten next round
         }
     }
     if (kApply) {
@@ -1402,9 +1561,82 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
 }
 
 template __global__ void k_aggregate_tiles<false>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
-                                                  uint32_t, uint32_t, ModelRows, float);
+                                                  uint32_t, uint32_t, ModelRows, float, SureView);
 template __global__ void k_aggregate_tiles<true>(float*, const uint32_t*, const float*, uint64_t, const uint32_t*,
-                                                 uint32_t, uint32_t, ModelRows, float);
+                                                 uint32_t, uint32_t, ModelRows, float, SureView);
+
+// ---- a split message in its canonical form (inspection: ddef_get_message) -----------------------
+// Worker w's message is its sure runs plus the band part of its message row; the one list in
+// ascending coordinate order is put together tile by tile.  k_tile_sure_count: sure entries per
+// tile; k_tile_scan: their exclusive prefix (in place); k_message_merge: a block marks its tile's
+// entries of both parts in LDS, ranks them by coordinate and writes them at
+// (sure entries before the tile) + (band entries before the tile).
+__global__ __launch_bounds__(256) void k_tile_sure_count(SureView sv, uint32_t w, uint32_t ntiles,
+                                                         uint32_t* __restrict__ tile_count) {
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= ntiles) return;
+    constexpr uint32_t kRuns = kTile / 256u;
+    const uint2* runs = sv.stab + (uint64_t)w * sv.ngroups + (uint64_t)b * kRuns;
+    uint32_t total = 0;
+    for (uint32_t r = 0; r < kRuns; ++r) total += runs[r].y;
+    tile_count[b] = total;
+}
+
+__global__ __launch_bounds__(1024) void k_tile_scan(uint32_t* __restrict__ tile_count, uint32_t ntiles) {
+    __shared__ uint32_t lds[17];
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < ntiles; base += 1024u) {
+        const uint32_t b = base + threadIdx.x;
+        const uint32_t v = b < ntiles ? tile_count[b] : 0u;
+        uint32_t total;
+        const uint32_t before = carry + block_excl_scan(v, lds, &total);
+        if (b < ntiles) tile_count[b] = before;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_message_merge(SureView sv, uint32_t w, const uint32_t* __restrict__ idx,
+                                                       const float* __restrict__ val, uint64_t msg_ld,
+                                                       const uint32_t* __restrict__ off, uint32_t ntiles,
+                                                       const uint32_t* __restrict__ sure_before,
+                                                       uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
+                                                       uint32_t k) {
+    __shared__ float tile[kTile];
+    __shared__ uint32_t present[kTile / 32u];
+    __shared__ uint32_t lds[5];
+    const uint32_t b = blockIdx.x, base = b * kTile;
+    constexpr uint32_t kRuns = kTile / 256u;
+    for (uint32_t q = threadIdx.x; q < kTile / 32u; q += 256u) present[q] = 0u;
+    __syncthreads();
+    const uint2* runs = sv.stab + (uint64_t)w * sv.ngroups + (uint64_t)b * kRuns;
+    const uint2* sw = sv.sure + (uint64_t)w * sv.cap;
+    for (uint32_t r = 0; r < kRuns; ++r) {
+        const uint2 run = runs[r];
+        for (uint32_t q = threadIdx.x; q < run.y; q += 256u) {
+            const uint2 item = sw[run.x + q];
+            const uint32_t at = item.x - base;
+            tile[at] = __uint_as_float(item.y);
+            atomicOr(&present[at >> 5], 1u << (at & 31u));
+        }
+    }
+    const uint32_t* o = off + (uint64_t)w * (ntiles + 1u) + b;
+    const uint32_t lo = o[0], hi = o[1];
+    for (uint32_t m = lo + threadIdx.x; m < hi; m += 256u) {
+        const uint32_t at = idx[(uint64_t)w * msg_ld + m] - base;
+        tile[at] = val[(uint64_t)w * msg_ld + m];
+        atomicOr(&present[at >> 5], 1u << (at & 31u));
+    }
+    __syncthreads();
+    // thread t owns coordinates [16 t, 16 t + 16): half a presence word
+    const uint32_t mine = (present[threadIdx.x >> 1] >> ((threadIdx.x & 1u) * 16u)) & 0xffffu;
+    uint32_t total;
+    uint32_t pos = sure_before[b] + lo + block_excl_scan((uint32_t)__popc(mine), lds, &total);
+    for (uint32_t c = 0; c < 16u; ++c)
+        if ((mine >> c) & 1u) {
+            if (pos < k) { out_idx[pos] = base + threadIdx.x * 16u + c; out_val[pos] = tile[threadIdx.x * 16u + c]; }
+            ++pos;
+        }
+}
 
 // Last node of a captured iteration: t <- t + 1 in device memory.
 __global__ void k_advance(uint64_t* t_dev) {

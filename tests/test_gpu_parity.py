@@ -560,3 +560,40 @@ def test_checkpoint_and_resume_continue_bit_for_bit(ddef, oracle_mod, tau, graph
     q = ddef.Context(1000, 2, 1, queue_form=True)
     assert q.raw("set_step_index", 3) == ddef.ESTATE
     q.close()
+
+
+# --- dense messages: candidates sure to be sent bypass the selection ----------------------------
+@pytest.mark.parametrize("mode", [1, 2, 3, 4, 0])
+@pytest.mark.parametrize("d,n,delta", [(300_017, 3, 0.1), (70_001, 2, 0.3), (1_200_003, 4, 0.04)])
+def test_dense_messages_sure_and_band_split(ddef, oracle_mod, mode, d, n, delta):
+    """Messages dense enough for the filter bound to come from a sample of p in every iteration
+    (k/d > 1/32): candidates a margin above the expected threshold are recorded once and go to the
+    aggregation as runs, the band around the threshold goes through the selection.  Messages (put
+    together by the getter), thresholds, error buffers, update and model against the oracle; the test
+    modes put the line where about half, none or all of the selections must fall back to their rows."""
+    w = workloads.get("C1", d=d, n=n)
+    w = workloads.replace(w, seed=900 + mode, tau=1, tau_max=1)
+    lam, xstar, x0 = workloads.make_problem(w)
+    g = ddef.Context(w.d, w.n, w.tau_max)
+    o = oracle_mod.Oracle(w.d, w.n, w.tau_max, threads=w.n)
+    for h in (g, o):
+        h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        h.set_tau(w.tau)
+    g.set_option(ddef.OPT_DENSE_SPLIT, mode)
+    steps = 7
+    for t in range(steps):
+        g.step(delta, w.lr)
+        o.step(delta, w.lr)
+        assert_step_state_equal(g, o, w.n, what=("split", mode, t))
+        assert np.array_equal(bits(g.get_update()), bits(o.get_update())), ("split update", mode, t)
+        assert_model_equal(g, o, what=("split", mode, t))
+    fell_back = g.full_select_count()
+    real = (steps - w.tau) * w.n
+    if mode in (0, 1, 3):
+        assert fell_back == 0, fell_back
+    if mode == 4:
+        assert fell_back == real
+    if mode == 2 and d > 2 ** 20:          # (a shorter row is sampled whole: the expected threshold is the true one)
+        assert 0 < fell_back < real
+    g.close()
+    o.close()
