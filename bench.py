@@ -24,8 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# one plain (unpacked, unfused) vector instruction per lane and clock: 256 CUs x 64 lanes x 2.4 GHz
-VALU_NOMINAL_TINSTR = 256 * 64 * 2.4e9 / 1e12
+# Ceiling for vector ALU work, in lane-instructions per second: the chip's fp32 vector peak of
+# 157.3 TFLOP/s counts a fused multiply-add as two operations, i.e. 78.6e12 lane-instructions per
+# second (256 compute units x 128 fp32 lanes per clock x 2.4 GHz).  Integer, 64-bit and correctly
+# rounded division / square-root sequences issue no faster, so no kernel can exceed it.
+VALU_PEAK_TINSTR = 157.3 / 2.0
 # vector lane-instructions k_grad executes per noise draw, by noise kind: SQ_INSTS_VALU x 64 / draws
 # (profiles/k_grad_C3_valu.txt)
 VALU_PER_DRAW = {2: 162.2}
@@ -77,18 +80,50 @@ class HipEvents:
         self.hip.hipStreamDestroy(self.stream)
 
 
-def measured_traffic(kernel, workload_name, key="traffic_bytes_per_launch"):
-    """HBM bytes from the committed hardware-counter summary (rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE, scaled by the copy yardstick): per launch of `kernel`, or with another key the
-    figure the summary holds under it; None when there is none for this kernel and workload."""
+def source_digest():
+    """sha256 over the library's sources (csrc/ and the public header), in a fixed order: names the
+    code a hardware-counter summary under profiles/ was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2507_17346_amd", "csrc")
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "ddef.h")]:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def counter_summary(kernel, workload_name):
+    """The committed hardware-counter summary of `kernel` on a workload (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, scaled by the copy yardstick) as a dict of its `key: value` lines, or None."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload_name}_pmc.txt")
+    out = {}
     try:
         for line in open(path):
-            if line.startswith(key + ":"):
-                return float(line.split(":", 1)[1])
+            if ":" in line and not line.startswith((" ", "#", "\t")):
+                key, value = line.split(":", 1)
+                if key.replace("_", "").isalnum():
+                    out[key] = value.strip()
     except OSError:
-        pass
-    return None
+        return None
+    return out
+
+
+def measured_traffic(kernel, workload_name, key="traffic_bytes_per_launch"):
+    """(bytes, provenance): HBM bytes the counters saw, from the committed summary -- but only if that
+    summary was measured on the very sources this run was built from (its source_digest line equals
+    source_digest()); otherwise (None, provenance), so that a figure from older code is never
+    passed off as this run's."""
+    summary = counter_summary(kernel, workload_name)
+    if not summary or key not in summary:
+        return None, None
+    prov = {"file": f"profiles/{kernel}_{workload_name}_pmc.txt", "commit": summary.get("commit"),
+            "box": summary.get("box"), "source_digest": summary.get("source_digest"),
+            "current_source_digest": source_digest()}
+    prov["matches_this_build"] = prov["source_digest"] == prov["current_source_digest"]
+    if not prov["matches_this_build"]:
+        return None, prov
+    return float(summary[key]), prov
 
 
 def log(*a):
@@ -144,7 +179,7 @@ def host_description():
     return {"cpu_model": model, "logical_cpus": os.cpu_count() or 1, "usable_cpus": usable}
 
 
-def describe(w, sched, k_of=None):
+def describe(w, sched, k_of):
     noise = {0: "no noise", 1: f"Gaussian noise x{w.noise_scale}", 2: f"Student-t3 noise x{w.noise_scale}"}[w.noise_kind]
     if w.adaptive_period > 0:
         pairs = sorted({sched(t) for t in range(0, w.steps, w.adaptive_period)})
@@ -152,7 +187,7 @@ def describe(w, sched, k_of=None):
     elif len(w.deltas) > 1:
         ratio = f"delta swept over {list(w.deltas)} in segments of {w.steps} iterations, tau={w.tau}"
     else:
-        ratio = f"delta={w.deltas[0]} (k={k_of(w.deltas[0]) if k_of else w.k()}), tau={w.tau}"
+        ratio = f"delta={w.deltas[0]} (k={k_of(w.deltas[0])}), tau={w.tau}"
     return f"{w.name}: d={w.d} fp32, n={w.n} workers, {ratio}, lr={w.lr}, {noise}, seed {w.seed}"
 
 
@@ -204,7 +239,12 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
     ap.add_argument("--cpu-sample-d", type=int, default=None)
+    ap.add_argument("--print-source-digest", action="store_true",
+                    help="print the digest of the library's sources (for a counter summary under profiles/) and exit")
     args = ap.parse_args()
+    if args.print_source_digest:
+        print(source_digest())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all workers' shares resident in one HBM); "
                  "--gpus N with N > 1 is not supported")
@@ -217,7 +257,7 @@ def main():
         w = workloads.replace(w, deltas=(args.delta,), adaptive_period=0, tau=w.tau if w.adaptive_period == 0 else 8)
     sched = make_schedule(w, binding, workloads)
     delta = sched(0)[1]
-    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (Top-k of the whole row: k={w.k(delta)}) tau={sched(0)[0]} lr={w.lr} "
+    log(f"workload {w.name}: d={w.d} n={w.n} delta={delta} (Top-k of the whole row: k={binding.k_from_delta(delta, w.d)}) tau={sched(0)[0]} lr={w.lr} "
         f"noise kind {w.noise_kind} scale {w.noise_scale} seed {w.seed}")
     t0 = time.perf_counter()
     lam, xstar, x0 = workloads.make_problem(w)
@@ -236,7 +276,7 @@ def main():
         """entries per worker in a message, as a share of d"""
         if args.compressor == "composed":
             return binding.k_from_delta(dl, binding.k_from_delta(args.rand_ratio, w.d)) / w.d
-        return w.k(dl) / w.d
+        return binding.k_from_delta(dl, w.d) / w.d
     ctx.set_option(binding.OPT_PREFETCH_GRAD, 1 if args.prefetch else 0)
     ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
     ctx.set_option(binding.OPT_GRAPH, 1 if args.graph else 0)
@@ -347,17 +387,19 @@ def main():
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "copy_kernel_GBps": copy_gbps,
                 "frac_of_copy_kernel": achieved / copy_gbps,
-                "traffic": measured_traffic(dominant, w.name) if args.d is None else None,
+                "traffic": None, "traffic_source": None,
                 "algorithmic_bytes_per_launch": algo_bytes,
                 "avg_launch_ms": kernels[dominant]["avg_ms"]}
+    if args.d is None:
+        roofline["traffic"], roofline["traffic_source"] = measured_traffic(dominant, w.name)
 
     if dominant == "k_ef_filter_fused" and w.noise_kind in VALU_PER_DRAW:
         # with the generator fused in, the pass is bound by vector issue like k_grad: lane-instructions
         # per element = k_grad's per draw + k_ef_filter's 82 wave instructions per 256 coordinates
         per_elem_instr = VALU_PER_DRAW[w.noise_kind] + 82.1 * 64.0 / 256.0
         rate = per_elem_instr * elems / (kernels[dominant]["avg_ms"] * 1e-3) / 1e12
-        roofline = {"bound": "alu", "kernel": dominant, "achieved": rate, "peak": VALU_NOMINAL_TINSTR,
-                    "unit": "T lane-instr/s", "frac": rate / VALU_NOMINAL_TINSTR, "traffic": None,
+        roofline = {"bound": "alu", "kernel": dominant, "achieved": rate, "peak": VALU_PEAK_TINSTR,
+                    "unit": "T lane-instr/s", "frac": rate / VALU_PEAK_TINSTR, "traffic": None,
                     "lane_instr_per_element": per_elem_instr, "avg_launch_ms": kernels[dominant]["avg_ms"],
                     "hbm_GBps": 4.0 * elems * 2 / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9}
 
@@ -372,7 +414,8 @@ def main():
         if w.noise_kind in VALU_PER_DRAW:
             grad_info["valu_lane_instr_per_draw"] = VALU_PER_DRAW[w.noise_kind]
             grad_info["valu_T_lane_instr_per_s"] = VALU_PER_DRAW[w.noise_kind] * elems / g_s / 1e12
-            grad_info["nominal_valu_T_lane_instr_per_s"] = VALU_NOMINAL_TINSTR
+            grad_info["peak_valu_T_lane_instr_per_s"] = VALU_PEAK_TINSTR
+            grad_info["frac_of_valu_peak"] = grad_info["valu_T_lane_instr_per_s"] / VALU_PEAK_TINSTR
 
     # metric of the path proper (EF + top-k + aggregate + apply), gradient generation aside
     path_ms = gpu_ms["ef_compress"] + gpu_ms["aggregate"] + gpu_ms["apply_delayed"]
@@ -387,7 +430,7 @@ def main():
     counted = None
     if args.d is None and args.delta is None and args.compressor == "topk" and not (
             args.fuse_grad or args.prefetch or args.queue_form):
-        counted = measured_traffic("k_ef_filter", w.name, key="path_traffic_bytes_per_step")
+        counted, _ = measured_traffic("k_ef_filter", w.name, key="path_traffic_bytes_per_step")
     if counted:
         path["measured_bytes_per_step"] = counted
         path["measured_bytes_per_worker_element"] = counted / elems

@@ -237,6 +237,14 @@ int ddef_deco(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32
 int ddef_deco_noniid(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t* tau,
                      double* delta);
 double ddef_phi_prime(double delta, double tau);
+/* The two corners of the (tau, delta) plane that Algorithm 3's joint choice is measured against
+ * (Section 2.2: compression alone, delayed aggregation alone), placed by the same two quantities
+ * the algorithm scans between.  Compression only: tau = 0 and the ratio whose transfer takes one
+ * computation time, delta = min{T_comp a / V_g, 1}.  Delay only: delta = 1 and the staleness at
+ * which Algorithm 3's scan starts, tau = ceil((b + V_g / a) / T_comp), at most tau_max. */
+int ddef_corner_compression_only(double v_g_bits, double a_bps, double t_comp_s, double* delta);
+int ddef_corner_delay_only(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t tau_max,
+                           uint32_t* tau);
 /* DeCo's objective phi(delta, tau) = (1 - delta) / (delta (1 - delta/2)^tau) (Theorems 1 and 2,
  * Algorithm 3); NaN outside 0 < delta <= 1, tau >= 0. */
 double ddef_phi(double delta, double tau);

@@ -38,6 +38,8 @@ SIGNATURES = {
     "ddef_set_heterogeneity": (C.c_int, [_ctx, C.c_float]),
     "ddef_deco_noniid": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, _u32p, C.POINTER(C.c_double)]),
     "ddef_phi_prime": (C.c_double, [C.c_double, C.c_double]),
+    "ddef_corner_compression_only": (C.c_int, [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]),
+    "ddef_corner_delay_only": (C.c_int, [C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint32, _u32p]),
     "ddef_grad": (C.c_int, [_ctx]),
     "ddef_load_grad": (C.c_int, [_ctx, C.c_uint32, _f32p]),
     "ddef_ef_compress": (C.c_int, [_ctx, C.c_double, C.c_float]),
@@ -147,6 +149,23 @@ def ef_compress_static(dev_e: int, dev_g: int, ld: int, d: int, n: int, delta: f
                                               float(delta), float(lr), C.c_void_p(int(dev_msg_idx)),
                                               C.c_void_p(int(dev_msg_val)), int(msg_ld),
                                               C.c_void_p(int(hip_stream)) if hip_stream else None))
+
+
+def corner_compression_only(v_g_bits: float, a_bps: float, t_comp_s: float) -> float:
+    delta = C.c_double()
+    rc = load().ddef_corner_compression_only(float(v_g_bits), float(a_bps), float(t_comp_s), C.byref(delta))
+    if rc != OK:
+        raise DdefError(rc, "ddef_corner_compression_only")
+    return float(delta.value)
+
+
+def corner_delay_only(v_g_bits: float, a_bps: float, b_s: float, t_comp_s: float, tau_max: int) -> int:
+    tau = C.c_uint32()
+    rc = load().ddef_corner_delay_only(float(v_g_bits), float(a_bps), float(b_s), float(t_comp_s), int(tau_max),
+                                       C.byref(tau))
+    if rc != OK:
+        raise DdefError(rc, "ddef_corner_delay_only")
+    return int(tau.value)
 
 
 def phi_prime(delta: float, tau: float) -> float:

@@ -71,6 +71,24 @@ int ddef_deco_noniid(double v_g_bits, double a_bps, double b_s, double t_comp_s,
     return deco_scan(true, v_g_bits, a_bps, b_s, t_comp_s, tau, delta);
 }
 
+int ddef_corner_compression_only(double v_g_bits, double a_bps, double t_comp_s, double* delta) {
+    if (!delta) return DDEF_EINVAL;
+    if (!positive_finite(v_g_bits) || !positive_finite(a_bps) || !positive_finite(t_comp_s)) return DDEF_EINVAL;
+    const double one_slot = t_comp_s * a_bps / v_g_bits;     // share of the gradient one T_comp carries
+    *delta = one_slot > 1.0 ? 1.0 : one_slot;
+    return DDEF_OK;
+}
+
+int ddef_corner_delay_only(double v_g_bits, double a_bps, double b_s, double t_comp_s, uint32_t tau_max,
+                           uint32_t* tau) {
+    if (!tau) return DDEF_EINVAL;
+    if (!positive_finite(v_g_bits) || !positive_finite(a_bps) || !positive_finite(t_comp_s)) return DDEF_EINVAL;
+    if (!std::isfinite(b_s) || b_s < 0.0) return DDEF_EINVAL;
+    const double slots = std::ceil((b_s + v_g_bits / a_bps) / t_comp_s);     // where Algorithm 3's scan starts
+    *tau = slots > (double)tau_max ? tau_max : (uint32_t)slots;
+    return DDEF_OK;
+}
+
 double ddef_t_avg_model(uint32_t tau, double delta, double v_g_bits, double a_bps, double b_s, double t_comp_s) {
     const double transfer = delta * v_g_bits / a_bps;
     double t = (t_comp_s + b_s + transfer) / ((double)tau + 1.0);

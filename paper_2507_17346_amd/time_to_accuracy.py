@@ -4,14 +4,13 @@ The paper's end-to-end figure of merit (Section 5: training time until a target 
 iterations-to-accuracy times the average iteration time T_avg.  Here the iterations come from
 the DD-EF-SGD path on the GPU (Algorithm 1 on the synthetic objective of problem (1)), and T_avg
 from the pipeline recurrence of Section 4.1 / Theorem 3 for a network of bandwidth a and latency
-b.  `strategies` names the corners of the (tau, delta) plane the paper compares: D-SGD
-(tau = 0, delta = 1), compression only, delay only, the static composed compressor with tau = 1
-that Section 5.1 gives for its strongest baseline, and DeCo's joint choice (Algorithm 3).
+b.  `strategies` names the corners of the (tau, delta) plane: D-SGD (tau = 0, delta = 1),
+compression only, delay only, and DeCo's joint choice (Algorithm 3); every (tau, delta) comes from
+the library (ddef_corner_*, ddef_deco), this module only runs them.
 
     python -m paper_2507_17346_amd.time_to_accuracy --d 1000000 --n 4 --a-mbps 100 --b 0.2
 """
 import argparse
-import math
 from dataclasses import dataclass
 from typing import List, Optional, Tuple
 
@@ -30,14 +29,7 @@ class Network:
 class Strategy:
     name: str
     tau: int
-    delta: float                         # ddef_ef_compress's ratio
-    compressor: int = binding.COMPRESSOR_TOPK
-    rand_ratio: float = 0.2              # composed compressor only
-    wire_ratio: Optional[float] = None   # share of V_g that crosses the wire; None: delta
-
-    @property
-    def on_wire(self) -> float:
-        return self.delta if self.wire_ratio is None else self.wire_ratio
+    delta: float                         # ddef_ef_compress's ratio = share of V_g that crosses the wire
 
 
 @dataclass
@@ -50,16 +42,12 @@ class Outcome:
 
 
 def strategies(net: Network, tau_max: int) -> List[Strategy]:
-    """D-SGD; compression only (tau = 0, the ratio whose transfer takes one T_comp); delay only
-    (delta = 1, enough staleness to cover latency and a whole gradient, clamped to tau_max);
-    DeCo (Algorithm 3), clamped to tau_max."""
+    """D-SGD; compression only and delay only (ddef_corner_*); DeCo (Algorithm 3), clamped to tau_max."""
     out = [Strategy("D-SGD", 0, 1.0)]
-    out.append(Strategy("compression only", 0, min(1.0, net.t_comp_s * net.a_bps / net.v_g_bits)))
-    hide = math.ceil((net.b_s + net.v_g_bits / net.a_bps) / net.t_comp_s)
-    out.append(Strategy("delay only", int(min(tau_max, hide)), 1.0))
-    # Section 5.1's static baseline: tau = 1, Random-k 20 %, Top-k 10 % of those, 4-bit values; as the
-    # paper counts delta * V_g bits for sparsified values, 2 % of the values at 4 of 32 bits each cross the wire
-    out.append(Strategy("static composed", min(1, tau_max), 0.1, binding.COMPRESSOR_COMPOSED, 0.2, 0.2 * 0.1 * 4.0 / 32.0))
+    out.append(Strategy("compression only", 0,
+                        binding.corner_compression_only(net.v_g_bits, net.a_bps, net.t_comp_s)))
+    out.append(Strategy("delay only",
+                        binding.corner_delay_only(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s, tau_max), 1.0))
     chosen = binding.deco(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
     if chosen is not None:
         out.append(Strategy("DeCo", int(min(tau_max, chosen[0])), float(chosen[1])))
@@ -68,7 +56,7 @@ def strategies(net: Network, tau_max: int) -> List[Strategy]:
 
 def t_avg(net: Network, s: Strategy, iterations: int = 2000) -> float:
     """Average iteration time of the pipeline of Section 4.1 (the recurrence, not the closed form)."""
-    return binding.t_avg_simulate(s.tau, s.on_wire, net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s, iterations)
+    return binding.t_avg_simulate(s.tau, s.delta, net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s, iterations)
 
 
 def run(w, s: Strategy, net: Network, target_ratio: float, max_iterations: int, check_every: int,
@@ -80,9 +68,6 @@ def run(w, s: Strategy, net: Network, target_ratio: float, max_iterations: int, 
     try:
         ctx.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
         ctx.set_tau(s.tau)
-        ctx.set_compressor(s.compressor)
-        if s.compressor == binding.COMPRESSOR_COMPOSED:
-            ctx.set_composed(s.rand_ratio)
         per_iteration = t_avg(net, s)
         f0 = ctx.objective()
         curve = [(0, 0.0, 1.0)]
@@ -121,12 +106,13 @@ def run_adaptive(w, nets: List[Network], period: int, adaptive: bool, target_rat
         while t < max_iterations and reached is None:
             net = nets[p % len(nets)]
             if adaptive or first is None:
-                if lut is not None:
-                    tau, delta, _ = lut.query(net.a_bps)
-                else:
-                    tau, delta = binding.deco(net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
-                first = Strategy("DeCo-SGD" if adaptive else "DeCo, first period's choice kept",
-                                 int(min(tau_max, tau)), float(delta))
+                choice = lut.query(net.a_bps) if lut is not None else binding.deco(
+                    net.v_g_bits, net.a_bps, net.b_s, net.t_comp_s)
+                if choice is None and first is None:
+                    raise ValueError("Algorithm 3 has no candidate (tau, delta) for the first period's network")
+                if choice is not None:             # no candidate for this network: the choice in force stays
+                    first = Strategy("DeCo-SGD" if adaptive else "DeCo, first period's choice kept",
+                                     int(min(tau_max, choice[0])), float(choice[1]))
             ctx.set_tau(first.tau)
             for _ in range(period):
                 ctx.step(first.delta, w.lr)

@@ -43,11 +43,6 @@ class Workload:
     adaptive_period: int = 0         # >0: (delta, tau) re-chosen every this many steps
     note: str = ""
 
-    def k(self, delta: Optional[float] = None) -> int:
-        """Number of kept entries for a ratio: ceil(delta*d) in double, clamped to [1, d]."""
-        dl = self.deltas[0] if delta is None else delta
-        return int(min(self.d, max(1, int(np.ceil(np.float64(dl) * np.float64(self.d))))))
-
 
 WORKLOADS = {
     "C1": Workload("C1", 1_000_000, 4, (0.01,), 2, 2, 0.05, 20, 0, NOISE_GAUSS, 0.1),

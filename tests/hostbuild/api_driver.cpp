@@ -281,6 +281,14 @@ static void deco_calls() {
         CHECK(ddef_t_avg_simulate(tau, delta, v_g, a, b, 0.02, 500) > 0.0);
         CHECK(ddef_t_avg_simulate(tau, delta, v_g, a, b, 0.02, 1) > 0.0);
     }
+    double only = 0.0;
+    uint32_t hide = 0;
+    CHECK(ddef_corner_compression_only(v_g, 1e8, 0.02, &only) == DDEF_OK && only > 0.0 && only < 1.0);
+    CHECK(ddef_corner_compression_only(v_g, 1e12, 0.02, &only) == DDEF_OK && only == 1.0);
+    CHECK(ddef_corner_delay_only(v_g, 1e8, 0.1, 0.02, 16, &hide) == DDEF_OK && hide == 16);
+    CHECK(ddef_corner_delay_only(v_g, 1e12, 0.01, 0.02, 16, &hide) == DDEF_OK && hide == 1);
+    CHECK(ddef_corner_delay_only(v_g, 0.0, 0.1, 0.02, 16, &hide) == DDEF_EINVAL);
+    CHECK(ddef_corner_compression_only(v_g, 1e8, 0.02, nullptr) == DDEF_EINVAL);
     ddef_lut* lut = nullptr;
     CHECK(ddef_lut_build(v_g, 1e8, 1e10, 20, 0.1, 0.02, &lut) == DDEF_OK);
     for (double a : {5e7, 1e8, 1.234e9, 9.99e9, 1e10, 2e10}) {

@@ -12,6 +12,10 @@ from paper_2507_17346_amd import binding, workloads
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+STATED_K = {("C1", 0.01): 10_000, ("C2", 0.01): 117_000, ("C3", 0.001): 124_000,
+            ("C4", 0.1): 130_000_000, ("C4", 0.01): 13_000_000, ("C4", 0.001): 1_300_000}   # as the workloads state them
+
+
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "ddef.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -55,7 +59,7 @@ def test_k_from_delta_matches_oracle(oracle_mod):
     for name in ("C1", "C2", "C3", "C4"):
         w = workloads.get(name)
         for dl in w.deltas:
-            assert binding.k_from_delta(dl, w.d) == w.k(dl)
+            assert binding.k_from_delta(dl, w.d) == STATED_K[(name, dl)]
     assert binding.k_from_delta(0.0, 10) == 0 and binding.k_from_delta(1.5, 10) == 0
     assert binding.k_from_delta(float("nan"), 10) == 0
 

@@ -148,7 +148,7 @@ def test_c4_full_size_one_worker_against_the_oracle(ddef, oracle_mod):
             continue
         gi, gv = g.get_message(0)
         oi, ov = o.get_message(0)
-        assert len(gi) == w.k(delta)
+        assert len(gi) == ddef.k_from_delta(delta, w.d)
         assert np.array_equal(gi, oi), ("C4 indices", t)
         assert np.array_equal(bits(gv), bits(ov)), ("C4 values", t)
         assert g.get_threshold(0) == o.get_threshold(0), ("C4 threshold", t)
@@ -177,7 +177,7 @@ def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
     e_prev = {i: np.zeros(len(sample), dtype=F32) for i in watched}
     for t in range(2 * w.tau + 1):
         delta = schedule.get(t, 0.001)
-        k = w.k(delta)
+        k = ddef.k_from_delta(delta, w.d)
         # the first real iteration searches the whole rows (the path without the candidate filter),
         # the others go through the filter, whose first bounds come from a sample of p
         g.set_option(ddef.OPT_FORCE_FULL_SELECT, 1 if t == w.tau else 0)

@@ -8,6 +8,10 @@ import pytest
 from paper_2507_17346_amd import workloads
 
 
+STATED_K = {("C1", 0.01): 10_000, ("C2", 0.01): 117_000, ("C3", 0.001): 124_000,
+            ("C4", 0.1): 130_000_000, ("C4", 0.01): 13_000_000, ("C4", 0.001): 1_300_000}   # as the workloads state them
+
+
 def key_of(p):
     return np.asarray(p, dtype=np.float32).view(np.uint32) & np.uint32(0x7FFFFFFF)
 
@@ -102,4 +106,4 @@ def test_k_from_delta(oracle_mod):
     for name in ["C1", "C2", "C3", "C4"]:
         w = workloads.get(name)
         for dl in w.deltas:
-            assert oracle_mod.k_from_delta(dl, w.d) == w.k(dl)
+            assert oracle_mod.k_from_delta(dl, w.d) == STATED_K[(name, dl)]

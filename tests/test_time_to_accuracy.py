@@ -23,10 +23,7 @@ def test_strategies_and_their_iteration_times():
     assert tta.t_avg(net, ss["compression only"]) == pytest.approx(0.02 + 0.02 + 0.1, rel=1e-3)
     assert tta.t_avg(net, ss["delay only"]) == pytest.approx(0.32, rel=2e-2)
     assert tta.t_avg(net, ss["DeCo"]) == pytest.approx(0.02, rel=2e-2)
-    # the static baseline: one iteration of staleness hides half of (T_comp + b + transfer)
-    sc = ss["static composed"]
-    assert (sc.tau, sc.delta, sc.on_wire) == (1, 0.1, pytest.approx(0.0025))
-    assert tta.t_avg(net, sc) == pytest.approx((0.02 + 0.1 + 0.0025 * 0.32) / 2.0, rel=2e-2)
+    assert set(ss) == {"D-SGD", "compression only", "delay only", "DeCo"}
 
 
 def test_a_fast_network_needs_neither():
