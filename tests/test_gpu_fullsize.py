@@ -76,45 +76,50 @@ def test_c3_full_size_bench_configuration(ddef, oracle_mod):
     assert used >= w.n                # at least the last iterations ran through the filter
 
 
-def test_c5_full_size_across_a_change_of_tau_and_delta(ddef, oracle_mod):
-    """The adaptive workload at its real shape (d = 124e6, n = 16, ring of 17 snapshots): the last
-    iterations of DeCo's first period and the first of its second, i.e. across a change of both tau
-    and delta (re-placed filter bound, messages of a different length), against the oracle."""
+def test_c5_full_size_across_changes_of_tau_and_delta(ddef, oracle_mod):
+    """The adaptive workload at its real shape (d = 124e6, n = 16, ring of 17 snapshots) against the
+    oracle over five of the ten periods of its DeCo schedule, two real iterations each: tau rises
+    (6 -> 9), falls (9 -> 2), reaches the ring's full depth (16) and falls again (16 -> 10), while
+    delta moves between 0.0013 and 0.036 -- sparse messages whose filter bound follows the last
+    thresholds, messages dense enough for a bound sampled in every iteration (delta = 0.008, 0.0105),
+    and dense ones whose sure candidates bypass the selection (delta = 0.036 > 1/32).  Every change
+    re-places the filter bound and changes the length of the messages."""
     w = workloads.get("C5")
     trace = workloads.network_trace(w)
     plan = []
-    for p in range(2):
+    for p in (0, 1, 2, 3, 7):
         tau, delta = ddef.deco(trace.v_g_bits, trace.bandwidth_bps[p], trace.latency_s[p], trace.t_comp_s)
         plan.append((int(np.clip(tau, *trace.tau_bounds)), float(np.clip(delta, *trace.delta_bounds))))
-    (tau1, delta1), (tau2, delta2) = plan
-    assert (tau1, delta1) != (tau2, delta2)
+    taus = [tau for tau, _ in plan]
+    assert taus[1] > taus[0] and taus[2] < taus[1] and taus[3] == w.tau_max and taus[4] < taus[3]
+    assert any(ddef.k_from_delta(delta, w.d) * 32 > w.d for _, delta in plan)
     lam, xstar, x0 = workloads.make_problem(w)
     g = ddef.Context(w.d, w.n, w.tau_max)
     o = oracle_mod.Oracle(w.d, w.n, w.tau_max, threads=w.n)
     for h in (g, o):
         h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
-    # period 1: tau1 empty iterations, then two real ones; period 2 starts at t = tau1 + 2 and runs
-    # until it has produced two real iterations as well (t - tau2 >= 0)
-    switch = tau1 + 2
-    last = max(switch, tau2) + 2
-    real = 0
-    for t in range(last):
-        tau, delta = (tau1, delta1) if t < switch else (tau2, delta2)
-        for h in (g, o):
-            h.set_tau(tau)
-            h.step(delta, w.lr)
-        if t >= tau:
-            real += 1
-            for i in (0, 7, w.n - 1):
-                gi, gv = g.get_message(i)
-                oi, ov = o.get_message(i)
-                assert np.array_equal(gi, oi), ("C5", t, i)
-                assert np.array_equal(bits(gv), bits(ov)), ("C5", t, i)
-            assert np.array_equal(bits(g.get_model()), bits(o.get_model())), ("C5 model", t)
-    assert real >= 4
-    for i in (0, w.n - 1):
-        assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), ("C5 error buffer", i)
-    assert np.array_equal(bits(g.get_update()), bits(o.get_update()))
+    t = 0
+    for period, (tau, delta) in enumerate(plan):
+        real = 0
+        while real < 2:
+            for h in (g, o):
+                h.set_tau(tau)
+                h.step(delta, w.lr)
+            if t >= tau:
+                real += 1
+                print(f"C5 vs oracle: period {period} (tau {tau}, delta {delta:.5f}), iteration {t}", flush=True)
+                for i in (0, 7, w.n - 1):
+                    gi, gv = g.get_message(i)
+                    oi, ov = o.get_message(i)
+                    assert np.array_equal(gi, oi), ("C5", t, i)
+                    assert np.array_equal(bits(gv), bits(ov)), ("C5", t, i)
+                    assert g.get_threshold(i) == o.get_threshold(i), ("C5 threshold", t, i)
+                assert np.array_equal(bits(g.get_model()), bits(o.get_model())), ("C5 model", t)
+            t += 1
+        for i in (0, w.n - 1):
+            assert np.array_equal(bits(g.get_error(i)), bits(o.get_error(i))), ("C5 error buffer", period, i)
+        assert np.array_equal(bits(g.get_update()), bits(o.get_update())), ("C5 update", period)
+    assert g.full_select_count() < w.n          # (every change of k places its bound from a sample of p)
     g.close()
     o.close()
 

@@ -1,13 +1,60 @@
 """The allocation-free entry point ddef_ef_compress_static against ddef_ef_compress: same error
 buffers and gradients in, bit-identical messages and residuals out, on two calls in a row (the
 second on a smaller problem, so that whatever the first left in the shared work memory is in the
-way), through the C-ABI.  torch only provides the caller's device buffers and the stream."""
+way), through the C-ABI.  The caller's device buffers and stream come straight from the HIP runtime
+(the one the library itself runs on), through ctypes."""
+import ctypes as C
+
 import numpy as np
 import pytest
 
 pytestmark = pytest.mark.gpu
 
 F32 = np.float32
+
+
+class Hip:
+    """The few HIP runtime calls a caller of the entry point needs: buffers, copies, a stream."""
+
+    def __init__(self):
+        self.lib = C.CDLL("libamdhip64.so")
+        self.owned = []
+
+    def ok(self, rc, what):
+        assert rc == 0, f"{what} failed with HIP error {rc}"
+
+    def malloc(self, nbytes):
+        p = C.c_void_p()
+        self.ok(self.lib.hipMalloc(C.byref(p), C.c_size_t(nbytes)), "hipMalloc")
+        self.owned.append(p)
+        return p
+
+    def upload(self, array):
+        a = np.ascontiguousarray(array)
+        p = self.malloc(a.nbytes)
+        self.ok(self.lib.hipMemcpy(p, C.c_void_p(a.ctypes.data), C.c_size_t(a.nbytes), C.c_int(1)), "hipMemcpy")
+        return p
+
+    def download(self, p, shape, dtype):
+        out = np.empty(shape, dtype=dtype)
+        self.ok(self.lib.hipMemcpy(C.c_void_p(out.ctypes.data), p, C.c_size_t(out.nbytes), C.c_int(2)), "hipMemcpy")
+        return out
+
+    def stream(self):
+        s = C.c_void_p()
+        self.ok(self.lib.hipStreamCreateWithFlags(C.byref(s), C.c_uint(1)), "hipStreamCreateWithFlags")
+        return s
+
+    def sync(self):
+        self.ok(self.lib.hipDeviceSynchronize(), "hipDeviceSynchronize")
+
+    def release(self, stream=None):
+        self.sync()
+        if stream is not None:
+            self.lib.hipStreamDestroy(stream)
+        for p in self.owned:
+            self.lib.hipFree(p)
+        self.owned = []
 
 
 def bits(a):
@@ -31,30 +78,31 @@ def reference(ddef, e, g, delta, lr):
     return out
 
 
-def static_call(ddef, torch, e, g, delta, lr, pad, side_stream=False):
+def static_call(ddef, hip, e, g, delta, lr, pad, side_stream=False):
     n, d = e.shape
     ld = (d + 3) // 4 * 4 + 4 * pad
     k = ddef.k_from_delta(delta, d)
     msg_ld = k + 5
-    dev = torch.device("cuda:0")
-    e_t = torch.zeros((n, ld), dtype=torch.float32, device=dev)
-    g_t = torch.zeros((n, ld), dtype=torch.float32, device=dev)
-    e_t[:, :d] = torch.from_numpy(e).to(dev)
-    g_t[:, :d] = torch.from_numpy(g).to(dev)
-    idx_t = torch.full((n, msg_ld), 0x7FFFFFFF, dtype=torch.int32, device=dev)
-    val_t = torch.full((n, msg_ld), -1.0, dtype=torch.float32, device=dev)
-    torch.cuda.synchronize()
+    e_rows = np.zeros((n, ld), dtype=F32)
+    g_rows = np.zeros((n, ld), dtype=F32)
+    e_rows[:, :d] = e
+    g_rows[:, :d] = g
+    e_dev, g_dev = hip.upload(e_rows), hip.upload(g_rows)
+    idx_dev = hip.upload(np.full((n, msg_ld), 0x7FFFFFFF, dtype=np.uint32))
+    val_dev = hip.upload(np.full((n, msg_ld), -1.0, dtype=F32))
+    hip.sync()
     # the null stream, or a stream of the caller's own
-    owner = torch.cuda.Stream(device=dev) if side_stream else torch.cuda.current_stream()
-    stream = owner.cuda_stream
-    rc = ddef.ef_compress_static(e_t.data_ptr(), g_t.data_ptr(), ld, d, n, delta, lr, idx_t.data_ptr(),
-                                 val_t.data_ptr(), msg_ld, stream)
+    stream = hip.stream() if side_stream else None
+    rc = ddef.ef_compress_static(e_dev.value, g_dev.value, ld, d, n, delta, lr, idx_dev.value, val_dev.value, msg_ld,
+                                 stream.value if stream is not None else 0)
     assert rc == ddef.OK, ddef.strerror(rc)
-    torch.cuda.synchronize()
-    idx = idx_t.cpu().numpy().view(np.uint32)
-    val = val_t.cpu().numpy()
+    hip.sync()
+    idx = hip.download(idx_dev, (n, msg_ld), np.uint32)
+    val = hip.download(val_dev, (n, msg_ld), F32)
+    res = hip.download(e_dev, (n, ld), F32)
+    hip.release(stream)
     assert np.all(idx[:, k:] == 0x7FFFFFFF) and np.all(val[:, k:] == -1.0)      # nothing past k was written
-    return [((idx[i, :k].copy(), val[i, :k].copy()), e_t[i, :d].cpu().numpy()) for i in range(n)]
+    return [((idx[i, :k].copy(), val[i, :k].copy()), res[i, :d].copy()) for i in range(n)]
 
 
 def make_inputs(seed, n, d, ties):
@@ -70,18 +118,16 @@ def make_inputs(seed, n, d, ties):
 
 
 def test_static_entry_point_matches_ef_compress_twice_in_a_row():
-    torch = pytest.importorskip("torch")
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
     from paper_2507_17346_amd import binding as ddef
     ddef.load()
+    hip = Hip()
     # first call: several tiles and chunks, a ragged tail, ties at the threshold; second: smaller
-    # in d, n and k, straight after it on the same stream
+    # in d, n and k, straight after it (on a stream of the caller's own); third: a handful of entries
     cases = [(11, 3, 300_017, 0.06, True, 2), (12, 2, 70_001, 0.003, False, 0), (13, 1, 5, 0.4, False, 1)]
     for seed, n, d, delta, ties, pad in cases:
         e, g = make_inputs(seed, n, d, ties)
         lr = 0.05
-        got = static_call(ddef, torch, e, g, delta, lr, pad, side_stream=(seed == 12))
+        got = static_call(ddef, hip, e, g, delta, lr, pad, side_stream=(seed == 12))
         want = reference(ddef, e, g, delta, lr)
         for i in range(n):
             (gi, gv), ge = got[i]
@@ -92,15 +138,12 @@ def test_static_entry_point_matches_ef_compress_twice_in_a_row():
 
 
 def test_static_entry_point_rejects_what_it_cannot_hold():
-    torch = pytest.importorskip("torch")
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
     from paper_2507_17346_amd import binding as ddef
     ddef.load()
-    buf = torch.zeros(1024, dtype=torch.float32, device="cuda:0")
-    out_i = torch.zeros(1024, dtype=torch.int32, device="cuda:0")
-    out_v = torch.zeros(1024, dtype=torch.float32, device="cuda:0")
-    p, q, r = buf.data_ptr(), out_i.data_ptr(), out_v.data_ptr()
+    hip = Hip()
+    p = hip.upload(np.zeros(1024, dtype=F32)).value
+    q = hip.upload(np.zeros(1024, dtype=np.uint32)).value
+    r = hip.upload(np.zeros(1024, dtype=F32)).value
     call = lambda **kw: ddef.ef_compress_static(**{**dict(dev_e=p, dev_g=p, ld=1024, d=1000, n=1, delta=0.01, lr=0.05,
                                                           dev_msg_idx=q, dev_msg_val=r, msg_ld=1024), **kw})
     assert call() == ddef.OK
@@ -109,4 +152,4 @@ def test_static_entry_point_rejects_what_it_cannot_hold():
     assert call(ld=999) == ddef.EINVAL and call(ld=1002) == ddef.EINVAL
     assert call(dev_e=p + 4) == ddef.EINVAL
     assert call(msg_ld=9) == ddef.EINVAL and call(delta=0.0) == ddef.EINVAL and call(dev_g=0) == ddef.EINVAL
-    torch.cuda.synchronize()
+    hip.release()
