@@ -119,8 +119,7 @@ int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_
  * step = (largest magnitude in the block) / 7, code = value / step rounded to the nearest integer
  * (halves to even) inside [-7, 7], all codes 0 where step is 0.  Delta holds what the receiver
  * decodes, code * step (that is what ddef_get_message returns and the aggregation sums), so
- * e' = p - Delta keeps the coding error with everything not sent.  Ring form only.  Under this
- * compressor ddef_ef_compress waits for the stream once per iteration (DDEF_OPT_COMPOSED_BOUND).
+ * e' = p - Delta keeps the coding error with everything not sent.  Ring form only.
  * Only between iterations. */
 int ddef_set_compressor(ddef_ctx* ctx, int kind);
 /* Share of the coordinates the Random-k stage of the composed compressor keeps, in (0, 1].
@@ -291,8 +290,8 @@ int ddef_device_info(ddef_ctx* ctx, uint32_t* compute_units, uint32_t* wave_size
  * rewritten by the next ddef_grad anyway. */
 int ddef_copy_probe(ddef_ctx* ctx, uint64_t* bytes_each_way);
 /* How many worker selections so far took the multi-pass path over the whole vector
- * (counted over all workers and iterations since ddef_set_problem), plus n for every iteration
- * of the composed compressor that had to be repeated without its bound. */
+ * (counted over all workers and iterations since ddef_set_problem), plus one for every worker and
+ * iteration of the composed compressor whose recording pass had to be repeated without its bound. */
 int ddef_full_select_count(ddef_ctx* ctx, uint64_t* count);
 /* Diagnostics of a worker's last selection: the magnitude bound its candidate filter will use
  * next, how many candidates the filter caught this time, and whether the selection had to
@@ -326,11 +325,11 @@ int ddef_get_filter_state(ddef_ctx* ctx, uint32_t worker, uint32_t* next_bound, 
                               * unchanged.                                                          */
 #define DDEF_OPT_COMPOSED_BOUND 7 /* composed compressor: 1 (default) records only the kept entries above a
                               * bound placed from a sample of e + lr*g, which a few more than k of them
-                              * are expected to pass, and repeats the pass without the bound when fewer
-                              * than k did (ddef_ef_compress then waits for the stream once per
-                              * iteration to learn which); 0 always records every kept entry; 2 places
-                              * the bound too high on purpose (tests of the repeat).  Results are
-                              * unchanged.                                                          */
+                              * are expected to pass; for a worker where fewer than k did, the pass is
+                              * repeated without the bound (the repeat is enqueued every time and decided
+                              * on the device, so ddef_ef_compress does not wait for the stream); 0 always
+                              * records every kept entry; 2 places the bound too high on purpose (tests of
+                              * the repeat).  Results are unchanged.                                 */
 #define DDEF_OPT_DENSE_SPLIT 8 /* 1 (default): where messages are dense (k/d > 1/32; ring form, Top-k; the filter
                               * bound is then placed from a sample of e + lr*g in every iteration), the
                               * candidates a margin above the expected threshold count as

@@ -137,7 +137,6 @@ struct ddef_ctx {
     int64_t opt_force_full = 0, opt_slack_x16 = 40;
     int64_t opt_bucket_percent = 0;      // Random-k buckets: 0 = expected fill plus slack, else that share of it
     int64_t opt_composed_bound = 1;      // composed compressor: 1 record only the kept entries above a sampled bound
-    uint64_t composed_retries = 0;       //   and how often that had to be repeated without the bound
     // ddef_step as a captured graph: the launches of one steady iteration, replayed while
     // (k, lr, tau) stay the same.  Inside the graph the iteration number comes from t_dev.
     int64_t opt_graph = 0;
@@ -392,7 +391,7 @@ void enqueue_select(ddef_ctx* c, uint32_t k, uint32_t kb, int fix_e = 1) {
 // Sets the bits of the k coordinates Random-k keeps for this (iteration, worker) in the bitmap.
 // A few coordinates are set one atomic each; many are first sorted into buckets by coordinate
 // region (the candidate buffer, idle at this point, holds the buckets) and set region by region.
-int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
+int enqueue_randk_mark(ddef_ctx* c, uint64_t k, const SelState* gate = nullptr) {
     const uint32_t n = c->n;
     const uint64_t bitmap_ld = c->ld / 32u;
     if (!c->bitmap) {
@@ -414,7 +413,7 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
     if (!binned) {
         LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
                c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
-               (uint32_t)c->t, (uint32_t)(c->t >> 32));
+               (uint32_t)c->t, (uint32_t)(c->t >> 32), gate);
         return DDEF_OK;
     }
     if (!c->region_count) {
@@ -428,10 +427,10 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k) {
     LAUNCH(c, SL_RANDK_BIN, k_randk_bin, dim3(blocks_for(c, (k + 8191u) / 8192u, n, 2), n), dim3(1024), bucket,
            2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
            (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)c->t,
-           (uint32_t)(c->t >> 32));
+           (uint32_t)(c->t >> 32), gate);
     LAUNCH(c, SL_RANDK_FILL, k_randk_fill, dim3((uint32_t)regions, n), dim3(1024), (const uint32_t*)bucket,
            2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
-           (uint32_t)c->d);
+           (uint32_t)c->d, gate);
     return DDEF_OK;
 }
 
@@ -775,7 +774,6 @@ int ddef_set_problem(ddef_ctx* c, const float* host_lambda, const float* host_xs
     c->t = 0; c->phase = PH_IDLE; c->problem_set = true; c->step_empty = true; c->k_step = 0;
     c->q_key = 0; c->q_key_floor = 0;
     c->full_selects = 0;
-    c->composed_retries = 0;
     c->u_zero = true;
     c->agg_deferred = false;
     return DDEF_OK;
@@ -932,32 +930,29 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
             if (rc) return rc;
             bounded = c->have_bound;
         }
-        auto record = [&](bool with_bound, int accumulate) -> int {
-            int rcm = enqueue_randk_mark(c, k1);
+        // gate: a repeat pass, whose kernels run only for the workers the first pass flagged (active == 3)
+        auto record = [&](bool with_bound, int accumulate, const SelState* gate) -> int {
+            int rcm = enqueue_randk_mark(c, k1, gate);
             if (rcm) return rcm;
-            LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
+            const uint32_t gx = gate ? std::min<uint32_t>(c->nwc, (uint32_t)c->cus * 32u) : c->nwc;
+            LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(gx, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
                    accumulate, with_bound ? (const uint32_t*)bound : (const uint32_t*)nullptr, c->bitmap, bitmap_ld,
-                   c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+                   c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, gate);
             LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
-                   c->span_sum, c->nspans);
+                   c->span_sum, c->nspans, gate);
             LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
-                   (uint32_t)k1, (uint32_t)k, n, with_bound ? 0 : 1, c->sel, cand_total, cand_count, c->hist);
+                   (uint32_t)k1, (uint32_t)k, n, with_bound ? 0 : 1, c->sel, cand_total, cand_count, c->hist,
+                   stat_full, gate ? 1 : 0);
             return DDEF_OK;
         };
-        rc = record(bounded, 1);
+        rc = record(bounded, 1, nullptr);
         if (rc) return rc;
         if (bounded) {
-            // the device says whether every worker caught enough (one small copy per iteration)
-            std::vector<SelState> st(n);
-            HIP_TRY(c, hipStreamSynchronize(c->stream));
-            HIP_TRY(c, hipMemcpy(st.data(), c->sel, sizeof(SelState) * n, hipMemcpyDeviceToHost));
-            bool again = false;
-            for (const SelState& q : st) again |= q.active == 3u;
-            if (again) {
-                c->composed_retries += 1;
-                rc = record(false, 0);
-                if (rc) return rc;
-            }
+            // Whether every worker caught enough is known on the device only.  The repeat of the pass
+            // (over the stored p, without the bound) is therefore enqueued every time, and its
+            // kernels return at once for the workers that need none: no wait for the stream here.
+            rc = record(false, 0, c->sel);
+            if (rc) return rc;
         }
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                (const uint32_t*)c->span_sum, c->nspans, (const SelState*)c->sel, (const uint2*)c->cand, c->cap,
@@ -980,9 +975,10 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
         rc = enqueue_randk_mark(c, k);
         if (rc) return rc;
         LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(c->nwc, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 1,
-               1, (const uint32_t*)nullptr, c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n);
+               1, (const uint32_t*)nullptr, c->bitmap, bitmap_ld, c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n,
+               (const SelState*)nullptr);
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
-               c->span_sum, c->nspans);
+               c->span_sum, c->nspans, (const SelState*)nullptr);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_randk, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
                (uint32_t)k, c->sel, cand_total, cand_count);
         LAUNCH(c, SL_TAB_ORDER, k_tab_order, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
@@ -1042,7 +1038,7 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
     c->msg_split = split;
     if (use_filter) {
         LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
-               c->span_sum, c->nspans);
+               c->span_sum, c->nspans, (const SelState*)nullptr);
         LAUNCH(c, SL_TAB_DECIDE, k_tab_decide, dim3(n), dim3(256), c->span_sum, c->nspans,
                (const uint32_t*)overflow, (uint32_t)k, (uint32_t)kb, (uint32_t)c->d, n, c->sel, cand_total,
                stat_full, (const uint32_t*)zero_at, c->hist, split ? c->sure_count : (uint32_t*)nullptr,
@@ -1516,7 +1512,7 @@ int ddef_full_select_count(ddef_ctx* c, uint64_t* count) {
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     std::vector<uint32_t> fell_back(c->n, 0u);
     HIP_TRY(c, hipMemcpy(fell_back.data(), c->filt + 2 * c->n, (size_t)c->n * 4u, hipMemcpyDeviceToHost));
-    uint64_t total = c->full_selects + c->composed_retries * c->n;
+    uint64_t total = c->full_selects;
     for (uint32_t v : fell_back) total += v;
     *count = total;
     return DDEF_OK;

@@ -84,7 +84,7 @@ __global__ void k_ef_filter(float* e, const float* g, GradSource src, uint32_t n
                             float lr, const uint32_t* bound, const uint32_t* zero_at, int use_filter, uint2* cand, uint64_t cap,
                             uint32_t* cand_count, uint32_t* overflow, uint2* tab, uint32_t ngroups,
                             uint32_t* nonfinite, SureRuns sp);
-__global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans);
+__global__ void k_tab_sum(const uint2* tab, uint32_t nwc, uint32_t* span_sum, uint32_t nspans, const SelState* gate);
 __global__ void k_tab_decide(uint32_t* span_sum, uint32_t nspans, const uint32_t* overflow, uint32_t k,
                              uint32_t kb, uint32_t d, uint32_t n, SelState* sel, uint32_t* cand_total,
                              uint32_t* stat_full, const uint32_t* zero_at, uint32_t* hist, uint32_t* sure_count,
@@ -96,21 +96,24 @@ __global__ void k_tab_order(const uint2* tab, uint32_t ngroups, const uint32_t* 
                             const SelState* sel, const uint2* cand, uint64_t cap, uint32_t* sorted_idx,
                             float* sorted_val, uint64_t out_ld, float* e_row, uint64_t e_ld);
 __global__ void k_randk_mark(uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d, uint32_t k, uint32_t seed_lo,
-                             uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
+                             uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi, const SelState* gate);
 __global__ void k_randk_bin(uint32_t* bucket, uint64_t bucket_ld, uint32_t bucket_cap, uint32_t* gcount,
                             uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d,
-                            uint32_t k, uint32_t seed_lo, uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi);
+                            uint32_t k, uint32_t seed_lo, uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi,
+                            const SelState* gate);
 __global__ void k_randk_fill(const uint32_t* bucket, uint64_t bucket_ld, uint32_t bucket_cap, uint32_t* gcount,
-                             uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d);
+                             uint32_t region_bits, uint32_t regions, uint32_t* bitmap, uint64_t bitmap_ld, uint32_t d,
+                             const SelState* gate);
 __global__ void k_ef_randk(float* e, const float* g, uint64_t ld, uint32_t d, float lr, int zero_marked, int accumulate,
                            const uint32_t* bound, uint32_t* bitmap,
                            uint64_t bitmap_ld, uint2* cand, uint64_t cap, uint32_t* cand_count,
-                           uint32_t* overflow, uint2* tab, uint32_t ngroups, uint32_t* nonfinite);
+                           uint32_t* overflow, uint2* tab, uint32_t ngroups, uint32_t* nonfinite,
+                           const SelState* gate);
 __global__ void k_tab_decide_randk(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k,
                                    SelState* sel, uint32_t* cand_total, uint32_t* cand_count);
 __global__ void k_tab_decide_composed(uint32_t* span_sum, uint32_t nspans, uint32_t* overflow, uint32_t k1, uint32_t k,
                                       uint32_t n, int exact, SelState* sel, uint32_t* cand_total, uint32_t* cand_count,
-                                      uint32_t* hist);
+                                      uint32_t* hist, uint32_t* stat_repeat, int gated);
 __global__ void k_quantize4(const uint32_t* msg_idx, float* msg_val, uint64_t msg_ld, uint32_t k, const SelState* sel,
                             float* e, uint64_t ld, uint8_t* codes, uint64_t codes_ld, float* steps, uint64_t steps_ld);
 __global__ void k_digit_hist(SelViews vs, const SelState* sel, uint32_t* hist, int level);

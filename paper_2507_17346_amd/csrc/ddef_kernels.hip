@@ -518,8 +518,10 @@ __device__ __forceinline__ uint32_t randk_image(const RandkPerm& p, uint64_t m) 
 
 __global__ __launch_bounds__(256) void k_randk_mark(uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
                                                     uint32_t d, uint32_t k, uint32_t seed_lo,
-                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
+                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi,
+                                                    const SelState* __restrict__ gate) {
     const uint32_t w = blockIdx.y;
+    if (gate != nullptr && gate[w].active != 3u) return;       // a repeat pass: only the workers that ask for it
     const RandkPerm perm = randk_perm(w, d, seed_lo, seed_hi, t_lo, t_hi);
     uint32_t* row = bitmap + (uint64_t)w * bitmap_ld;
     for (uint32_t m = blockIdx.x * blockDim.x + threadIdx.x; m < k; m += gridDim.x * blockDim.x) {
@@ -541,11 +543,13 @@ __global__ __launch_bounds__(1024) void k_randk_bin(uint32_t* __restrict__ bucke
                                                     uint32_t region_bits, uint32_t regions,
                                                     uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
                                                     uint32_t d, uint32_t k, uint32_t seed_lo,
-                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi) {
+                                                    uint32_t seed_hi, uint32_t t_lo, uint32_t t_hi,
+                                                    const SelState* __restrict__ gate) {
     __shared__ uint32_t cnt[2048];
     __shared__ uint32_t base[2048];
     __shared__ uint32_t images[8192];         // images[i * 1024 + thread]: the thread's i-th image
     const uint32_t w = blockIdx.y;
+    if (gate != nullptr && gate[w].active != 3u) return;
     const RandkPerm perm = randk_perm(w, d, seed_lo, seed_hi, t_lo, t_hi);
     uint32_t* mine = bucket + (uint64_t)w * bucket_ld;
     const uint32_t chunks = (uint32_t)(((uint64_t)k + 8191u) >> 13);
@@ -609,9 +613,10 @@ __global__ __launch_bounds__(1024) void k_randk_fill(const uint32_t* __restrict_
                                                      uint32_t bucket_cap, uint32_t* __restrict__ gcount,
                                                      uint32_t region_bits, uint32_t regions,
                                                      uint32_t* __restrict__ bitmap, uint64_t bitmap_ld,
-                                                     uint32_t d) {
+                                                     uint32_t d, const SelState* __restrict__ gate) {
     __shared__ uint32_t bits[8192];
     const uint32_t w = blockIdx.y, r = blockIdx.x;
+    if (gate != nullptr && gate[w].active != 3u) return;
     uint32_t count = gcount[(uint64_t)w * regions + r];
     if (count > bucket_cap) count = bucket_cap;
     __syncthreads();
@@ -655,8 +660,12 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
                                                  uint32_t* __restrict__ cand_count,
                                                  uint32_t* __restrict__ overflow,
                                                  uint2* __restrict__ tab, uint32_t ngroups,
-                                                 uint32_t* __restrict__ nonfinite) {
-    const uint32_t w = blockIdx.y, grp = blockIdx.x, lane = threadIdx.x;
+                                                 uint32_t* __restrict__ nonfinite,
+                                                 const SelState* __restrict__ gate) {
+    const uint32_t w = blockIdx.y, lane = threadIdx.x;
+    if (gate != nullptr && gate[w].active != 3u) return;     // a repeat pass: only the workers that ask for it
+    // (one group per block in the main pass; a repeat pass is launched with fewer blocks, which stride)
+    for (uint32_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
     const uint32_t j = grp * 256u + lane * 4u;
     uint32_t* word = bitmap + (uint64_t)w * bitmap_ld + (j >> 5);
     const uint32_t bitsel = (*word >> (j & 31u)) & 0xfu;     // this lane's four coordinates
@@ -709,6 +718,7 @@ __global__ __launch_bounds__(64) void k_ef_randk(float* __restrict__ e, const fl
         }
     }
     if (lane == 0) tab[(uint64_t)w * ngroups + grp] = make_uint2(first, total);
+    }
 }
 
 // One block per worker: span sums -> span offsets; the runs must hold exactly k entries.
@@ -746,9 +756,11 @@ __global__ __launch_bounds__(256) void k_tab_decide_randk(uint32_t* __restrict__
 // also decides whether the filter caught enough, and the prefixes inside a span, which drive
 // the copy of the runs into coordinate order.
 __global__ __launch_bounds__(1024) void k_tab_sum(const uint2* __restrict__ tab, uint32_t ngroups,
-                                                  uint32_t* __restrict__ span_sum, uint32_t nspans) {
+                                                  uint32_t* __restrict__ span_sum, uint32_t nspans,
+                                                  const SelState* __restrict__ gate) {
     __shared__ uint32_t red[16];
     const uint32_t w = blockIdx.y, sp = blockIdx.x;
+    if (gate != nullptr && gate[w].active != 3u) return;       // (the other workers' sums are offsets by now)
     const uint32_t c = sp * kSpan + threadIdx.x;
     uint32_t mine = c < ngroups ? tab[(uint64_t)w * ngroups + c].y : 0u;
     mine = wave_sum(mine);
@@ -877,9 +889,11 @@ __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restric
                                                              SelState* __restrict__ sel,
                                                              uint32_t* __restrict__ cand_total,
                                                              uint32_t* __restrict__ cand_count,
-                                                             uint32_t* __restrict__ hist) {
+                                                             uint32_t* __restrict__ hist,
+                                                             uint32_t* __restrict__ stat_repeat, int gated) {
     __shared__ uint32_t lds[5];
     const uint32_t w = blockIdx.x;
+    if (gated && sel[w].active != 3u) return;   // a repeat pass: the worker's first verdict stands
     uint32_t* sw = span_sum + (uint64_t)w * nspans;
     uint32_t carry = 0;
     for (uint32_t first = 0; first < nspans; first += 256u) {
@@ -894,6 +908,7 @@ __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restric
     __syncthreads();                            // every thread has read the flag
     if (threadIdx.x == 0) {
         cand_total[w] = fine ? carry : 0u;
+        if (!fine && !exact) stat_repeat[w] += 1u;          // the pass is repeated without the bound for this worker
         sel[w].active = fine ? 0u : (exact ? 2u : 3u);
         sel[w].zero_used = 0xffffffffu;         // nothing was cleared ahead of time
         sel[w].seen = carry;
