@@ -1471,6 +1471,25 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
     __shared__ uint32_t run_first[256], run_at[kHoist * (kRuns + 1u)];
     const uint32_t b = blockIdx.x;
     const uint32_t base = b * kTile;
+    // the tile of x_t is asked for first, so that it travels while the messages are located and summed
+    // (not where one row is updated in place: there only the touched coordinates may be read at all)
+    const float* x = rows.x;
+    float* xn = rows.xn;
+    float4 xv[kTile / 1024u];
+    bool have_x = false;
+    if (kApply) {
+        if (rows.t_dev != nullptr) {
+            const uint64_t t = *rows.t_dev;
+            x = rows.ring + (t % rows.ring_slots) * rows.ring_ld;
+            xn = rows.ring + ((t + 1u) % rows.ring_slots) * rows.ring_ld;
+        }
+        if (x != xn) {
+            const float4* xin = reinterpret_cast<const float4*>(x + (uint64_t)base);
+#pragma unroll
+            for (uint32_t i = 0; i < kTile / 1024u; ++i) xv[i] = xin[threadIdx.x + i * 256u];
+            have_x = true;
+        }
+    }
     for (uint32_t q = threadIdx.x; q < kTile; q += 256u) tile[q] = 0.0f;
     uint32_t entries = 0;                                  // message entries that fall into this tile
     for (uint32_t w0 = 0; w0 < n; w0 += 256u) {
@@ -1539,13 +1558,6 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
         }
     }
     if (kApply) {
-        const float* x = rows.x;
-        float* xn = rows.xn;
-        if (rows.t_dev != nullptr) {
-            const uint64_t t = *rows.t_dev;
-            x = rows.ring + (t % rows.ring_slots) * rows.ring_ld;
-            xn = rows.ring + ((t + 1u) % rows.ring_slots) * rows.ring_ld;
-        }
         if (x == xn && entries < kTile / 64u) {
             // one model row updated in place (message-queue form) and few entries: only the
             // coordinates some message named can change, x - (+0)/n being x itself, so only those
@@ -1559,14 +1571,16 @@ __global__ __launch_bounds__(256) void k_aggregate_tiles(float* __restrict__ U,
         }
         const float4* xin = reinterpret_cast<const float4*>(x + (uint64_t)base);
         float4* xout = reinterpret_cast<float4*>(xn + (uint64_t)base);
-        for (uint32_t q = threadIdx.x; q < kTile / 4u; q += 256u) {
-            const float4 xv = xin[q];
+#pragma unroll
+        for (uint32_t i = 0; i < kTile / 1024u; ++i) {
+            const uint32_t q = threadIdx.x + i * 256u;
+            const float4 xq = have_x ? xv[i] : xin[q];
             const float4 uv = reinterpret_cast<const float4*>(tile)[q];
             float4 o;
-            o.x = xv.x - uv.x / nf;
-            o.y = xv.y - uv.y / nf;
-            o.z = xv.z - uv.z / nf;
-            o.w = xv.w - uv.w / nf;
+            o.x = xq.x - uv.x / nf;
+            o.y = xq.y - uv.y / nf;
+            o.z = xq.z - uv.z / nf;
+            o.w = xq.w - uv.w / nf;
             xout[q] = o;
         }
     } else {
