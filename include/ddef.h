@@ -109,7 +109,7 @@ int ddef_set_problem(ddef_ctx* ctx, const float* host_lambda, const float* host_
  * (half XOR round key), cycle-walked into [0, d), round keys from Philox4x32-10 with counter
  * (0xFFFFFFFF, worker, t).  Messages, error feedback and k = ceil(delta*d) are as for Top-k;
  * ddef_get_threshold reports (0, 0).
- * Composed is the compressor the paper gives for its strongest static baseline (Section 5.1
+ * Composed is the compressor the paper gives for its strongest static baseline (Section 5.2
  * "Baselines": Random-k with 20 %, Top-k with 10 %, 4-bit quantisation); the paper describes it no
  * further, the stages below are this library's reading.  (1) Random-k as above keeps
  * k1 = ceil(rand_ratio * d) coordinates (ddef_set_composed, default 0.2).  (2) Top-k keeps the
@@ -210,7 +210,7 @@ int ddef_get_update(ddef_ctx* ctx, float* host_U);   /* U of the last ddef_aggre
  * host_idx / host_val may be NULL to query k only; otherwise they hold at least k items. */
 int ddef_get_message(ddef_ctx* ctx, uint32_t worker, uint32_t* host_idx, float* host_val,
                      uint64_t* k);
-/* Wire form of a worker's last message under the composed compressor (Section 5.1 "Baselines",
+/* Wire form of a worker's last message under the composed compressor (Section 5.2 "Baselines",
  * 4-bit stage as read in ddef_set_compressor's comment): (k+1)/2 bytes of codes, entry 2m in the
  * low and entry 2m+1 in the high nibble of byte m, two's complement, a missing last entry 0; and
  * (k+255)/256 block steps.  Entry m decodes to code * steps[m / 256] at coordinate idx[m] of

@@ -16,7 +16,7 @@
 //   EF accumulate     p = e + gamma*g                         Algorithm 1, worker side
 //   compressor        Top-k of p, k = ceil(delta*d)           Section 5.2 "Baselines"; Top-k lemma
 //   other sparsifier  Random-k: k entries chosen at random    Appendix "Experiment Results with other sparsifiers"
-//   composed          Random-k, Top-k inside it, 4-bit codes  Section 5.1 "Baselines" (the strongest static baseline's compressor)
+//   composed          Random-k, Top-k inside it, 4-bit codes  Section 5.2 "Baselines" (the strongest static baseline's compressor)
 //   residual          e' = e + gamma*g - Delta                Algorithm 1, worker side
 //   server update     x' = x - (1/n) sum_i Delta_i            Algorithm 1, server side
 //   start-up          Delta_{t-tau} = 0 while t-tau < 0       Section 3.2, boundary convention
@@ -37,9 +37,11 @@
 // Theorem 3 against the recurrence.  The composed compressor (tests/test_oracle_composed.py):
 // its selection against a numpy sort of the Random-k subset, its quantiser against a hand-worked
 // block, the nearest-level property by brute force over all 15 levels, the case whose values lie
-// on the 4-bit grid (lossless: equals plain Top-k), conservation and the contraction.  Under a *changing* tau both forms are pinned at
-// delta = 1 (numpy replays of SGD with a time-varying delay) and by the invariants; with
-// delta < 1 the paper fixes no trajectory: parity unpinned for that case.
+// on the 4-bit grid (lossless: equals plain Top-k), conservation and the contraction.  Under a *changing* (tau, delta) -- Algorithm 2
+// re-chooses both while Algorithm 1 runs; the paper prints no trajectory for it -- both forms are
+// pinned against numpy replays written from the reading "iteration t uses what lies tau_t iterations
+// back": at delta = 1 (SGD with a time-varying delay) and at delta < 1 (error feedback and Top-k by a
+// full stable sort), messages, error buffers and iterates bit for bit (tests/test_oracle_step.py).
 #include <algorithm>
 #include <cmath>
 #include <cstdint>

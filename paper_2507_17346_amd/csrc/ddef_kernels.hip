@@ -872,7 +872,7 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 }
 
 // ---- composed compressor: Random-k, Top-k inside the kept coordinates, 4-bit codes ---------
-// (Section 5.1 "Baselines": the strongest static baseline's compressor.)  The Random-k pass above
+// (Section 5.2 "Baselines": the strongest static baseline's compressor.)  The Random-k pass above
 // records the k1 kept entries as runs and leaves e = p; the radix select of S2/S3 then runs on
 // those entries in coordinate order for rank k, as it does on a filter's candidates, and the
 // message it writes is coded below.

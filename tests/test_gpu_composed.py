@@ -1,5 +1,5 @@
 """GPU parity of the composed compressor (Random-k, Top-k inside the kept coordinates, 4-bit block
-codes; Section 5.1 "Baselines") with the oracle, through the C-ABI: index sets, packed codes and
+codes; Section 5.2 "Baselines") with the oracle, through the C-ABI: index sets, packed codes and
 block steps byte for byte, decoded values, error buffers, thresholds, update and model bit for bit."""
 import numpy as np
 import pytest

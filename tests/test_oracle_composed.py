@@ -1,7 +1,7 @@
 """Pins for the oracle's composed compressor: Random-k, Top-k inside the kept coordinates, 4-bit
-codes (Section 5.1 "Baselines": the compressor of the strongest static baseline, "Random-k with
-k = 20%, Top-k with k = 10% and using 4-bit quantization").  The paper says nothing more about
-it; the block rule of the quantiser is a reading, pinned here by a hand-worked block, by brute
+codes (Section 5.2 "Baselines": the compressor of the strongest static baseline, given there as the
+three stages with their ratios, 20 % and 10 %, and the code width, 4 bits).  The paper says nothing
+more about it; the block rule of the quantiser is a reading, pinned here by a hand-worked block, by brute
 force over all 15 levels, and by the case where quantisation loses nothing."""
 import os
 
