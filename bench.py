@@ -379,9 +379,11 @@ def main():
     copy_gbps = 2.0 * probe_bytes / (copy_ms / copy_cnt * 1e-3) / 1e9
     log(f"  copy yardstick k_copy_f4: {probe_bytes} bytes each way, {copy_ms / copy_cnt:.4f} ms, {copy_gbps:.0f} GB/s")
 
-    hot = [k for k in kernels if k != "k_grad"]
-    dominant = max(hot, key=lambda k: kernels[k]["ms_per_step"])
-    per_elem = ALGO_BYTES_PER_ELEM.get(dominant, 4.0)
+    # the dominant kernel of the path is its accumulate pass (12 B per worker and element; 8 B with the
+    # gradient fused in), in whichever form this workload runs it most
+    passes = [k for k in ("k_ef_filter", "k_ef_filter_split", "k_ef_filter_fused", "k_ef_randk") if k in kernels]
+    dominant = max(passes, key=lambda k: kernels[k]["ms_per_step"])
+    per_elem = ALGO_BYTES_PER_ELEM[dominant]
     algo_bytes = per_elem * elems
     achieved = algo_bytes / (kernels[dominant]["avg_ms"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

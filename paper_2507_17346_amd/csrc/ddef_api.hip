@@ -24,13 +24,13 @@ enum Slot {
     SL_GRAD = 0, SL_EF_FILTER, SL_EF_FILTER_FUSED, SL_RANDK_MARK, SL_RANDK_BIN, SL_RANDK_FILL, SL_EF_RANDK, SL_TAB_SUM, SL_TAB_DECIDE, SL_TAB_ORDER, SL_SEL_BEGIN_ROWS,
     SL_DIGIT_HIST, SL_DIGIT_PICK, SL_CHUNK_COUNT, SL_CHUNK_SCAN, SL_CHUNK_EMIT, SL_QUANTIZE4, SL_SAMPLE, SL_FILL,
     SL_MSG_OFFSETS, SL_AGGREGATE_TILES, SL_AGGREGATE_APPLY, SL_ADVANCE, SL_APPLY, SL_COPY_PROBE, SL_OBJECTIVE,
-    SL_EF_FILTER_SPLIT, SL_RESTORE_SURE, SL_MESSAGE_MERGE, SL_COUNT
+    SL_EF_FILTER_SPLIT, SL_RESTORE_SURE, SL_MESSAGE_MERGE, SL_COMPOSED_REPEAT, SL_COUNT
 };
 const char* const kSlotNames[SL_COUNT] = {
     "k_grad", "k_ef_filter", "k_ef_filter_fused", "k_randk_mark", "k_randk_bin", "k_randk_fill", "k_ef_randk", "k_tab_sum", "k_tab_decide", "k_tab_order",
     "k_sel_begin_rows", "k_digit_hist", "k_digit_pick", "k_chunk_count", "k_chunk_scan", "k_chunk_emit", "k_quantize4",
     "k_sample", "k_fill_f4", "k_msg_offsets", "k_aggregate_tiles", "k_aggregate_apply_tiles", "k_advance", "k_apply", "k_copy_f4", "k_objective",
-    "k_ef_filter_split", "k_restore_sure", "k_message_merge"};
+    "k_ef_filter_split", "k_restore_sure", "k_message_merge", "composed_repeat_pass"};
 
 struct ProfRecord { int slot; hipEvent_t start, stop; };
 
@@ -411,7 +411,7 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k, const SelState* gate = nullptr) 
     const bool binned = k >= ((uint64_t)1 << 20) && regions <= 2048u && regions * bucket_cap <= 2u * c->cap &&
                         bucket_cap < 0xffffffffull;
     if (!binned) {
-        LAUNCH(c, SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
+        LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_RANDK_MARK, k_randk_mark, dim3(blocks_for(c, (k + 255u) / 256u, n, 8), n), dim3(256),
                c->bitmap, bitmap_ld, (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32),
                (uint32_t)c->t, (uint32_t)(c->t >> 32), gate);
         return DDEF_OK;
@@ -424,11 +424,11 @@ int enqueue_randk_mark(ddef_ctx* c, uint64_t k, const SelState* gate = nullptr) 
         c->region_count = counts;
     }
     uint32_t* bucket = reinterpret_cast<uint32_t*>(c->cand);
-    LAUNCH(c, SL_RANDK_BIN, k_randk_bin, dim3(blocks_for(c, (k + 8191u) / 8192u, n, 2), n), dim3(1024), bucket,
+    LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_RANDK_BIN, k_randk_bin, dim3(blocks_for(c, (k + 8191u) / 8192u, n, 2), n), dim3(1024), bucket,
            2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
            (uint32_t)c->d, (uint32_t)k, (uint32_t)c->seed, (uint32_t)(c->seed >> 32), (uint32_t)c->t,
            (uint32_t)(c->t >> 32), gate);
-    LAUNCH(c, SL_RANDK_FILL, k_randk_fill, dim3((uint32_t)regions, n), dim3(1024), (const uint32_t*)bucket,
+    LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_RANDK_FILL, k_randk_fill, dim3((uint32_t)regions, n), dim3(1024), (const uint32_t*)bucket,
            2u * c->cap, (uint32_t)bucket_cap, c->region_count, region_bits, (uint32_t)regions, c->bitmap, bitmap_ld,
            (uint32_t)c->d, gate);
     return DDEF_OK;
@@ -935,12 +935,13 @@ int ddef_ef_compress(ddef_ctx* c, double delta, float lr) {
             int rcm = enqueue_randk_mark(c, k1, gate);
             if (rcm) return rcm;
             const uint32_t gx = gate ? std::min<uint32_t>(c->nwc, (uint32_t)c->cus * 32u) : c->nwc;
-            LAUNCH(c, SL_EF_RANDK, k_ef_randk, dim3(gx, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
+            // (the repeat pass's launches are timed under a slot of their own: they return at once as a rule)
+            LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_EF_RANDK, k_ef_randk, dim3(gx, n), dim3(64), c->e, c->g, c->ld, (uint32_t)c->d, lr, 0,
                    accumulate, with_bound ? (const uint32_t*)bound : (const uint32_t*)nullptr, c->bitmap, bitmap_ld,
                    c->cand, c->cap, cand_count, overflow, c->tab, c->nwc, c->filt + 4 * n, gate);
-            LAUNCH(c, SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
+            LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_TAB_SUM, k_tab_sum, dim3(c->nspans, n), dim3(1024), (const uint2*)c->tab, c->nwc,
                    c->span_sum, c->nspans, gate);
-            LAUNCH(c, SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
+            LAUNCH(c, gate ? SL_COMPOSED_REPEAT : SL_TAB_DECIDE, k_tab_decide_composed, dim3(n), dim3(256), c->span_sum, c->nspans, overflow,
                    (uint32_t)k1, (uint32_t)k, n, with_bound ? 0 : 1, c->sel, cand_total, cand_count, c->hist,
                    stat_full, gate ? 1 : 0);
             return DDEF_OK;

@@ -335,8 +335,31 @@ static void static_entry_point() {
     CHECK(ddef_ef_compress_static(ep, gp, ld, 0, 2, 0.01, 0.05f, idx.data(), val.data(), 200, nullptr) == DDEF_EINVAL);
 }
 
+// the buffers of the sure / band split of dense messages (records, run table, slot counters) and the
+// canonical-message buffers of the getter, each allocation failing in turn
+static void dense_split_setup_failures() {
+    for (long at = 0; at < 8; ++at) {
+        ddef_ctx* c = nullptr;
+        CHECK(ddef_init(70001, 2, 0, &c) == DDEF_OK);
+        set_problem(c, 70001);
+        CHECK(ddef_grad(c) == DDEF_OK);
+        fake_hip::state().fail_malloc_in = at;
+        const int rc = ddef_ef_compress(c, 0.3, 0.05f);
+        const bool fired = fake_hip::state().fail_malloc_in == -1;
+        fake_hip::state().fail_malloc_in = -1;
+        if (fired) { CHECK(rc == DDEF_ENOMEM); CHECK(ddef_ef_compress(c, 0.3, 0.05f) == DDEF_OK); }
+        else CHECK(rc == DDEF_OK);
+        CHECK(ddef_aggregate(c) == DDEF_OK);
+        CHECK(ddef_apply_delayed(c, 0.05f) == DDEF_OK);
+        read_everything(c, 70001, 2);
+        CHECK(step(c, 0.3, 0.05f) == DDEF_OK);
+        CHECK(ddef_destroy(c) == DDEF_OK);
+    }
+}
+
 int main() {
     deco_calls();
+    dense_split_setup_failures();
     static_entry_point();
     plain_runs();
     call_order_and_arguments();
