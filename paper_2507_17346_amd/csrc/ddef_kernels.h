@@ -17,7 +17,8 @@ constexpr uint32_t kTile = 4096;      // coordinates per block of the tile sum
 
 // Per-worker selection state in device memory.
 struct SelState {
-    uint32_t active;      // 1: search the whole row; 0: search the filtered candidates; 2: invariant broken
+    uint32_t active;      // 1: search the whole row; 0: search the filtered candidates; 2: invariant broken;
+                          // 3: composed compressor, too few kept entries passed the bound: repeat the pass without it
     uint32_t prefix[2];   // magnitude pattern built so far for rank 0 (k) and rank 1 (filter)
     uint32_t krem[2];     // rank still to find inside the current prefix group (1-based)
     uint32_t T, r;        // threshold pattern and how many entries equal to T are sent

@@ -881,7 +881,9 @@ __global__ __launch_bounds__(256) void k_sel_begin_rows(SelState* __restrict__ s
 // largest recorded entries starts.  exact = 1: every kept coordinate was recorded, the runs must
 // hold exactly k1 entries (active = 2 flags a slot overflow).  exact = 0: only the kept entries
 // above a bound were recorded, which is enough when there are at least k of them; otherwise
-// active = 3 asks the host to run the pass again without the bound.  Leaves the slot counters
+// active = 3 marks the worker for the repeat pass (recording every kept entry, no bound), whose
+// kernels are enqueued every time and run only for such workers (gated = 1: this kernel, too, then
+// looks at those workers only and leaves the others' verdict alone).  Leaves the slot counters
 // and the overflow flag cleared.
 __global__ __launch_bounds__(256) void k_tab_decide_composed(uint32_t* __restrict__ span_sum, uint32_t nspans,
                                                              uint32_t* __restrict__ overflow, uint32_t k1,
