@@ -426,7 +426,12 @@ def main():
             "elements_per_s": elems / (path_ms * 1e-3),
             "floor_bytes_per_step": floor_bytes,
             "floor_GBps": floor_bytes / (path_ms * 1e-3) / 1e9,
-            "floor_frac_of_peak": floor_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            "floor_frac_of_peak": floor_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            # the same rate over ddef_ef_compress + ddef_aggregate alone; on the GPU the sum of the
+            # messages is formed inside ddef_apply_delayed (fused with the model update), so this
+            # figure leaves the summation out as well and is not a rate of the whole server side
+            "elements_per_s_without_apply_delayed":
+                elems / ((gpu_ms["ef_compress"] + gpu_ms["aggregate"]) * 1e-3)}
     # bytes the hardware counters saw for all kernels of the path in one iteration (default
     # configuration of this workload only), and the rate and share of the peak they give
     counted = None
