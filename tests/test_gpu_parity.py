@@ -564,7 +564,8 @@ def test_checkpoint_and_resume_continue_bit_for_bit(ddef, oracle_mod, tau, graph
 
 # --- dense messages: candidates sure to be sent bypass the selection ----------------------------
 @pytest.mark.parametrize("mode", [1, 2, 3, 4, 0])
-@pytest.mark.parametrize("d,n,delta", [(300_017, 3, 0.1), (70_001, 2, 0.3), (1_200_003, 4, 0.04)])
+@pytest.mark.parametrize("d,n,delta", [(300_017, 3, 0.1), (70_001, 2, 0.3), (1_200_003, 4, 0.04),
+                                       (40_009, 37, 0.07)])     # more workers than one round of run descriptors
 def test_dense_messages_sure_and_band_split(ddef, oracle_mod, mode, d, n, delta):
     """Messages dense enough for the filter bound to come from a sample of p in every iteration
     (k/d > 1/32): candidates a margin above the expected threshold are recorded once and go to the

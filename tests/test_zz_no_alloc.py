@@ -122,8 +122,10 @@ def test_static_entry_point_matches_ef_compress_twice_in_a_row():
     ddef.load()
     hip = Hip()
     # first call: several tiles and chunks, a ragged tail, ties at the threshold; second: smaller
-    # in d, n and k, straight after it (on a stream of the caller's own); third: a handful of entries
-    cases = [(11, 3, 300_017, 0.06, True, 2), (12, 2, 70_001, 0.003, False, 0), (13, 1, 5, 0.4, False, 1)]
+    # in d, n and k, straight after it (on a stream of the caller's own); third: a handful of entries;
+    # fourth: as many workers as the work memory holds, over what the smaller calls left in it
+    cases = [(11, 3, 300_017, 0.06, True, 2), (12, 2, 70_001, 0.003, False, 0), (13, 1, 5, 0.4, False, 1),
+             (14, 64, 9_001, 0.02, True, 1)]
     for seed, n, d, delta, ties, pad in cases:
         e, g = make_inputs(seed, n, d, ties)
         lr = 0.05
