@@ -235,6 +235,8 @@ def main():
     ap.add_argument("--dense-split", type=int, default=1,
                     help="0: dense messages go through the selection whole (study runs; default 1: candidates "
                          "sure to be sent bypass it)")
+    ap.add_argument("--full-select", type=int, default=0,
+                    help="1: every selection searches its whole row (no candidate filter; study runs only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="launch the plain copy yardstick this many times (for hardware byte counters)")
@@ -281,6 +283,8 @@ def main():
     ctx.set_option(binding.OPT_FUSE_GRAD, 1 if args.fuse_grad else 0)
     ctx.set_option(binding.OPT_GRAPH, 1 if args.graph else 0)
     ctx.set_option(binding.OPT_DENSE_SPLIT, 1 if args.dense_split else 0)
+    if args.full_select:
+        ctx.set_option(binding.OPT_FORCE_FULL_SELECT, 1)
 
     state = {"tau": None}
 
@@ -436,7 +440,7 @@ def main():
     # configuration of this workload only), and the rate and share of the peak they give
     counted = None
     if args.d is None and args.delta is None and args.compressor == "topk" and not (
-            args.fuse_grad or args.prefetch or args.queue_form):
+            args.fuse_grad or args.prefetch or args.queue_form or args.full_select):
         counted, _ = measured_traffic("k_ef_filter", w.name, key="path_traffic_bytes_per_step")
     if counted:
         path["measured_bytes_per_step"] = counted
@@ -451,7 +455,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(w, sched, lambda dl: round(sent_ratio(dl) * w.d)),
                    "d": w.d, "n": w.n, "k": round(sent_ratio(sched(ctx.t)[1]) * w.d), "tau": sched(ctx.t)[0],
-                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph), "dense_split": bool(args.dense_split),
+                   "compressor": args.compressor, **({"rand_ratio": args.rand_ratio} if args.compressor == "composed" else {}), **({"zeta": args.zeta} if args.zeta else {}), "prefetch_grad": bool(args.prefetch), "fuse_grad": bool(args.fuse_grad), "server_state": "queue" if args.queue_form else "ring", "hip_graph": bool(args.graph), "dense_split": bool(args.dense_split), **({"full_select": True} if args.full_select else {}),
                    "step": "grad + ef_compress + aggregate + apply_delayed, all workers"},
         "roofline": roofline,
         "grad": grad_info,
