@@ -22,19 +22,33 @@ CXXFLAGS = ["-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-fno-
 
 
 def build(force: bool = True) -> str:
+    if _prebuilt:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["g++", *CXXFLAGS, _SRC, "-o", _LIB])
     return _LIB
 
 
 _lib = None
+_prebuilt = False
+
+
+def use_library(path: str) -> None:
+    """Load this build of the oracle instead of oracle/libddef_oracle.so (before first use).
+    For the test that compiles copies of the source with mistakes planted in them and checks
+    that the pins notice."""
+    global _LIB, _prebuilt
+    if _lib is not None:
+        raise RuntimeError("the oracle library is already loaded")
+    _LIB, _prebuilt = path, True
 
 
 def lib():
     global _lib
     if _lib is not None:
         return _lib
-    build(force=False)
+    if not _prebuilt:
+        build(force=False)
     L = C.CDLL(_LIB)
     u32p, f32p, u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
     vp = C.c_void_p

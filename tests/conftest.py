@@ -15,5 +15,9 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def oracle_mod():
     import oracle
+    # (tests/test_pins_catch_planted_mistakes.py runs the pins against other builds of the oracle)
+    other = os.environ.get("DDEF_ORACLE_LIB")
+    if other:
+        oracle.use_library(other)
     oracle.build(force=False)
     return oracle

@@ -89,3 +89,24 @@ def test_theorem3_against_recurrence(oracle_mod, tau, delta, a, b, t_comp):
     # tau = 0: every iteration is compute, then transfer, then latency, in series
     if tau == 0:
         assert cf == pytest.approx(t_comp + b + delta * v_g / a, rel=1e-12)
+
+
+@pytest.mark.parametrize("delta,a,b,t_comp", [(1.0, 1e9, 0.1, 0.3), (0.02, 3e8, 0.25, 0.05), (0.5, 1e8, 0.0, 0.2)])
+def test_recurrence_in_the_cases_that_can_be_worked_by_hand(oracle_mod, delta, a, b, t_comp):
+    """Where the pipeline of Section 4.1 cannot overlap anything its completion time is a plain sum:
+    a single iteration computes, transfers and waits out the latency, whatever tau is; and with
+    tau = 0 every iteration waits for the one before it to arrive, so E iterations take E times
+    that (the latency of the last message included)."""
+    v_g = 32 * 11.7e6
+    serial = t_comp + delta * v_g / a + b
+    for tau in (0, 1, 5):
+        assert oracle_mod.t_avg_recurrence(tau, delta, v_g, a, b, t_comp, 1) == pytest.approx(serial, rel=1e-12)
+    for E in (2, 3, 50, 777):
+        assert oracle_mod.t_avg_recurrence(0, delta, v_g, a, b, t_comp, E) == pytest.approx(serial, rel=1e-12)
+    # tau = 1, two iterations, by hand: the second computation starts when the first ends (the
+    # message it would wait for dates from before the start), its transfer when both the first
+    # transfer and the second computation are over
+    xfer = delta * v_g / a
+    tm1 = t_comp + xfer
+    tm2 = xfer + max(tm1, 2 * t_comp)
+    assert oracle_mod.t_avg_recurrence(1, delta, v_g, a, b, t_comp, 2) == pytest.approx((tm2 + b) / 2, rel=1e-12)

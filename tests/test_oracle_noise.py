@@ -62,6 +62,20 @@ def test_unit_circle_matches_libm(oracle_mod):
         assert abs(s - math.sin(ang)) <= 3e-7, hex(w)
 
 
+def test_unit_circle_angles_sit_in_the_middle_of_their_steps(oracle_mod):
+    """The 2^24 angles are 2 pi (a + 1/2) / 2^24: none lies on an axis, and the set is its own mirror
+    image, a and 2^24 - 1 - a giving the same cosine and opposite sines bit for bit (the offset
+    inside the quadrant changes sign exactly).  The first angle is pi / 2^24, whose sine in fp32 is
+    the angle itself."""
+    c, s = oracle_mod.unit_circle_point(0)
+    assert s == float(np.float32(math.pi / 2.0 ** 24)) and c == 1.0
+    rng = np.random.default_rng(13)
+    for a in [0, 1, 0x1FFFFF, 0x200000, 0x3FFFFF, 0x400000, 0x7FFFFF, 0x800000] + [int(v) for v in rng.integers(0, 1 << 24, 3000)]:
+        c1, s1 = oracle_mod.unit_circle_point(a << 8)
+        c2, s2 = oracle_mod.unit_circle_point(((1 << 24) - 1 - a) << 8)
+        assert c1 == c2 and s1 == -s2 and s1 != 0.0 and c1 != 0.0, hex(a)
+
+
 def test_draws_are_box_muller_of_the_philox_words(oracle_mod):
     seed, t, worker = 0x1234567855AA33CC, (7 << 32) | 9, 3
     key = [seed & 0xFFFFFFFF, seed >> 32]

@@ -229,6 +229,47 @@ def test_startup_noop_steps_and_snapshot_ring(oracle_mod):
     assert np.array_equal(bits(o.get_grad(1)), bits(lam * (xs - xstar) + F32(w.noise_scale) * z))
 
 
+def test_gradient_does_not_depend_on_the_number_of_threads(oracle_mod):
+    """With more threads than workers the oracle's threads share each worker's coordinates in
+    ranges.  Every coordinate must still be computed, and computed as lambda (x - x*) + scale z
+    (Assumption 2) from the noise draws taken one by one."""
+    w, lam, xstar, x0 = small_problem(seed=21, d=1003, n=2, noise_kind=2, noise_scale=0.3)
+    want = None
+    for threads in (1, 2, 5, 7, 16):
+        o = oracle_mod.Oracle(w.d, w.n, 0, threads=threads)
+        o.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+        o.set_tau(0)
+        for i in range(w.n):
+            o.set_error(i, np.full(w.d, np.nan, dtype=F32))      # (the gradient does not read it)
+        o.grad()
+        got = [o.get_grad(i) for i in range(w.n)]
+        if want is None:
+            want = got
+            for i in range(w.n):
+                z = oracle_mod.noise_fill(w.seed, 0, i, 0, w.d, w.noise_kind)
+                assert np.array_equal(bits(got[i]), bits(lam * (x0 - xstar) + F32(w.noise_scale) * z))
+        for i in range(w.n):
+            assert np.array_equal(bits(got[i]), bits(want[i])), (threads, i)
+        o.close()
+
+
+def test_a_new_problem_starts_from_empty_error_buffers(oracle_mod):
+    """e_0 = 0 (Algorithm 1's initialisation): handing the problem over again restarts the run."""
+    w, lam, xstar, x0 = small_problem(seed=22, d=700, n=2)
+    o = make_oracle(oracle_mod, w, lam, xstar, x0, 1)
+    first = []
+    for _ in range(4):
+        o.step(0.05, 0.05)
+        first.append(o.get_model())
+    assert any(np.any(o.get_error(i) != 0) for i in range(w.n))
+    o.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
+    assert o.t == 0 and all(not np.any(o.get_error(i)) for i in range(w.n))
+    for t in range(4):
+        o.step(0.05, 0.05)
+        assert np.array_equal(bits(o.get_model()), bits(first[t])), t
+    o.close()
+
+
 def test_aggregate_sums_in_worker_order(oracle_mod):
     # three workers whose selected values do not add associatively in fp32
     d, n = 4, 3
