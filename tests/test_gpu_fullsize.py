@@ -76,32 +76,35 @@ def test_c3_full_size_bench_configuration(ddef, oracle_mod):
     assert used >= w.n                # at least the last iterations ran through the filter
 
 
-def test_c5_full_size_across_changes_of_tau_and_delta(ddef, oracle_mod):
+@pytest.mark.parametrize("periods", [range(0, 5), range(5, 10)], ids=["periods 0-4", "periods 5-9"])
+def test_c5_full_size_across_changes_of_tau_and_delta(ddef, oracle_mod, periods):
     """The adaptive workload at its real shape (d = 124e6, n = 16, ring of 17 snapshots) against the
-    oracle over all ten periods of its DeCo schedule, the first two real iterations of each: tau
-    rises (6 -> 9), falls (9 -> 2), reaches the ring's full depth (16) and moves on through 15, 16,
-    6, 10, 7, 14, while delta moves between 0.0006 and 0.036 -- sparse messages whose filter bound
-    follows the last thresholds, messages dense enough for a bound sampled in every iteration
+    oracle over all ten periods of its DeCo schedule, the first two real iterations of each, in two
+    runs of five periods (each from x_0, so that neither run is silent for minutes): tau rises
+    (6 -> 9), falls (9 -> 2), reaches the ring's full depth (16), goes to 15; and 16, 6, 10, 7, 14
+    in the second run, while delta moves between 0.0006 and 0.036 -- sparse messages whose filter
+    bound follows the last thresholds, messages dense enough for a bound sampled in every iteration
     (delta = 0.0044 ... 0.0105), and dense ones whose sure candidates bypass the selection
     (delta = 0.036 > 1/32).  Every change re-places the filter bound and changes the length of the
     messages."""
     w = workloads.get("C5")
     trace = workloads.network_trace(w)
-    plan = []
+    whole = []
     for p in range(len(trace.bandwidth_bps)):
         tau, delta = ddef.deco(trace.v_g_bits, trace.bandwidth_bps[p], trace.latency_s[p], trace.t_comp_s)
-        plan.append((int(np.clip(tau, *trace.tau_bounds)), float(np.clip(delta, *trace.delta_bounds))))
-    taus = [tau for tau, _ in plan]
-    assert len(plan) == 10 and taus[1] > taus[0] and taus[2] < taus[1] and max(taus) == w.tau_max
-    assert any(ddef.k_from_delta(delta, w.d) * 32 > w.d for _, delta in plan)
-    assert any(ddef.k_from_delta(delta, w.d) * w.n < 2 ** 23 for _, delta in plan)
+        whole.append((int(np.clip(tau, *trace.tau_bounds)), float(np.clip(delta, *trace.delta_bounds))))
+    taus = [tau for tau, _ in whole]
+    assert len(whole) == 10 and taus[1] > taus[0] and taus[2] < taus[1] and max(taus) == w.tau_max
+    assert any(ddef.k_from_delta(delta, w.d) * 32 > w.d for _, delta in whole)
+    assert any(ddef.k_from_delta(delta, w.d) * w.n < 2 ** 23 for _, delta in whole)
+    plan = [whole[p] for p in periods]
     lam, xstar, x0 = workloads.make_problem(w)
     g = ddef.Context(w.d, w.n, w.tau_max)
     o = oracle_mod.Oracle(w.d, w.n, w.tau_max, threads=w.n)
     for h in (g, o):
         h.set_problem(lam, xstar, x0, w.seed, w.noise_kind, w.noise_scale)
     t = 0
-    for period, (tau, delta) in enumerate(plan):
+    for period, (tau, delta) in zip(periods, plan):
         real = 0
         while real < 2:
             for h in (g, o):
