@@ -31,7 +31,8 @@
  *     for it.  A context is not thread-safe;
  *   - all arithmetic of the method is IEEE fp32 with every operation rounded separately (no
  *     fused multiply-add; the fused steps inside the noise generator are part of its
- *     definition), indices are uint32, d < 2^32.
+ *     definition), indices are uint32, d < 2^32 - 8192 (so that rounding a length up to whole
+ *     groups, chunks or tiles never leaves 32 bits).
  */
 #ifndef DDEF_H
 #define DDEF_H
@@ -62,7 +63,7 @@ typedef struct ddef_ctx ddef_ctx;
 
 /* Problem statement of Algorithm 1: x in R^d, n workers, staleness at most tau_max.
  * Allocates e[n][d] = 0, g[n][d], the snapshot ring [tau_max+1][d], U[d] and work buffers
- * on the current device; tau starts at tau_max.  d in [1, 2^32), n >= 1, tau_max <= 4096.
+ * on the current device; tau starts at tau_max.  d in [1, 2^32 - 8192), n in [1, 65535], tau_max <= 4096.
  * On failure *out is NULL.  ENOMEM when the device cannot hold the state. */
 int ddef_init(uint64_t d, uint32_t n, uint32_t tau_max, ddef_ctx** out);
 

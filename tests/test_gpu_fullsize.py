@@ -241,24 +241,33 @@ def test_c4_full_size_properties_and_samples(ddef, oracle_mod):
     c4_problem.cache_clear()
 
 
-def test_coordinates_beyond_2_to_31(ddef, oracle_mod):
-    """One worker with d = 3e9 + 11: indices above 2^31, ragged last quad.  Properties of the
-    selection plus gradients / error-feedback values on sampled coordinates (the oracle's noise is
-    evaluated one coordinate at a time)."""
-    d, n, delta, lr, seed = 3_000_000_011, 1, 1e-4, 0.05, 77
+def test_the_longest_vector_the_library_takes(ddef, oracle_mod):
+    """One worker with d = 2^32 - 8193, the largest length ddef_init accepts: indices up to 2^32 - 8194
+    (far above 2^31), an odd length with a ragged last quad, group, chunk and tile.  Properties of
+    the selection plus gradients / error-feedback values on sampled coordinates (the oracle's noise
+    is evaluated one coordinate at a time).  The problem vectors are a random block of 2^26 entries
+    laid end to end at shifting offsets (the noise differs in every coordinate)."""
+    d, n, delta, lr, seed = 2 ** 32 - 8193, 1, 1e-4, 0.05, 77
+    with pytest.raises(ddef.DdefError):
+        ddef.Context(d + 1, n, 0)                       # one more is rejected before anything is allocated
     rng = np.random.default_rng(5)
+    block = 1 << 26
+    base = ((10.0 ** rng.uniform(-3, 0, block)).astype(F32), rng.standard_normal(block, dtype=F32),
+            rng.standard_normal(block, dtype=F32))
     lam = np.empty(d, dtype=F32); xstar = np.empty(d, dtype=F32); x0 = np.empty(d, dtype=F32)
-    step = 1 << 26
-    for lo in range(0, d, step):
-        hi = min(d, lo + step)
-        lam[lo:hi] = (10.0 ** rng.uniform(-3, 0, hi - lo)).astype(F32)
-        xstar[lo:hi] = rng.standard_normal(hi - lo, dtype=F32)
-        x0[lo:hi] = rng.standard_normal(hi - lo, dtype=F32)
+    for piece, lo in enumerate(range(0, d, block)):
+        hi = min(d, lo + block)
+        shift = (piece * 1_000_003) % block
+        for out, src in zip((lam, xstar, x0), base):
+            first = min(hi - lo, block - shift)
+            out[lo:lo + first] = src[shift:shift + first]
+            out[lo + first:hi] = src[:hi - lo - first]
     c = ddef.Context(d, n, 0)
     c.set_problem(lam, xstar, x0, seed, 1, 0.05)
     c.set_tau(0)
     k = ddef.k_from_delta(delta, d)
-    sample = np.unique(np.concatenate([rng.integers(0, d, 3000), [0, d - 1, 2 ** 31 - 1, 2 ** 31, 2 ** 31 + 1]]))
+    sample = np.unique(np.concatenate([rng.integers(0, d, 3000), rng.integers(d - 10000, d, 50),
+                                       [0, d - 1, d - 2, d - 3, d - 4, d - 257, d - 4097, 2 ** 31 - 1, 2 ** 31, 2 ** 31 + 1]]))
     e_prev = np.zeros(len(sample), dtype=F32)
     x_cur = x0
     for t in range(5):
@@ -285,6 +294,27 @@ def test_coordinates_beyond_2_to_31(ddef, oracle_mod):
         c.apply_delayed(lr)
         x_cur = c.get_model()
     assert c.full_select_count() < 5          # the candidate filter carried the later selections
+    # one iteration of Random-k at this length (k = 4.3e6 kept coordinates, sorted into regions of
+    # 2^21 coordinates before their bits are set): the oracle's subset, the accumulated values there
+    del x_cur
+    c.set_compressor(1)
+    k_r = ddef.k_from_delta(1e-3, d)
+    e_before = c.get_error(0)
+    c.grad()
+    grad = c.get_grad(0)
+    c.ef_compress(1e-3, lr)
+    idx, val = c.get_message(0)
+    assert np.array_equal(idx, oracle_mod.randk_indices(seed, 5, 0, d, k_r))
+    some = np.concatenate([np.arange(0, k_r, 997), [k_r - 1]])
+    assert np.array_equal(bits(val[some]), bits(e_before[idx[some]] + F32(lr) * grad[idx[some]]))
+    p = e_before[sample] + F32(lr) * grad[sample]
+    del e_before, grad
+    e_new = c.get_error(0)
+    unsent = ~np.isin(sample, idx)
+    assert np.all(bits(e_new[idx]) == 0) and np.array_equal(bits(e_new[sample][unsent]), bits(p[unsent]))
+    del e_new
+    c.aggregate()
+    c.apply_delayed(lr)
     c.close()
 
 
